@@ -1,0 +1,175 @@
+/*
+ * sfc.h - C ABI of the one-GPU sparse-embedding hot path of ScaleFreeCTR
+ * (Virtual Sparse Id + MixCache + gather + gradient segment-sum + sparse
+ * Adagrad), implemented with HIP kernels for gfx950 (MI355X).
+ *
+ * One training step is four calls, in this order (Algorithm 1, lines 3-14,
+ * with the multi-GPU lines 7, 10 and 13 and the dense model of line 12 left to
+ * the caller):
+ *
+ *     sfc_prepare          lines 3-4   ids -> global_id / virtual_id, hit / miss / victims, slots
+ *     sfc_fetch_misses     lines 5-6   victims cache->Host, missed rows Host->cache (side stream)
+ *     sfc_lookup           lines 9,11  [bags, dim] model input from the cached rows
+ *     sfc_backward_update  line 14     segment-sum of the gradients per virtual id + Adagrad
+ *
+ * Conventions
+ *   - Every function returns 0 (SFC_OK) or a negative SFC_E* code; nothing throws or aborts.
+ *     sfc_last_error() gives a text for the most recent failure on the calling thread.
+ *   - Pointers named d_* are DEVICE memory owned by the caller; pointers named h_* are HOST
+ *     memory owned by the caller.  The library owns the cache rows, the accumulators, the
+ *     cache index and all scratch.  Buffers handed to sfc_prepare are used by the later calls
+ *     of the same step and must stay alive and unmodified until sfc_backward_update (or the
+ *     next sfc_prepare) has completed on the stream.
+ *   - All work is enqueued on the streams given at creation and is asynchronous to the host,
+ *     except sfc_cache_create, sfc_flush, sfc_get_stats, sfc_cache_state and sfc_cache_destroy,
+ *     which synchronise.  No call allocates device memory after sfc_cache_create.
+ *   - One sfc_cache must be driven by one host thread at a time.
+ *   - Rows are fp32, row-major, dim floats each; dim must be a multiple of 4 and all row
+ *     buffers 16-byte aligned.
+ */
+#ifndef SFC_H
+#define SFC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SFC_OK 0
+#define SFC_EINVAL (-1)  /* bad argument: null pointer, size out of range, dim not a multiple of 4 */
+#define SFC_ESTATE (-2)  /* call out of order */
+#define SFC_EHIP (-3)    /* a HIP runtime call failed; see sfc_last_error() */
+#define SFC_ENOMEM (-4)  /* device or host allocation failed */
+#define SFC_ELIMIT (-5)  /* more steps than max_steps */
+
+#define SFC_POLICY_LRU_BATCH 0
+
+typedef struct sfc_cache sfc_cache; /* opaque */
+
+typedef struct {
+  int64_t capacity_rows;      /* C >= 0: row slots of the cache buffer (0 = every row bypasses) */
+  int32_t dim;                /* D: floats per row, multiple of 4, <= 1024 */
+  int32_t policy;             /* SFC_POLICY_LRU_BATCH */
+  int64_t max_ids_per_batch;  /* upper bound on n_ids of any step; sizes scratch and bypass rows */
+  int64_t max_bags_per_batch; /* upper bound on n_bags of any step */
+  int64_t host_rows;          /* V: rows of the Host table; valid ids are [0, V) */
+  float* h_weights;           /* [V, D] Host table, pinned and device-mapped (see sfc_host_alloc) */
+  float* h_acc;               /* [V, D] Adagrad accumulator of every row, same kind of memory */
+  float lr;                   /* Adagrad learning rate */
+  float eps;                  /* Adagrad epsilon, added outside the square root */
+  int32_t lookahead;          /* 0: rows of the batch being prepared are protected from eviction.
+                                 1: rows of the previous batch are protected as well. */
+  int32_t max_steps;          /* steps this cache may run (sizes the recency histogram); 0 = 1<<20 */
+  void* stream;               /* hipStream_t for prepare / lookup / backward_update */
+  void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */
+} sfc_config;
+
+typedef struct {
+  int64_t n_unique;   /* U: distinct ids of the batch (a null entry for out-of-range ids included) */
+  int64_t n_hit;      /* unique ids already resident */
+  int64_t n_miss;     /* unique ids fetched from Host (bypass rows included) */
+  int64_t n_evict;    /* resident rows written back to Host to make room */
+  int64_t n_bypass;   /* misses that found no slot and live in a transient row for this step */
+  int64_t n_invalid;  /* positions whose id was outside [0, V) */
+  int64_t h2d_bytes;  /* Host->cache bytes of this step (rows + accumulators) */
+  int64_t d2h_bytes;  /* cache->Host bytes of this step (victims + bypass rows) */
+} sfc_stats;
+
+/* Pinned, device-mapped Host memory suitable for h_weights / h_acc.  Returns NULL on failure. */
+void* sfc_host_alloc(int64_t bytes);
+void sfc_host_free(void* p);
+
+/*
+ * Create an empty cache (MixCache: "allocates a cache buffer in HBM ... which stores the working
+ * embedding parameters", Host-Manager section).  The manager state (id -> slot index, per-slot
+ * recency stamp) lives in HBM too.  Allocates all device memory the later calls use.
+ */
+int sfc_cache_create(const sfc_config* cfg, sfc_cache** out);
+void sfc_cache_destroy(sfc_cache* c);
+
+/*
+ * Step 1 (Algorithm 1 lines 3-4; Data-Loader section, Host-Manager section).
+ *  d_ids       [n_ids] int64 raw feature ids, row-major [batch, fields] or the concatenated bags.
+ *  d_offsets   NULL for one-hot input (then n_bags must equal n_ids), else [n_bags+1] int64 CSR
+ *              offsets with d_offsets[0] = 0 and d_offsets[n_bags] = n_ids, non-decreasing.
+ *  outputs (each sized for n_ids entries by the caller):
+ *  d_unique_ids  global_id: the distinct ids in order of first appearance; ids outside [0, V)
+ *                all collapse into one null entry with value -1.
+ *  d_inverse     virtual_id per position: d_unique_ids[d_inverse[p]] == d_ids[p] (or -1).
+ *  d_slot        per virtual id: cache slot in [0, C), or C + j for the j-th bypass row of this
+ *                step, or -1 for the null entry.  Slots of misses hold valid data only after
+ *                sfc_fetch_misses.
+ *  d_miss_vids   virtual ids that must be fetched from Host, ascending; n_miss entries.
+ * Hit / miss / victim counts stay on the device (sfc_get_stats reads them).
+ * Victims are chosen by batch-granular LRU: among resident rows not used by this batch (nor by
+ * the previous one when lookahead = 1), those whose last use is oldest, ties by lower slot; the
+ * i-th miss takes the i-th slot of (free + victim slots) in ascending slot order.
+ * Errors: SFC_EINVAL (null pointers, n_ids > max_ids_per_batch, n_bags > max_bags_per_batch,
+ * one-hot with n_bags != n_ids), SFC_ELIMIT, SFC_EHIP.  Malformed offsets are not detected.
+ */
+int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t* d_offsets,
+                int64_t n_bags, int64_t* d_unique_ids, int32_t* d_inverse, int32_t* d_slot,
+                int32_t* d_miss_vids);
+
+/*
+ * Step 2 (Algorithm 1 lines 5-6): on the side stream, after the prepare of this step, first
+ * write every victim row and accumulator back to the Host table, then copy every missed row and
+ * accumulator from the Host table into its slot.  The main stream is made to wait for both.
+ */
+int sfc_fetch_misses(sfc_cache* c);
+
+/*
+ * Step 3 (Algorithm 1 lines 9 and 11; GPU-Worker / Forward): d_out[b, :] = sum over the
+ * positions q of bag b of the cached row of d_ids[q]  (one row for one-hot input).  Rows of the
+ * null entry count as zeros.  d_out is [n_bags, D] fp32.  May be called more than once.
+ */
+int sfc_lookup(sfc_cache* c, float* d_out);
+
+/*
+ * GPU-Worker / Backward, first half: d_common_grad[v, :] = sum over positions q with
+ * d_inverse[q] == v of d_grad[bag(q), :] (the unsorted segment sum that turns Local Gradients
+ * into Local Common Gradients), accumulated in fp64 and rounded to fp32 once.
+ * d_grad is [n_bags, D]; d_common_grad is [n_unique, D], caller-sized for n_ids rows.
+ * Optional: a multi-GPU caller exchanges this matrix; sfc_backward_update does not need it.
+ */
+int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad);
+
+/*
+ * Step 4 (GPU-Worker / Backward; Algorithm 1 line 14): segment-sum d_grad [n_bags, D] per
+ * virtual id as above and apply one Adagrad update per unique row in the cache:
+ *     acc += g*g ;  w -= lr * g / (sqrt(acc) + eps)        (fp32, element-wise)
+ * Bypass rows are then written back to the Host table.  Ends the step.
+ */
+int sfc_backward_update(sfc_cache* c, const float* d_grad);
+
+/* Write every resident row and accumulator to the Host table and wait; the cache stays warm. */
+int sfc_flush(sfc_cache* c);
+
+/* Counters of the most recent sfc_prepare; waits for the streams. */
+int sfc_get_stats(sfc_cache* c, sfc_stats* h_out);
+
+/*
+ * Snapshot of the cache for inspection; waits for the streams.  Any pointer may be NULL.
+ *  h_slot_id [C] int64  resident id per slot, -1 = free
+ *  h_stamp   [C] int32  step number of the last batch that used the slot, 0 = never
+ *  h_rows    [C, D]     cached weights        h_acc [C, D] cached accumulators
+ */
+int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h_rows, float* h_acc);
+
+/*
+ * Per-call device timing.  When enabled, hipEvents bracket the kernels of each of the four step
+ * calls on the stream they run on.  sfc_profile_read waits for the streams and returns, for
+ * which = 0..3 (prepare, fetch_misses, lookup, backward_update), the summed milliseconds and the
+ * number of calls since the last read.
+ */
+int sfc_profile_enable(sfc_cache* c, int32_t on);
+int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);
+
+const char* sfc_strerror(int code);
+const char* sfc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SFC_H */

@@ -1,0 +1,297 @@
+"""Python binding of libsfc.so (C ABI in include/sfc.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch supplies device memory and
+streams.  There is no CPU fallback: importing works anywhere the shared library loads, but
+every call needs a GPU, and a missing library is an error, not a reason to compute elsewhere.
+
+The module-level functions carry the names of the C entry points and take torch tensors (device
+tensors for d_* arguments).  `Cache` is a convenience holder for one cache, its output buffers
+and its streams.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsfc.so")
+
+SFC_OK, SFC_EINVAL, SFC_ESTATE, SFC_EHIP, SFC_ENOMEM, SFC_ELIMIT = 0, -1, -2, -3, -4, -5
+SFC_POLICY_LRU_BATCH = 0
+
+EXPORTS = [
+    "sfc_host_alloc", "sfc_host_free", "sfc_cache_create", "sfc_cache_destroy", "sfc_prepare",
+    "sfc_fetch_misses", "sfc_lookup", "sfc_segment_sum", "sfc_backward_update", "sfc_flush",
+    "sfc_get_stats", "sfc_cache_state", "sfc_profile_enable", "sfc_profile_read", "sfc_strerror",
+    "sfc_last_error",
+]
+
+
+class SfcError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("sfc error %d (%s): %s" % (code, _strerror(code), msg))
+        self.code = code
+
+
+class sfc_config(ctypes.Structure):
+    _fields_ = [
+        ("capacity_rows", ctypes.c_int64), ("dim", ctypes.c_int32), ("policy", ctypes.c_int32),
+        ("max_ids_per_batch", ctypes.c_int64), ("max_bags_per_batch", ctypes.c_int64),
+        ("host_rows", ctypes.c_int64), ("h_weights", ctypes.c_void_p), ("h_acc", ctypes.c_void_p),
+        ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("lookahead", ctypes.c_int32),
+        ("max_steps", ctypes.c_int32), ("stream", ctypes.c_void_p), ("side_stream", ctypes.c_void_p),
+    ]
+
+
+class sfc_stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in
+                ("n_unique", "n_hit", "n_miss", "n_evict", "n_bypass", "n_invalid", "h2d_bytes",
+                 "d2h_bytes")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libsfc.so is not built (%s); run `python paper_2104_08542_amd/build.py` or "
+            "__graft_entry__.build(). There is no fallback path." % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int
+    lib.sfc_host_alloc.restype, lib.sfc_host_alloc.argtypes = vp, [i64]
+    lib.sfc_host_free.restype, lib.sfc_host_free.argtypes = None, [vp]
+    lib.sfc_cache_create.restype = ci
+    lib.sfc_cache_create.argtypes = [ctypes.POINTER(sfc_config), ctypes.POINTER(vp)]
+    lib.sfc_cache_destroy.restype, lib.sfc_cache_destroy.argtypes = None, [vp]
+    lib.sfc_prepare.restype, lib.sfc_prepare.argtypes = ci, [vp, vp, i64, vp, i64, vp, vp, vp, vp]
+    lib.sfc_fetch_misses.restype, lib.sfc_fetch_misses.argtypes = ci, [vp]
+    lib.sfc_lookup.restype, lib.sfc_lookup.argtypes = ci, [vp, vp]
+    lib.sfc_segment_sum.restype, lib.sfc_segment_sum.argtypes = ci, [vp, vp, vp]
+    lib.sfc_backward_update.restype, lib.sfc_backward_update.argtypes = ci, [vp, vp]
+    lib.sfc_flush.restype, lib.sfc_flush.argtypes = ci, [vp]
+    lib.sfc_get_stats.restype, lib.sfc_get_stats.argtypes = ci, [vp, ctypes.POINTER(sfc_stats)]
+    lib.sfc_cache_state.restype, lib.sfc_cache_state.argtypes = ci, [vp, vp, vp, vp, vp]
+    lib.sfc_profile_enable.restype, lib.sfc_profile_enable.argtypes = ci, [vp, i32]
+    lib.sfc_profile_read.restype = ci
+    lib.sfc_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.sfc_strerror.restype, lib.sfc_strerror.argtypes = ctypes.c_char_p, [ci]
+    lib.sfc_last_error.restype, lib.sfc_last_error.argtypes = ctypes.c_char_p, []
+    return lib
+
+
+_lib = _load()
+
+
+def _strerror(code):
+    return _lib.sfc_strerror(code).decode()
+
+
+def _check(rc):
+    if rc != SFC_OK:
+        raise SfcError(rc, _lib.sfc_last_error().decode())
+
+
+def _dptr(t: Optional[torch.Tensor], dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+# ------------------------------------------------------------------ C entry points, same names
+
+def sfc_host_alloc(nbytes: int) -> int:
+    p = _lib.sfc_host_alloc(int(nbytes))
+    if not p:
+        raise SfcError(SFC_ENOMEM, "sfc_host_alloc(%d) failed" % nbytes)
+    return p
+
+
+def sfc_host_free(ptr: int) -> None:
+    _lib.sfc_host_free(ctypes.c_void_p(ptr))
+
+
+def sfc_cache_create(cfg: sfc_config) -> int:
+    h = ctypes.c_void_p()
+    _check(_lib.sfc_cache_create(ctypes.byref(cfg), ctypes.byref(h)))
+    return h.value
+
+
+def sfc_cache_destroy(h: int) -> None:
+    _lib.sfc_cache_destroy(ctypes.c_void_p(h))
+
+
+def sfc_prepare(h, d_ids, n_ids, d_offsets, n_bags, d_unique_ids, d_inverse, d_slot, d_miss_vids):
+    _check(_lib.sfc_prepare(ctypes.c_void_p(h), _dptr(d_ids, torch.int64), int(n_ids),
+                            _dptr(d_offsets, torch.int64), int(n_bags),
+                            _dptr(d_unique_ids, torch.int64), _dptr(d_inverse, torch.int32),
+                            _dptr(d_slot, torch.int32), _dptr(d_miss_vids, torch.int32)))
+
+
+def sfc_fetch_misses(h):
+    _check(_lib.sfc_fetch_misses(ctypes.c_void_p(h)))
+
+
+def sfc_lookup(h, d_out):
+    _check(_lib.sfc_lookup(ctypes.c_void_p(h), _dptr(d_out, torch.float32)))
+
+
+def sfc_segment_sum(h, d_grad, d_common_grad):
+    _check(_lib.sfc_segment_sum(ctypes.c_void_p(h), _dptr(d_grad, torch.float32),
+                                _dptr(d_common_grad, torch.float32)))
+
+
+def sfc_backward_update(h, d_grad):
+    _check(_lib.sfc_backward_update(ctypes.c_void_p(h), _dptr(d_grad, torch.float32)))
+
+
+def sfc_flush(h):
+    _check(_lib.sfc_flush(ctypes.c_void_p(h)))
+
+
+def sfc_get_stats(h) -> dict:
+    st = sfc_stats()
+    _check(_lib.sfc_get_stats(ctypes.c_void_p(h), ctypes.byref(st)))
+    return {k: int(getattr(st, k)) for k, _ in sfc_stats._fields_}
+
+
+def sfc_cache_state(h, capacity_rows, dim, rows=False):
+    """(slot_id[C] int64, stamp[C] int32[, rows[C,D], acc[C,D]]) as numpy arrays."""
+    sid = np.empty(capacity_rows, np.int64)
+    stp = np.empty(capacity_rows, np.int32)
+    w = np.empty((capacity_rows, dim), np.float32) if rows else None
+    a = np.empty((capacity_rows, dim), np.float32) if rows else None
+    p = lambda x: None if x is None else x.ctypes.data_as(ctypes.c_void_p)
+    _check(_lib.sfc_cache_state(ctypes.c_void_p(h), p(sid), p(stp), p(w), p(a)))
+    return (sid, stp, w, a) if rows else (sid, stp)
+
+
+def sfc_profile_enable(h, on: bool):
+    _check(_lib.sfc_profile_enable(ctypes.c_void_p(h), 1 if on else 0))
+
+
+PROFILE_CALLS = ("prepare", "fetch_misses", "lookup", "backward_update")
+
+
+def sfc_profile_read(h) -> dict:
+    out = {}
+    for i, name in enumerate(PROFILE_CALLS):
+        ms, n = ctypes.c_double(), ctypes.c_int64()
+        _check(_lib.sfc_profile_read(ctypes.c_void_p(h), i, ctypes.byref(ms), ctypes.byref(n)))
+        out[name] = (ms.value, n.value)
+    return out
+
+
+# ------------------------------------------------------------------ conveniences
+
+class HostTable:
+    """[V, D] fp32 weights and accumulators in pinned, device-mapped host memory."""
+
+    def __init__(self, rows: int, dim: int):
+        self.rows, self.dim = int(rows), int(dim)
+        nbytes = self.rows * self.dim * 4
+        self._pw = sfc_host_alloc(nbytes)
+        try:
+            self._pa = sfc_host_alloc(nbytes)
+        except SfcError:
+            sfc_host_free(self._pw)
+            raise
+        mk = lambda p: np.ctypeslib.as_array((ctypes.c_float * (self.rows * self.dim)).from_address(p)
+                                             ).reshape(self.rows, self.dim)
+        self.w, self.acc = mk(self._pw), mk(self._pa)      # numpy views of the pinned memory
+        self.w_t, self.acc_t = torch.from_numpy(self.w), torch.from_numpy(self.acc)
+
+    def free(self):
+        if self._pw:
+            self.w = self.acc = self.w_t = self.acc_t = None
+            sfc_host_free(self._pw)
+            sfc_host_free(self._pa)
+            self._pw = self._pa = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Cache:
+    """One sfc_cache with its output buffers; methods mirror the C calls of a step."""
+
+    def __init__(self, table: HostTable, capacity_rows: int, max_ids: int, max_bags: Optional[int] = None,
+                 lr=0.01, eps=1e-8, lookahead=0, max_steps=0, device="cuda:0", side_stream=True):
+        self.table, self.C, self.D = table, int(capacity_rows), table.dim
+        self.device = torch.device(device)
+        self.max_ids = int(max_ids)
+        self.max_bags = int(max_bags if max_bags is not None else max_ids)
+        with torch.cuda.device(self.device):
+            self.stream = torch.cuda.current_stream()
+            self.side = torch.cuda.Stream() if side_stream else self.stream
+            cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH, self.max_ids, self.max_bags,
+                             table.rows, table._pw, table._pa, lr, eps, lookahead, max_steps,
+                             self.stream.cuda_stream, self.side.cuda_stream)
+            self.h = sfc_cache_create(cfg)
+            n = max(self.max_ids, 1)
+            self.unique_ids = torch.empty(n, dtype=torch.int64, device=self.device)
+            self.inverse = torch.empty(n, dtype=torch.int32, device=self.device)
+            self.slot = torch.empty(n, dtype=torch.int32, device=self.device)
+            self.miss_vids = torch.empty(n, dtype=torch.int32, device=self.device)
+        self.n_ids = self.n_bags = 0
+        self._keep = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            sfc_cache_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def prepare(self, ids: torch.Tensor, offsets: Optional[torch.Tensor] = None):
+        self.n_ids = ids.numel()
+        self.n_bags = self.n_ids if offsets is None else offsets.numel() - 1
+        self._keep = (ids, offsets)
+        sfc_prepare(self.h, ids, self.n_ids, offsets, self.n_bags, self.unique_ids, self.inverse,
+                    self.slot, self.miss_vids)
+
+    def fetch_misses(self):
+        sfc_fetch_misses(self.h)
+
+    def lookup(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty(self.n_bags, self.D, dtype=torch.float32, device=self.device)
+        sfc_lookup(self.h, out)
+        return out
+
+    def segment_sum(self, grad: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty(max(self.n_ids, 1), self.D, dtype=torch.float32, device=self.device)
+        sfc_segment_sum(self.h, grad, out)
+        return out
+
+    def backward_update(self, grad: torch.Tensor):
+        sfc_backward_update(self.h, grad)
+
+    def flush(self):
+        sfc_flush(self.h)
+
+    def stats(self) -> dict:
+        return sfc_get_stats(self.h)
+
+    def state(self, rows=False):
+        return sfc_cache_state(self.h, self.C, self.D, rows)
+
+    def step(self, ids, grad, offsets=None, out=None):
+        self.prepare(ids, offsets)
+        self.fetch_misses()
+        out = self.lookup(out)
+        self.backward_update(grad)
+        return out

@@ -1,0 +1,491 @@
+// Host side of the C ABI declared in include/sfc.h: owns the device memory of one cache and
+// enqueues the kernels of each step call on the caller's streams.  No call after
+// sfc_cache_create allocates device memory or waits for the device, except the ones the header
+// documents as synchronising.
+#include "../../include/sfc.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "sfc_prepare_kernels.h"
+#include "sfc_row_kernels.h"
+
+using namespace sfc;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* what, hipError_t e = hipSuccess) {
+  char buf[512];
+  if (e != hipSuccess) snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+  else snprintf(buf, sizeof buf, "%s", what);
+  g_err = buf;
+  return code;
+}
+
+#define HIPCHK(call)                                            \
+  do {                                                          \
+    hipError_t e_ = (call);                                     \
+    if (e_ != hipSuccess) return fail(SFC_EHIP, #call, e_);     \
+  } while (0)
+
+enum State { IDLE = 0, PREPARED = 1, FETCHED = 2 };
+enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_N = 4 };
+
+struct EventPair { hipEvent_t a, b; };
+
+}  // namespace
+
+struct sfc_cache {
+  sfc_config cfg{};
+  int64_t C = 0, V = 0, max_ids = 0, max_bags = 0;
+  int D = 0, d4 = 0;
+  hipStream_t st = nullptr, side = nullptr;
+  hipEvent_t ev_prepared = nullptr, ev_fetched = nullptr;
+  // device memory
+  float *cw = nullptr, *ca = nullptr;           // [(C + max_ids), D]
+  int64_t* slot_id = nullptr;                   // [C]
+  int* stamp = nullptr;                         // [C]
+  IdxEntry* index = nullptr; uint32_t hi = 0;   // cache index
+  int* hist = nullptr; int hist_len = 0;        // [max_steps + 2]
+  int64_t* ukeys = nullptr; int* uminpos = nullptr; int* uvid = nullptr;  // batch table [2*max_ids]
+  int* hslot = nullptr;                         // [max_ids]
+  int* vid_hslot = nullptr;                     // [max_ids]
+  int* blk_cnt = nullptr;                       // [max_ids / kPosChunk + 1]
+  int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
+  int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
+  int* victim_slot = nullptr; int64_t* victim_id = nullptr;  // [max_ids]
+  double* g64 = nullptr;                        // [max_ids, D] fp64 gradient scratch, zero at rest
+  Ctr* ctr = nullptr;
+  float *d_hw = nullptr, *d_ha = nullptr;       // device view of the Host table
+  std::vector<void*> allocs;
+  // step state
+  int state = IDLE;
+  int t = 0;
+  int64_t n_ids = 0, n_bags = 0;
+  const int64_t* d_offsets = nullptr;
+  int64_t* d_unique = nullptr; int32_t* d_inverse = nullptr; int32_t* d_slot = nullptr;
+  int32_t* d_miss = nullptr;
+  // profiling
+  bool prof = false;
+  std::vector<EventPair> pending[P_N], spare;
+  double ms_sum[P_N] = {0, 0, 0, 0};
+  int64_t calls[P_N] = {0, 0, 0, 0};
+};
+
+namespace {
+
+template <typename T>
+int dalloc(sfc_cache* c, T** p, int64_t n) {
+  if (n < 1) n = 1;
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, (size_t)n * sizeof(T));
+  if (e != hipSuccess) return fail(SFC_ENOMEM, "hipMalloc", e);
+  c->allocs.push_back(q);
+  *p = (T*)q;
+  return SFC_OK;
+}
+
+template <typename T>
+void fill(hipStream_t s, T* p, int64_t n, T v) {
+  if (n <= 0) return;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(k_fill<T>, dim3((unsigned)blocks), dim3(256), 0, s, p, n, v);
+}
+
+int grid_for(int64_t items, int per_block, int cap) {
+  int64_t b = (items + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (int)b;
+}
+
+int prof_begin(sfc_cache* c, int which, hipStream_t s, EventPair* ep) {
+  if (!c->prof) return SFC_OK;
+  if (!c->spare.empty()) { *ep = c->spare.back(); c->spare.pop_back(); }
+  else { HIPCHK(hipEventCreate(&ep->a)); HIPCHK(hipEventCreate(&ep->b)); }
+  HIPCHK(hipEventRecord(ep->a, s));
+  (void)which;
+  return SFC_OK;
+}
+int prof_end(sfc_cache* c, int which, hipStream_t s, EventPair* ep) {
+  if (!c->prof) return SFC_OK;
+  HIPCHK(hipEventRecord(ep->b, s));
+  c->pending[which].push_back(*ep);
+  return SFC_OK;
+}
+int prof_collect(sfc_cache* c) {
+  for (int w = 0; w < P_N; ++w) {
+    for (EventPair& ep : c->pending[w]) {
+      float ms = 0.f;
+      HIPCHK(hipEventSynchronize(ep.b));
+      HIPCHK(hipEventElapsedTime(&ms, ep.a, ep.b));
+      c->ms_sum[w] += ms;
+      c->calls[w] += 1;
+      c->spare.push_back(ep);
+    }
+    c->pending[w].clear();
+  }
+  return SFC_OK;
+}
+
+constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
+
+}  // namespace
+
+extern "C" {
+
+const char* sfc_strerror(int code) {
+  switch (code) {
+    case SFC_OK: return "ok";
+    case SFC_EINVAL: return "invalid argument";
+    case SFC_ESTATE: return "call out of order";
+    case SFC_EHIP: return "HIP runtime error";
+    case SFC_ENOMEM: return "out of memory";
+    case SFC_ELIMIT: return "step limit reached";
+    default: return "unknown error";
+  }
+}
+const char* sfc_last_error(void) { return g_err.c_str(); }
+
+void* sfc_host_alloc(int64_t bytes) {
+  void* p = nullptr;
+  if (bytes <= 0) return nullptr;
+  if (hipHostMalloc(&p, (size_t)bytes, hipHostMallocMapped | hipHostMallocPortable) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  return p;
+}
+void sfc_host_free(void* p) { if (p) (void)hipHostFree(p); }
+
+void sfc_cache_destroy(sfc_cache* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->st);
+  if (c->side != c->st) (void)hipStreamSynchronize(c->side);
+  for (int w = 0; w < P_N; ++w)
+    for (EventPair& ep : c->pending[w]) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
+  for (EventPair& ep : c->spare) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
+  if (c->ev_prepared) (void)hipEventDestroy(c->ev_prepared);
+  if (c->ev_fetched) (void)hipEventDestroy(c->ev_fetched);
+  for (void* p : c->allocs) (void)hipFree(p);
+  delete c;
+}
+
+int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
+  if (!cfg || !out) return fail(SFC_EINVAL, "null config or output pointer");
+  *out = nullptr;
+  if (cfg->capacity_rows < 0 || cfg->dim <= 0 || cfg->dim % 4 || cfg->dim > 1024)
+    return fail(SFC_EINVAL, "capacity_rows must be >= 0 and dim a multiple of 4 in [4, 1024]");
+  if (cfg->policy != SFC_POLICY_LRU_BATCH) return fail(SFC_EINVAL, "unknown policy");
+  if (cfg->max_ids_per_batch < 1 || cfg->max_bags_per_batch < 1 || cfg->host_rows < 1)
+    return fail(SFC_EINVAL, "max_ids_per_batch, max_bags_per_batch and host_rows must be >= 1");
+  if (cfg->capacity_rows + cfg->max_ids_per_batch >= (int64_t)1 << 31 ||
+      2 * (cfg->capacity_rows + cfg->max_ids_per_batch) >= (int64_t)1 << 32 ||
+      cfg->max_bags_per_batch >= (int64_t)1 << 31)
+    return fail(SFC_EINVAL, "capacity_rows + max_ids_per_batch must stay below 2^31");
+  if (!cfg->h_weights || !cfg->h_acc) return fail(SFC_EINVAL, "null host table");
+  if (((uintptr_t)cfg->h_weights | (uintptr_t)cfg->h_acc) & 15)
+    return fail(SFC_EINVAL, "host table must be 16-byte aligned");
+  if (cfg->lookahead < 0 || cfg->lookahead > 1) return fail(SFC_EINVAL, "lookahead must be 0 or 1");
+  if (cfg->max_steps < 0) return fail(SFC_EINVAL, "max_steps must be >= 0");
+
+  sfc_cache* c = new (std::nothrow) sfc_cache;
+  if (!c) return fail(SFC_ENOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  c->C = cfg->capacity_rows; c->V = cfg->host_rows; c->D = cfg->dim; c->d4 = cfg->dim / 4;
+  c->max_ids = cfg->max_ids_per_batch; c->max_bags = cfg->max_bags_per_batch;
+  c->st = (hipStream_t)cfg->stream;
+  c->side = cfg->side_stream ? (hipStream_t)cfg->side_stream : c->st;
+  c->hist_len = (cfg->max_steps ? cfg->max_steps : (1 << 20)) + 2;
+  c->hi = (uint32_t)(2 * (c->C + c->max_ids));
+  if (c->hi < 64) c->hi = 64;
+
+  int rc = SFC_OK;
+  hipError_t e;
+  void* dp = nullptr;
+  if ((e = hipHostGetDevicePointer(&dp, cfg->h_weights, 0)) != hipSuccess) {
+    rc = fail(SFC_EINVAL, "h_weights is not pinned device-mapped host memory", e); goto bad;
+  }
+  c->d_hw = (float*)dp;
+  if ((e = hipHostGetDevicePointer(&dp, cfg->h_acc, 0)) != hipSuccess) {
+    rc = fail(SFC_EINVAL, "h_acc is not pinned device-mapped host memory", e); goto bad;
+  }
+  c->d_ha = (float*)dp;
+
+  {
+    const int64_t rows = c->C + c->max_ids;
+    const int64_t hu = 2 * c->max_ids;
+    if ((rc = dalloc(c, &c->cw, rows * c->D))) goto bad;
+    if ((rc = dalloc(c, &c->ca, rows * c->D))) goto bad;
+    if ((rc = dalloc(c, &c->slot_id, c->C))) goto bad;
+    if ((rc = dalloc(c, &c->stamp, c->C))) goto bad;
+    if ((rc = dalloc(c, &c->index, (int64_t)c->hi))) goto bad;
+    if ((rc = dalloc(c, &c->hist, (int64_t)c->hist_len))) goto bad;
+    if ((rc = dalloc(c, &c->ukeys, hu))) goto bad;
+    if ((rc = dalloc(c, &c->uminpos, hu))) goto bad;
+    if ((rc = dalloc(c, &c->uvid, hu))) goto bad;
+    if ((rc = dalloc(c, &c->hslot, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->vid_hslot, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->blk_cnt, c->max_ids / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->tile_miss, c->max_ids / kVidTile + 2))) goto bad;
+    if ((rc = dalloc(c, &c->tile_lt, c->C / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->tile_eq, c->C / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->victim_slot, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->victim_id, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->g64, c->max_ids * c->D))) goto bad;
+    if ((rc = dalloc(c, &c->ctr, 1))) goto bad;
+
+    hipStream_t s = c->st;
+    fill<int64_t>(s, c->slot_id, c->C, (int64_t)-1);
+    fill<int>(s, c->stamp, c->C, 0);
+    IdxEntry empty; empty.key = kEmpty; empty.slot = -1; empty.pad = 0;
+    fill<IdxEntry>(s, c->index, (int64_t)c->hi, empty);
+    fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
+    fill<int64_t>(s, c->ukeys, hu, kEmpty);
+    fill<int>(s, c->uminpos, hu, kIntMax);
+    fill<double>(s, c->g64, c->max_ids * c->D, 0.0);
+    Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
+    if ((e = hipMemcpyAsync(c->ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&c->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&c->ev_fetched, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipStreamSynchronize(s)) != hipSuccess || (e = hipGetLastError()) != hipSuccess) {
+      rc = fail(SFC_EHIP, "cache initialisation", e); goto bad;
+    }
+  }
+  *out = c;
+  return SFC_OK;
+bad:
+  sfc_cache_destroy(c);
+  return rc;
+}
+
+int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t* d_offsets,
+                int64_t n_bags, int64_t* d_unique_ids, int32_t* d_inverse, int32_t* d_slot,
+                int32_t* d_miss_vids) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (n_ids < 0 || n_bags < 0 || n_ids > c->max_ids || n_bags > c->max_bags)
+    return fail(SFC_EINVAL, "n_ids / n_bags out of range");
+  if (!d_offsets && n_bags != n_ids) return fail(SFC_EINVAL, "one-hot input needs n_bags == n_ids");
+  if ((n_ids > 0 && !d_ids) || !d_unique_ids || !d_inverse || !d_slot || !d_miss_vids)
+    return fail(SFC_EINVAL, "null buffer");
+  if (c->state == PREPARED)
+    return fail(SFC_ESTATE, "sfc_prepare twice without sfc_fetch_misses: missed rows would never arrive");
+  if (c->t + 1 >= c->hist_len - 1) return fail(SFC_ELIMIT, "max_steps reached");
+  c->t += 1;
+  c->n_ids = n_ids; c->n_bags = n_bags; c->d_offsets = d_offsets;
+  c->d_unique = d_unique_ids; c->d_inverse = d_inverse; c->d_slot = d_slot; c->d_miss = d_miss_vids;
+  hipStream_t s = c->st;
+  EventPair ep{};
+  int rc;
+  if ((rc = prof_begin(c, P_PREPARE, s, &ep))) return rc;
+
+  const int n = (int)n_ids;
+  uint32_t hu = (uint32_t)(2 * n_ids);
+  if (hu < 64) hu = 64;                       // the batch table is empty between steps: any size works
+  if (hu > 2 * c->max_ids) hu = (uint32_t)(2 * c->max_ids);
+  const int nchunk = (n + kPosChunk - 1) / kPosChunk;
+  // per-step counters that the kernels accumulate into
+  hipLaunchKernelGGL(k_fill<int>, dim3(1), dim3(64), 0, s, &c->ctr->n_hit, (int64_t)2, 0);  // n_hit, n_invalid
+  if (n > 0) {
+    hipLaunchKernelGGL(k_uniq_insert, dim3((n + 1023) / 1024), dim3(256), 0, s, d_ids, n, c->V,
+                       c->ukeys, c->uminpos, hu, c->hslot, c->ctr);
+    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uminpos, n,
+                       c->blk_cnt);
+  }
+  hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->ctr);
+  hipLaunchKernelGGL(k_index_reinsert, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi,
+                     c->slot_id, c->ctr);
+  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, c->ctr);
+  if (n > 0) {
+    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uminpos,
+                       c->ukeys, n, c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot);
+    hipLaunchKernelGGL(k_uniq_inverse, dim3((n + 1023) / 1024), dim3(256), 0, s, c->hslot, c->uvid,
+                       n, d_inverse);
+  }
+  const int gv = grid_for(n, kVidTile, kGridCap);
+  hipLaunchKernelGGL(k_resolve, dim3(gv), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->ukeys,
+                     c->uminpos, c->index, c->hi, c->stamp, c->hist, c->t, d_slot, c->tile_miss,
+                     c->ctr);
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->hist, c->t,
+                     c->cfg.lookahead, (int)c->C, c->hi, c->ctr);
+  const int gs = grid_for(c->C, kPosChunk, kGridCap);
+  hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
+                     c->ctr);
+  hipLaunchKernelGGL(k_victim_scan, dim3(1), dim3(1024), 0, s, c->tile_lt, c->tile_eq, c->ctr);
+  hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
+                     c->tile_eq, c->index, c->hi, c->victim_slot, c->victim_id, c->ctr);
+  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->tile_miss,
+                     c->victim_slot, d_slot, d_miss_vids, c->slot_id, c->stamp, c->index, c->hi,
+                     c->t, (int)c->C, c->ctr);
+  HIPCHK(hipGetLastError());
+  if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
+  HIPCHK(hipEventRecord(c->ev_prepared, s));
+  c->state = PREPARED;
+  return SFC_OK;
+}
+
+int sfc_fetch_misses(sfc_cache* c) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (c->state != PREPARED) return fail(SFC_ESTATE, "sfc_fetch_misses needs a preceding sfc_prepare");
+  hipStream_t s = c->side;
+  if (s != c->st) HIPCHK(hipStreamWaitEvent(s, c->ev_prepared, 0));
+  EventPair ep{};
+  int rc;
+  if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
+  const float4 *cw = (const float4*)c->cw, *ca = (const float4*)c->ca;
+  const int g = grid_for(c->n_ids * c->d4, 256, 1024);
+  hipLaunchKernelGGL(k_writeback_victims, dim3(g), dim3(256), 0, s, c->victim_slot, c->victim_id,
+                     cw, ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
+  hipLaunchKernelGGL(k_fetch_misses, dim3(g), dim3(256), 0, s, c->d_miss, c->d_unique, c->d_slot,
+                     (const float4*)c->d_hw, (const float4*)c->d_ha, (float4*)c->cw,
+                     (float4*)c->ca, c->d4, c->ctr);
+  HIPCHK(hipGetLastError());
+  if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
+  if (s != c->st) {
+    HIPCHK(hipEventRecord(c->ev_fetched, s));
+    HIPCHK(hipStreamWaitEvent(c->st, c->ev_fetched, 0));
+  }
+  c->state = FETCHED;
+  return SFC_OK;
+}
+
+int sfc_lookup(sfc_cache* c, float* d_out) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (c->state != FETCHED) return fail(SFC_ESTATE, "sfc_lookup needs sfc_prepare and sfc_fetch_misses first");
+  if (!d_out) return fail(SFC_EINVAL, "null output");
+  if ((uintptr_t)d_out & 15) return fail(SFC_EINVAL, "output must be 16-byte aligned");
+  hipStream_t s = c->st;
+  EventPair ep{};
+  int rc;
+  if ((rc = prof_begin(c, P_LOOKUP, s, &ep))) return rc;
+  const int64_t total = c->n_bags * c->d4;
+  if (total > 0) {
+    if (!c->d_offsets)
+      hipLaunchKernelGGL(k_lookup_onehot, dim3((unsigned)((total + 1023) / 1024)), dim3(256), 0, s,
+                         c->d_inverse, c->d_slot, (const float4*)c->cw, (float4*)d_out, total, c->d4);
+    else
+      hipLaunchKernelGGL(k_lookup_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                         c->d_offsets, c->d_inverse, c->d_slot, (const float4*)c->cw,
+                         (float4*)d_out, total, c->d4);
+  }
+  HIPCHK(hipGetLastError());
+  return prof_end(c, P_LOOKUP, s, &ep);
+}
+
+static int accumulate(sfc_cache* c, const float* d_grad) {
+  const int64_t total = c->n_bags * c->d4;
+  if (total <= 0) return SFC_OK;
+  if (!c->d_offsets)
+    hipLaunchKernelGGL(k_accum_onehot, dim3((unsigned)((total + 1023) / 1024)), dim3(256), 0, c->st,
+                       (const float4*)d_grad, c->d_inverse, c->g64, total, c->d4);
+  else
+    hipLaunchKernelGGL(k_accum_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->st,
+                       (const float4*)d_grad, c->d_offsets, c->d_inverse, c->g64, total, c->d4);
+  return SFC_OK;
+}
+
+int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (c->state == IDLE) return fail(SFC_ESTATE, "sfc_segment_sum needs a preceding sfc_prepare");
+  if ((c->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
+  if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
+  accumulate(c, d_grad);
+  hipLaunchKernelGGL(k_emit_common, dim3(grid_for(c->n_ids * c->d4, 256, kGridCap)), dim3(256), 0,
+                     c->st, c->g64, (float4*)d_common_grad, c->d4, c->ctr);
+  HIPCHK(hipGetLastError());
+  return SFC_OK;
+}
+
+int sfc_backward_update(sfc_cache* c, const float* d_grad) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (c->state != FETCHED) return fail(SFC_ESTATE, "sfc_backward_update needs sfc_prepare and sfc_fetch_misses first");
+  if (c->n_bags > 0 && !d_grad) return fail(SFC_EINVAL, "null gradient");
+  if ((uintptr_t)d_grad & 15) return fail(SFC_EINVAL, "gradient must be 16-byte aligned");
+  hipStream_t s = c->st;
+  EventPair ep{};
+  int rc;
+  if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
+  accumulate(c, d_grad);
+  const int g = grid_for(c->n_ids * c->d4, 256, kGridCap);
+  hipLaunchKernelGGL(k_adagrad, dim3(g), dim3(256), 0, s, c->g64, c->d_slot, (float4*)c->cw,
+                     (float4*)c->ca, c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
+  hipLaunchKernelGGL(k_writeback_bypass, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0,
+                     s, c->d_miss, c->d_unique, c->d_slot, (const float4*)c->cw,
+                     (const float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
+  HIPCHK(hipGetLastError());
+  if ((rc = prof_end(c, P_BACKWARD, s, &ep))) return rc;
+  c->state = IDLE;
+  return SFC_OK;
+}
+
+static int sync_all(sfc_cache* c) {
+  HIPCHK(hipStreamSynchronize(c->st));
+  if (c->side != c->st) HIPCHK(hipStreamSynchronize(c->side));
+  return SFC_OK;
+}
+
+int sfc_flush(sfc_cache* c) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (c->state == PREPARED) return fail(SFC_ESTATE, "sfc_flush between sfc_prepare and sfc_fetch_misses");
+  hipLaunchKernelGGL(k_flush, dim3(grid_for(c->C * c->d4, 256, kGridCap)), dim3(256), 0, c->st,
+                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, (float4*)c->d_hw,
+                     (float4*)c->d_ha, c->d4, c->ctr);
+  HIPCHK(hipGetLastError());
+  return sync_all(c);
+}
+
+int sfc_get_stats(sfc_cache* c, sfc_stats* h_out) {
+  if (!c || !h_out) return fail(SFC_EINVAL, "null argument");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  Ctr h;
+  HIPCHK(hipMemcpy(&h, c->ctr, sizeof h, hipMemcpyDeviceToHost));
+  if (h.err) return fail(SFC_EHIP, "cache index probe ran off its bound (index corrupt)");
+  const int64_t rowbytes = 2 * (int64_t)sizeof(float) * c->D;
+  h_out->n_unique = h.U; h_out->n_hit = h.n_hit; h_out->n_miss = h.M; h_out->n_evict = h.K;
+  h_out->n_bypass = h.n_bypass; h_out->n_invalid = h.n_invalid;
+  h_out->h2d_bytes = h.M * rowbytes;
+  h_out->d2h_bytes = ((int64_t)h.K + h.n_bypass) * rowbytes;
+  return SFC_OK;
+}
+
+int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h_rows, float* h_acc) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  if (c->C == 0) return SFC_OK;
+  const size_t rows = (size_t)c->C * c->D * sizeof(float);
+  if (h_slot_id) HIPCHK(hipMemcpy(h_slot_id, c->slot_id, (size_t)c->C * sizeof(int64_t), hipMemcpyDeviceToHost));
+  if (h_stamp) HIPCHK(hipMemcpy(h_stamp, c->stamp, (size_t)c->C * sizeof(int32_t), hipMemcpyDeviceToHost));
+  if (h_rows) HIPCHK(hipMemcpy(h_rows, c->cw, rows, hipMemcpyDeviceToHost));
+  if (h_acc) HIPCHK(hipMemcpy(h_acc, c->ca, rows, hipMemcpyDeviceToHost));
+  return SFC_OK;
+}
+
+int sfc_profile_enable(sfc_cache* c, int32_t on) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  c->prof = on != 0;
+  return SFC_OK;
+}
+
+int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls) {
+  if (!c || which < 0 || which >= P_N || !h_ms_sum || !h_calls) return fail(SFC_EINVAL, "bad argument");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  if ((rc = prof_collect(c))) return rc;
+  *h_ms_sum = c->ms_sum[which];
+  *h_calls = c->calls[which];
+  c->ms_sum[which] = 0;
+  c->calls[which] = 0;
+  return SFC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Device-side building blocks shared by the kernels of the sparse-embedding step:
+// hashing, wavefront/block scans and reductions for 64-wide wavefronts, 16-byte row chunks.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sfc {
+
+constexpr int kWave = 64;
+constexpr int64_t kEmpty = -1;      // never-used entry of a hash table
+constexpr int64_t kNullKey = -2;    // batch-unique table: the collapsed out-of-range id
+constexpr int64_t kTomb = -2;       // cache index: deleted entry (ids in the index are >= 0)
+constexpr int kMissMark = -2;       // d_slot value between resolve and assignment
+constexpr int kIntMax = 0x7fffffff;
+
+// Device counters of one cache.  Written by kernels only; the host reads a copy in get_stats.
+struct Ctr {
+  int U;          // unique ids of the batch
+  int M;          // misses
+  int K;          // victims
+  int n_bypass;
+  int n_hit;
+  int n_invalid;
+  int f;          // slots [0, f) are occupied, [f, C) have never been used
+  int f_old;      // f before this step's inserts
+  int need;       // misses that found no free slot
+  int T;          // stamp threshold: stamp < T is evicted, stamp == T partly
+  int r;          // how many slots with stamp == T are evicted (lowest slots first)
+  int oldest;     // no occupied slot has a stamp below this
+  int tomb;       // deleted entries in the cache index
+  int rebuild;    // set when the index must be rebuilt before the next resolve
+  int err;        // nonzero: a probe loop ran off its bound
+  int pad;
+};
+
+struct __attribute__((aligned(16))) IdxEntry {
+  int64_t key;    // id, kEmpty or kTomb
+  int32_t slot;
+  int32_t pad;
+};
+
+// murmur3 64-bit finaliser
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  x ^= x >> 33; x *= 0xff51afd7ed558ccdULL;
+  x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ULL;
+  x ^= x >> 33;
+  return x;
+}
+// bucket in [0, n) without a power-of-two table: high half of a 32x32 product
+__device__ __forceinline__ uint32_t bucket_of(int64_t key, uint32_t n) {
+  return (uint32_t)(((mix64((uint64_t)key) >> 32) * (uint64_t)n) >> 32);
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int y = __shfl_up(x, d, kWave);
+    if (lane >= d) x += y;
+  }
+  return x;
+}
+
+__device__ __forceinline__ int wave_sum(int x) {
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) x += __shfl_xor(x, d, kWave);
+  return x;
+}
+
+// Exclusive scan of one int per thread over the block (blockDim.x multiple of 64, <= 1024).
+// smem: at least 17 ints.  total = sum over the block.  Safe to call repeatedly.
+__device__ __forceinline__ int block_excl_scan(int x, int& total, int* smem) {
+  const int lane = lane_id(), w = (int)(threadIdx.x >> 6), nw = (int)(blockDim.x >> 6);
+  int inc = wave_incl_scan(x);
+  if (lane == kWave - 1) smem[w] = inc;
+  __syncthreads();
+  if (w == 0) {
+    int s = lane < nw ? smem[lane] : 0;
+    int si = wave_incl_scan(s);
+    if (lane < nw) smem[lane] = si - s;   // exclusive prefix of the wave sums
+    if (lane == nw - 1) smem[16] = si;
+  }
+  __syncthreads();
+  int res = inc - x + smem[w];
+  total = smem[16];
+  __syncthreads();
+  return res;
+}
+
+__device__ __forceinline__ int block_sum(int x, int* smem) {
+  const int lane = lane_id(), w = (int)(threadIdx.x >> 6), nw = (int)(blockDim.x >> 6);
+  x = wave_sum(x);
+  if (lane == 0) smem[w] = x;
+  __syncthreads();
+  int s = 0;
+  for (int i = 0; i < nw; ++i) s += smem[i];
+  __syncthreads();
+  return s;
+}
+
+}  // namespace sfc

@@ -1,0 +1,462 @@
+// Kernels of sfc_prepare: Virtual Sparse Id (batch unique with first-appearance order and the
+// per-position inverse) and the MixCache manager (resolve against the index in HBM, victim
+// selection by batch-granular LRU, slot assignment, index maintenance).
+//
+// Determinism: every output is a function of the input sets and slot numbers only.  Orders are
+// produced by prefix scans over positions / virtual ids / slots, never by arrival order of
+// atomics; atomics are used only where the result is order-free (min, counters, set insert).
+#pragma once
+#include "sfc_device.h"
+
+namespace sfc {
+
+constexpr int kPosChunk = 2048;   // positions (or slots) per block in the scan passes
+constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
+
+// ---------------------------------------------------------------------------------------------
+// VSI pass 1: insert every position's id into the batch table (open addressing, linear probing)
+// and keep the smallest position per key.  Remembers the table entry of each position.
+// Hot ids are read-mostly: a position only issues an atomic when the plain load has not yet
+// seen its key / a smaller position, so the hottest key costs loads, not serialised atomics.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__ ids, int n,
+                                                      int64_t V, int64_t* ukeys, int* uminpos,
+                                                      uint32_t hu, int* __restrict__ hslot,
+                                                      Ctr* ctr) {
+  const int base = blockIdx.x * 1024;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = base + i * 256 + (int)threadIdx.x;
+    bool invalid = false;
+    if (p < n) {
+      int64_t key = ids[p];
+      if (key < 0 || key >= V) { key = kNullKey; invalid = true; }
+      uint32_t h = bucket_of(key, hu);
+      for (uint32_t probes = 0; probes < hu; ++probes) {
+        int64_t k = ukeys[h];
+        if (k == key) break;
+        if (k == kEmpty) {
+          int64_t old = (int64_t)atomicCAS((unsigned long long*)&ukeys[h],
+                                           (unsigned long long)kEmpty, (unsigned long long)key);
+          if (old == kEmpty || old == key) break;
+        }
+        h = h + 1 == hu ? 0 : h + 1;
+      }
+      if (uminpos[h] > p) atomicMin(&uminpos[h], p);
+      hslot[p] = (int)h;
+    }
+    const uint64_t b = __ballot(invalid);
+    if (b && lane_id() == 0) atomicAdd(&ctr->n_invalid, __popcll(b));
+  }
+}
+
+// VSI pass 2: per chunk of positions, how many are the first appearance of their id.
+__global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslot,
+                                                     const int* __restrict__ uminpos, int n,
+                                                     int* __restrict__ blk_cnt) {
+  __shared__ int smem[20];
+  const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
+  int c = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j;
+    if (p < n) c += (uminpos[hslot[p]] == p);
+  }
+  const int tot = block_sum(c, smem);
+  if (threadIdx.x == 0) blk_cnt[blockIdx.x] = tot;
+}
+
+// Single-block exclusive scan of data[0..n) in place; total to *total_out.  Also the place where
+// per-step flags are reset (it runs once per prepare, after the optional index rebuild).
+__global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* ctr) {
+  __shared__ int smem[20];
+  int carry = 0;
+  for (int b = 0; b < n; b += 1024) {
+    const int i = b + (int)threadIdx.x;
+    const int x = i < n ? data[i] : 0;
+    int tot;
+    const int e = block_excl_scan(x, tot, smem);
+    if (i < n) data[i] = carry + e;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) {
+    ctr->U = carry;
+    if (ctr->rebuild) { ctr->rebuild = 0; ctr->tomb = 0; }
+  }
+}
+
+// VSI pass 3: first appearances get consecutive virtual ids in position order.
+__global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hslot,
+                                                      const int* __restrict__ uminpos,
+                                                      const int64_t* __restrict__ ukeys, int n,
+                                                      const int* __restrict__ blk_off,
+                                                      int64_t* __restrict__ unique_ids,
+                                                      int* __restrict__ uvid,
+                                                      int* __restrict__ vid_hslot) {
+  __shared__ int smem[20];
+  const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
+  int hs[8];
+  unsigned flags = 0;
+  int c = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j;
+    hs[j] = 0;
+    if (p < n) {
+      hs[j] = hslot[p];
+      if (uminpos[hs[j]] == p) { flags |= 1u << j; ++c; }
+    }
+  }
+  int tot;
+  int vid = block_excl_scan(c, tot, smem) + blk_off[blockIdx.x];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (flags & (1u << j)) {
+      const int64_t key = ukeys[hs[j]];
+      unique_ids[vid] = key == kNullKey ? (int64_t)-1 : key;
+      uvid[hs[j]] = vid;
+      vid_hslot[vid] = hs[j];
+      ++vid;
+    }
+  }
+}
+
+// VSI pass 4: virtual id of every position.
+__global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hslot,
+                                                       const int* __restrict__ uvid, int n,
+                                                       int* __restrict__ inverse) {
+  const int base = blockIdx.x * 1024;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = base + i * 256 + (int)threadIdx.x;
+    if (p < n) inverse[p] = uvid[hslot[p]];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Cache index helpers (open addressing, linear probing, tombstones).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int index_find(const IdxEntry* __restrict__ index, uint32_t hi,
+                                          int64_t id, uint32_t* where, Ctr* ctr) {
+  uint32_t h = bucket_of(id, hi);
+  for (uint32_t probes = 0; probes < hi; ++probes) {
+    const int4 raw = *reinterpret_cast<const int4*>(&index[h]);
+    const int64_t k = ((int64_t)(uint32_t)raw.y << 32) | (uint32_t)raw.x;
+    if (k == id) { if (where) *where = h; return raw.z; }
+    if (k == kEmpty) return -1;
+    h = h + 1 == hi ? 0 : h + 1;
+  }
+  ctr->err = 1;
+  return -1;
+}
+
+// id is known to be absent.  Takes the first empty or deleted entry of its probe sequence.
+__device__ __forceinline__ void index_insert(IdxEntry* index, uint32_t hi, int64_t id, int slot,
+                                             Ctr* ctr) {
+  uint32_t h = bucket_of(id, hi);
+  for (uint32_t probes = 0; probes < hi; ++probes) {
+    const int64_t k = index[h].key;
+    if (k == kEmpty || k == kTomb) {
+      const int64_t old = (int64_t)atomicCAS((unsigned long long*)&index[h].key,
+                                             (unsigned long long)k, (unsigned long long)id);
+      if (old == k) {
+        index[h].slot = slot;
+        if (k == kTomb) atomicSub(&ctr->tomb, 1);
+        return;
+      }
+    }
+    h = h + 1 == hi ? 0 : h + 1;
+  }
+  ctr->err = 2;
+}
+
+// Optional rebuild (runs every step, returns at once unless the plan kernel asked for it).
+__global__ __launch_bounds__(256) void k_index_clear(IdxEntry* index, uint32_t hi, const Ctr* ctr) {
+  if (!ctr->rebuild) return;
+  IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
+  for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
+}
+__global__ __launch_bounds__(256) void k_index_reinsert(IdxEntry* index, uint32_t hi,
+                                                         const int64_t* __restrict__ slot_id,
+                                                         Ctr* ctr) {
+  if (!ctr->rebuild) return;
+  const int f = ctr->f;
+  for (int s = blockIdx.x * 256 + threadIdx.x; s < f; s += gridDim.x * 256) {
+    const int64_t id = slot_id[s];
+    if (id < 0) continue;
+    uint32_t h = bucket_of(id, hi);
+    for (uint32_t probes = 0; probes < hi; ++probes) {
+      if (index[h].key == kEmpty &&
+          (int64_t)atomicCAS((unsigned long long*)&index[h].key, (unsigned long long)kEmpty,
+                             (unsigned long long)id) == kEmpty) {
+        index[h].slot = s;
+        break;
+      }
+      h = h + 1 == hi ? 0 : h + 1;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Resolve: each unique id against the index.  Hits get their slot and the current stamp; the
+// recency histogram hist[stamp] = #slots with that stamp is kept exact.  Also returns the batch
+// table entries of this step to the empty state, so no per-step clear of that table is needed.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
+                                                  const int* __restrict__ vid_hslot,
+                                                  int64_t* ukeys, int* uminpos,
+                                                  const IdxEntry* __restrict__ index, uint32_t hi,
+                                                  int* stamp, int* hist, int t,
+                                                  int* __restrict__ slot_out,
+                                                  int* __restrict__ tile_miss, Ctr* ctr) {
+  __shared__ int smem[20];
+  const int U = ctr->U;
+  for (int tile = blockIdx.x; tile * kVidTile < U; tile += gridDim.x) {
+    const int v = tile * kVidTile + (int)threadIdx.x;
+    bool hit = false, miss = false;
+    int old = 0;
+    if (v < U) {
+      const int h = vid_hslot[v];
+      ukeys[h] = kEmpty;
+      uminpos[h] = kIntMax;
+      const int64_t id = unique_ids[v];
+      if (id < 0) {
+        slot_out[v] = -1;
+      } else {
+        const int s = index_find(index, hi, id, nullptr, ctr);
+        if (s >= 0) {
+          slot_out[v] = s;
+          old = stamp[s];
+          stamp[s] = t;
+          hit = true;
+        } else {
+          slot_out[v] = kMissMark;
+          miss = true;
+        }
+      }
+    }
+    // hist[old] -= 1 per hit, one atomic per distinct old stamp in the wavefront
+    uint64_t m = __ballot(hit);
+    while (m) {
+      const int leader = __ffsll((unsigned long long)m) - 1;
+      const int lo = __shfl(old, leader, kWave);
+      const uint64_t same = __ballot(hit && old == lo);
+      if (lane_id() == leader) atomicSub(&hist[lo], __popcll(same));
+      m &= ~same;
+    }
+    const int nmiss = block_sum(miss ? 1 : 0, smem);
+    const int nhit = block_sum(hit ? 1 : 0, smem);
+    if (threadIdx.x == 0) {
+      tile_miss[tile] = nmiss;
+      if (nhit) { atomicAdd(&ctr->n_hit, nhit); atomicAdd(&hist[t], nhit); }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plan (one block): scan the per-tile miss counts, then decide the victims' stamp threshold from
+// the recency histogram: need = M - free; T is the stamp at which the running count of
+// evictable slots (stamp < limit, oldest first) passes need; r of the slots stamped T go too.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* hist, int t, int lookahead,
+                                               int C, uint32_t hi, Ctr* ctr) {
+  __shared__ int smem[20];
+  __shared__ int s_found;
+  // every thread reads the counters here; thread 0 overwrites them only after the last barrier
+  const int U = ctr->U;
+  const int f = ctr->f;
+  const int oldest = ctr->oldest;
+  const int ntiles = (U + kVidTile - 1) / kVidTile;
+  int carry = 0;
+  for (int b = 0; b < ntiles; b += 1024) {
+    const int i = b + (int)threadIdx.x;
+    const int x = i < ntiles ? tile_miss[i] : 0;
+    int tot;
+    const int e = block_excl_scan(x, tot, smem);
+    if (i < ntiles) tile_miss[i] = carry + e;
+    carry += tot;
+  }
+  const int M = carry;
+  const int free_slots = C - f;
+  const int need = M - free_slots;
+  const int limit = t - lookahead;       // candidates have stamp < limit
+  int T = limit, r = 0, K = 0;
+  if (need > 0) {
+    // running count of candidates from the oldest stamp upwards
+    int cum = 0;           // slots with stamp in [oldest, b)
+    bool done = false;
+    for (int b = oldest; b < limit && !done; b += 1024) {
+      if (threadIdx.x == 0) s_found = kIntMax;
+      __syncthreads();
+      const int s = b + (int)threadIdx.x;
+      const int x = s < limit ? hist[s] : 0;
+      int tot;
+      const int e = block_excl_scan(x, tot, smem);
+      // first stamp whose inclusive count exceeds need
+      if (s < limit && cum + e + x > need) atomicMin(&s_found, s);
+      __syncthreads();
+      if (s_found != kIntMax) {
+        T = s_found;
+        if (s == T) smem[18] = cum + e;    // candidates strictly older than T
+        __syncthreads();
+        r = need - smem[18];
+        K = need;
+        done = true;
+      } else {
+        cum += tot;
+      }
+      __syncthreads();
+    }
+    if (!done) { T = limit; r = 0; K = cum; }   // everything evictable goes, the rest bypasses
+    // the histogram after eviction: stamps below T vanish, r leave stamp T
+    for (int s = oldest + (int)threadIdx.x; s < T; s += 1024) hist[s] = 0;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (need > 0 && r > 0) hist[T] -= r;
+    int f_new = f + (M - K);
+    if (f_new > C) f_new = C;
+    const int n_bypass = M - K - (f_new - f);
+    hist[t] += M - n_bypass;
+    ctr->M = M; ctr->K = K; ctr->n_bypass = n_bypass;
+    ctr->need = need; ctr->T = T; ctr->r = r;
+    ctr->f_old = f; ctr->f = f_new;
+    if (need > 0 && T > oldest) ctr->oldest = T;
+    // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
+    // quarter of the index would be deleted entries
+    if ((unsigned)(ctr->tomb + K) > hi / 4) ctr->rebuild = 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Victim selection over the occupied slots, in slot order (two passes around a scan):
+// victim  <=>  stamp < T, or stamp == T and fewer than r earlier slots carry stamp T.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_victim_count(const int* __restrict__ stamp,
+                                                       int* __restrict__ tile_lt,
+                                                       int* __restrict__ tile_eq, const Ctr* ctr) {
+  __shared__ int smem[20];
+  if (ctr->K == 0) return;
+  const int f = ctr->f_old, T = ctr->T;
+  for (int tile = blockIdx.x; tile * kPosChunk < f; tile += gridDim.x) {
+    const int base = tile * kPosChunk + (int)threadIdx.x * 8;
+    int lt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int s = base + j;
+      if (s < f) { const int st = stamp[s]; lt += st < T; eq += st == T; }
+    }
+    lt = block_sum(lt, smem);
+    eq = block_sum(eq, smem);
+    if (threadIdx.x == 0) { tile_lt[tile] = lt; tile_eq[tile] = eq; }
+  }
+}
+
+__global__ __launch_bounds__(1024) void k_victim_scan(int* tile_lt, int* tile_eq, const Ctr* ctr) {
+  __shared__ int smem[20];
+  if (ctr->K == 0) return;
+  const int ntiles = (ctr->f_old + kPosChunk - 1) / kPosChunk;
+  int c_lt = 0, c_eq = 0;
+  for (int b = 0; b < ntiles; b += 1024) {
+    const int i = b + (int)threadIdx.x;
+    int tot;
+    const int x = i < ntiles ? tile_lt[i] : 0;
+    const int e = block_excl_scan(x, tot, smem);
+    if (i < ntiles) tile_lt[i] = c_lt + e;
+    c_lt += tot;
+    const int y = i < ntiles ? tile_eq[i] : 0;
+    const int e2 = block_excl_scan(y, tot, smem);
+    if (i < ntiles) tile_eq[i] = c_eq + e2;
+    c_eq += tot;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ stamp,
+                                                       const int64_t* __restrict__ slot_id,
+                                                       const int* __restrict__ tile_lt,
+                                                       const int* __restrict__ tile_eq,
+                                                       IdxEntry* index, uint32_t hi,
+                                                       int* __restrict__ victim_slot,
+                                                       int64_t* __restrict__ victim_id, Ctr* ctr) {
+  __shared__ int smem[20];
+  if (ctr->K == 0) return;
+  const int f = ctr->f_old, T = ctr->T, r = ctr->r, K = ctr->K;
+  for (int tile = blockIdx.x; tile * kPosChunk < f; tile += gridDim.x) {
+    const int base = tile * kPosChunk + (int)threadIdx.x * 8;
+    unsigned mlt = 0, meq = 0;
+    int lt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int s = base + j;
+      if (s < f) {
+        const int st = stamp[s];
+        if (st < T) { mlt |= 1u << j; ++lt; }
+        if (st == T) { meq |= 1u << j; ++eq; }
+      }
+    }
+    int tot;
+    int lt_before = block_excl_scan(lt, tot, smem) + tile_lt[tile];
+    int eq_before = block_excl_scan(eq, tot, smem) + tile_eq[tile];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool is_lt = mlt & (1u << j), is_eq = meq & (1u << j);
+      if (is_lt || (is_eq && eq_before < r)) {
+        const int s = base + j;
+        const int idx = lt_before + (eq_before < r ? eq_before : r);
+        const int64_t id = slot_id[s];
+        if (idx < K) {                       // always true while hist mirrors the stamps
+          victim_slot[idx] = s;
+          victim_id[idx] = id;
+          uint32_t where;
+          if (index_find(index, hi, id, &where, ctr) >= 0) index[where].key = kTomb;
+          else ctr->err = 3;
+        } else {
+          ctr->err = 4;
+        }
+      }
+      lt_before += is_lt;
+      eq_before += is_eq;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Assignment: the i-th miss in virtual-id order takes the i-th slot of (victims u free) in
+// ascending slot order: victims (all below the watermark) first, then never-used slots from the
+// watermark up, then transient bypass rows C + j.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict__ unique_ids,
+                                                        const int* __restrict__ tile_moff,
+                                                        const int* __restrict__ victim_slot,
+                                                        int* __restrict__ slot_out,
+                                                        int* __restrict__ miss_vids,
+                                                        int64_t* __restrict__ slot_id, int* stamp,
+                                                        IdxEntry* index, uint32_t hi, int t, int C,
+                                                        Ctr* ctr) {
+  __shared__ int smem[20];
+  const int U = ctr->U, K = ctr->K, f = ctr->f_old;
+  const int free_slots = C - f;
+  for (int tile = blockIdx.x; tile * kVidTile < U; tile += gridDim.x) {
+    const int v = tile * kVidTile + (int)threadIdx.x;
+    const bool miss = v < U && slot_out[v] == kMissMark;
+    int tot;
+    const int i = block_excl_scan(miss ? 1 : 0, tot, smem) + tile_moff[tile];
+    if (miss) {
+      miss_vids[i] = v;
+      int s;
+      if (i < K) s = victim_slot[i];
+      else if (i - K < free_slots) s = f + (i - K);
+      else s = C + (i - K - free_slots);
+      slot_out[v] = s;
+      if (s < C) {
+        const int64_t id = unique_ids[v];
+        slot_id[s] = id;
+        stamp[s] = t;
+        index_insert(index, hi, id, s, ctr);
+      }
+    }
+  }
+}
+
+}  // namespace sfc

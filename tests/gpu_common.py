@@ -1,0 +1,98 @@
+"""Drives the HIP path and the CPU oracle side by side on the same seeded inputs and compares
+every output of every call: bit-exact for ids / indices / counts / cache state, and within
+1e-5 relative + 1e-6 absolute for fp32 values."""
+import numpy as np
+import torch
+
+import sfc_inputs as si
+from oracle import Oracle
+
+RTOL, ATOL = 1e-5, 1e-6
+
+
+def assert_close(a, b, what):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    assert a.shape == b.shape, (what, a.shape, b.shape)
+    bad = np.abs(a - b) > ATOL + RTOL * np.abs(b)
+    assert not bad.any(), "%s: %d of %d outside tolerance, worst abs err %.3e" % (
+        what, int(bad.sum()), bad.size, float(np.abs(a - b).max()))
+
+
+class Pair:
+    """One HIP cache and one oracle over identical copies of a host table."""
+
+    def __init__(self, V, D, C, max_ids, max_bags=None, lookahead=0, seed=5, lr=0.01, eps=1e-8,
+                 init_acc=0.1, max_steps=0, side_stream=True, device="cuda:0"):
+        import paper_2104_08542_amd as sfc
+        self.sfc = sfc
+        self.V, self.D, self.C = V, D, C
+        self.dev = torch.device(device)
+        self.table = sfc.HostTable(V, D)
+        chunk = max(1, (1 << 24) // D)
+        for r0 in range(0, V, chunk):
+            r1 = min(V, r0 + chunk)
+            self.table.w_t[r0:r1] = si.table_rows(seed, r0, r1, D, self.dev).cpu()
+        self.table.acc[:] = init_acc
+        self.ow, self.oa = self.table.w.copy(), self.table.acc.copy()
+        self.cache = sfc.Cache(self.table, C, max_ids, max_bags, lr=lr, eps=eps, lookahead=lookahead,
+                               max_steps=max_steps, device=device, side_stream=side_stream)
+        self.orc = Oracle(C, D, self.ow, self.oa, lr=lr, eps=eps, lookahead=lookahead)
+
+    def close(self):
+        self.cache.close()
+        self.table.free()
+
+    def step(self, ids, grad, offsets=None, check_common=True, check_state=True, update=True):
+        """ids/offsets: int64 CPU tensors or numpy; grad: [bags, D] fp32.  Returns oracle's Prepared."""
+        c, o = self.cache, self.orc
+        ids_np = np.asarray(ids, np.int64)
+        off_np = None if offsets is None else np.asarray(offsets, np.int64)
+        grad_np = np.asarray(grad, np.float32)
+        d_ids = torch.from_numpy(ids_np).to(self.dev)
+        d_off = None if off_np is None else torch.from_numpy(off_np).to(self.dev)
+        d_grad = torch.from_numpy(grad_np).to(self.dev)
+        n = ids_np.size
+
+        pr = o.prepare(ids_np, off_np)
+        c.prepare(d_ids, d_off)
+        st = c.stats()
+        assert st == pr.stats, (st, pr.stats)
+        U, M = st["n_unique"], st["n_miss"]
+        assert np.array_equal(c.unique_ids[:U].cpu().numpy(), pr.unique_ids), "unique_ids"
+        assert np.array_equal(c.inverse[:n].cpu().numpy(), pr.inverse), "inverse"
+        assert np.array_equal(c.slot[:U].cpu().numpy(), pr.slot), "slot"
+        assert np.array_equal(c.miss_vids[:M].cpu().numpy(), pr.miss_vids), "miss_vids"
+
+        o.fetch_misses()
+        c.fetch_misses()
+        if check_state and self.C:
+            sid, stamp = c.state()
+            osid, ostamp = o.state()
+            assert np.array_equal(sid, osid), "slot_id after fetch"
+            assert np.array_equal(stamp, ostamp), "stamp after fetch"
+
+        out = c.lookup()
+        assert_close(out.cpu().numpy(), o.lookup(), "lookup")
+        if not update:
+            return pr
+        if check_common:
+            cg = c.segment_sum(d_grad)
+            ocg = o.backward_update(grad_np, want_common_grad=True)
+            assert_close(cg[:U].cpu().numpy(), ocg, "common gradient")
+        else:
+            o.backward_update(grad_np)
+        c.backward_update(d_grad)
+        if check_state and self.C:
+            _, _, w, a = c.state(rows=True)
+            _, _, ow, oa = o.state(rows=True)
+            res = o.state()[0] >= 0
+            assert_close(w[res], ow[res], "cached rows after update")
+            assert_close(a[res], oa[res], "cached accumulators after update")
+        return pr
+
+    def finish(self):
+        self.cache.flush()
+        self.orc.flush()
+        assert_close(self.table.w, self.ow, "host weights after flush")
+        assert_close(self.table.acc, self.oa, "host accumulators after flush")

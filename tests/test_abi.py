@@ -1,0 +1,39 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/sfc.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "sfc.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(sfc_[a-z_]+)\s*\(", txt)))
+
+
+def test_header_symbols_exported():
+    import paper_2104_08542_amd as sfc
+    lib = ctypes.CDLL(sfc.LIB_PATH)
+    names = _declared()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(sfc.EXPORTS) == names      # the binding covers the same set, same names
+
+
+def test_error_strings_and_argument_checks_need_no_gpu():
+    import paper_2104_08542_amd as sfc
+    assert sfc._strerror(0) == "ok" and "order" in sfc._strerror(sfc.SFC_ESTATE)
+    cfg = sfc.sfc_config()          # all zero: rejected before any device call
+    try:
+        sfc.sfc_cache_create(cfg)
+        raise AssertionError("expected SFC_EINVAL")
+    except sfc.SfcError as e:
+        assert e.code == sfc.SFC_EINVAL
+
+
+def test_struct_layout_matches_header():
+    import paper_2104_08542_amd as sfc
+    assert ctypes.sizeof(sfc.sfc_config) == 88 and ctypes.sizeof(sfc.sfc_stats) == 64
+    assert sfc.sfc_config.h_weights.offset == 40 and sfc.sfc_config.stream.offset == 72

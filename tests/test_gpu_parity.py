@@ -1,0 +1,171 @@
+"""HIP path vs CPU oracle, element by element (run with -m gpu on an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import sfc_inputs as si
+from gpu_common import Pair
+
+pytestmark = pytest.mark.gpu
+
+
+def _zipf_steps(p, V, n, s, seed, steps, **kw):
+    for t in range(steps):
+        ids = si.zipf_ids(n, s, V, seed, t).numpy()
+        p.step(ids, si.grads(n, p.D, seed, t).numpy(), **kw)
+
+
+def test_paper_examples_on_gpu():
+    # VSI example + MixCache example (12 slots; 7 replaces 1, 8 takes the free slot)
+    p = Pair(V=32, D=4, C=12, max_ids=64)
+    z = lambda n: np.zeros((n, 4), np.float32)
+    pr = p.step([1, 3, 2, 5, 4, 6, 12, 13, 14, 15, 9], z(11))
+    pr = p.step([3, 2, 5, 4], z(4))
+    pr = p.step([6, 7, 8], z(3))
+    assert p.cache.state()[0].tolist() == [7, 3, 2, 5, 4, 6, 12, 13, 14, 15, 9, 8]
+    p.finish(); p.close()
+    p = Pair(V=8, D=4, C=8, max_ids=16)
+    pr = p.step([1, 3, 2, 2, 3, 1], np.ones((6, 4), np.float32))
+    assert p.cache.unique_ids[:3].tolist() == [1, 3, 2]
+    assert p.cache.inverse[:6].tolist() == [0, 1, 2, 2, 1, 0]
+    p.finish(); p.close()
+
+
+def test_tiny_config_bypass_every_step():
+    w = si.WORKLOADS["tiny"]                  # U ~ 10.7k > C = 10k: bypass rows on every step
+    p = Pair(w.vocab, w.dim, w.cache_rows, w.max_ids, seed=w.seed)
+    saw_bypass = saw_evict = False
+    for t in range(6):
+        ids, _ = w.batch_ids(t)
+        pr = p.step(ids.numpy(), w.batch_grads(t).numpy())
+        saw_bypass |= pr.stats["n_bypass"] > 0
+        saw_evict |= pr.stats["n_evict"] > 0
+    assert saw_bypass and saw_evict
+    p.finish(); p.close()
+
+
+@pytest.mark.parametrize("lookahead", [0, 1])
+def test_eviction_heavy_small_cache(lookahead):
+    V, D, n = 5000, 8, 3000                    # several scan tiles, ragged tails (3000 % 256, % 2048)
+    p = Pair(V, D, C=1500, max_ids=4096, lookahead=lookahead)
+    _zipf_steps(p, V, n, 1.05, 21, 10)
+    p.finish(); p.close()
+
+
+def test_ties_in_stamp_break_by_slot():
+    # fill 100 slots in one step (all stamp 1), then need 7 victims among equal stamps
+    p = Pair(V=1000, D=4, C=100, max_ids=256)
+    p.step(np.arange(100), np.zeros((100, 4), np.float32))
+    pr = p.step(np.arange(500, 507), np.ones((7, 4), np.float32))
+    assert pr.evict_slots.tolist() == list(range(7))
+    pr = p.step(np.array([99, 98, 600, 601, 602]), np.ones((5, 4), np.float32))
+    assert pr.evict_slots.tolist() == [7, 8, 9]
+    p.finish(); p.close()
+
+
+def test_multihot_bags():
+    V, D, nb = 20000, 16, 1500
+    p = Pair(V, D, C=4000, max_ids=nb * 20, max_bags=nb)
+    for t in range(6):
+        off = si.bag_offsets(nb, 1, 20, 31, t).numpy()
+        ids = si.zipf_ids(int(off[-1]), 1.1, V, 31, t).numpy()
+        p.step(ids, si.grads(nb, D, 31, t).numpy(), offsets=off)
+    p.finish(); p.close()
+
+
+def test_multihot_with_empty_bags_and_repeats_inside_a_bag():
+    p = Pair(V=50, D=4, C=8, max_ids=64, max_bags=8)
+    off = np.array([0, 0, 3, 3, 7, 8])
+    ids = np.array([4, 4, 9, 1, 4, 30, 30, 2])
+    p.step(ids, si.grads(5, 4, 1, 0).numpy(), offsets=off)
+    p.finish(); p.close()
+
+
+def test_capacity_zero_is_the_host_strategy():
+    V, D, n = 3000, 8, 1000
+    p = Pair(V, D, C=0, max_ids=1024)
+    _zipf_steps(p, V, n, 1.1, 41, 4)
+    p.finish(); p.close()
+
+
+def test_degenerate_batches():
+    p = Pair(V=100, D=4, C=16, max_ids=512)
+    g = lambda n, t: si.grads(n, 4, 77, t).numpy()
+    p.step(np.zeros(0, np.int64), np.zeros((0, 4), np.float32))     # empty batch
+    p.step(np.full(300, 42), g(300, 1))                              # one id, many times
+    p.step(np.array([-5, 100, 10 ** 12, -1]), g(4, 2))               # only out-of-range ids
+    p.step(np.array([3, -1, 3, 200, 7]), g(5, 3))                    # mixed
+    p.step(np.arange(100)[::-1].copy(), g(100, 4))                   # all distinct, > C
+    p.step(np.arange(512) % 100, g(512, 5))                          # n_ids == max_ids
+    p.finish(); p.close()
+
+
+def test_medium_zipf_many_tiles():
+    # 16384 x 39 positions like the second configuration, vocabulary shrunk so that the oracle
+    # and its table stay small; cache small enough to evict from the third step on
+    V, D, n = 10 ** 6, 16, 16384 * 39
+    p = Pair(V, D, C=200_000, max_ids=n)
+    for t in range(5):
+        ids = si.zipf_ids(n, 1.1, V, 1001, t).numpy()
+        p.step(ids, si.grads(n, D, 1001, t).numpy(), check_state=(t in (0, 4)))
+    p.finish(); p.close()
+
+
+def test_same_stream_for_copies():
+    V, D, n = 4000, 32, 2000
+    p = Pair(V, D, C=1000, max_ids=2048, side_stream=False)
+    _zipf_steps(p, V, n, 1.2, 5, 4)
+    p.finish(); p.close()
+
+
+def test_hot_id_accumulation_stays_in_tolerance():
+    # one id owns ~half of 400k positions: the segment sum has ~2e5 N(0,1) terms per element
+    V, D, n = 1000, 32, 400_000
+    p = Pair(V, D, C=1000, max_ids=n)
+    rng = np.random.default_rng(3)
+    ids = np.where(rng.random(n) < 0.5, 7, rng.integers(0, V, n))
+    p.step(ids, si.grads(n, D, 9, 0).numpy())
+    p.finish(); p.close()
+
+
+def test_index_rebuild_after_many_evictions():
+    # tiny cache, every step evicts almost everything: deleted index entries pile up and the
+    # rebuild path runs many times; state must stay identical to the oracle throughout
+    V, D = 100_000, 4
+    p = Pair(V, D, C=64, max_ids=64)
+    for t in range(60):
+        ids = si.uniform_ids(64, V, 3, t).numpy()
+        p.step(ids, si.grads(64, D, 3, t).numpy(), check_common=False)
+    p.finish(); p.close()
+
+
+def test_call_order_and_argument_errors():
+    import paper_2104_08542_amd as sfc
+    p = Pair(V=100, D=4, C=16, max_ids=32)
+    c = p.cache
+    ids = torch.arange(8, dtype=torch.int64, device="cuda:0")
+    out = torch.empty(8, 4, device="cuda:0")
+    for fn in (lambda: c.lookup(out), lambda: c.backward_update(out), c.fetch_misses):
+        with pytest.raises(sfc.SfcError) as e:
+            fn()
+        assert e.value.code == sfc.SFC_ESTATE
+    with pytest.raises(sfc.SfcError) as e:
+        c.prepare(torch.zeros(33, dtype=torch.int64, device="cuda:0"))
+    assert e.value.code == sfc.SFC_EINVAL
+    c.prepare(ids)
+    with pytest.raises(sfc.SfcError) as e:
+        c.prepare(ids)
+    assert e.value.code == sfc.SFC_ESTATE
+    c.fetch_misses(); c.lookup(out); c.backward_update(out)
+    p.close()
+
+
+def test_step_limit():
+    import paper_2104_08542_amd as sfc
+    p = Pair(V=100, D=4, C=16, max_ids=32, max_steps=3)
+    for t in range(3):
+        p.step(np.arange(5) + t, np.zeros((5, 4), np.float32))
+    with pytest.raises(sfc.SfcError) as e:
+        p.cache.prepare(torch.arange(5, dtype=torch.int64, device="cuda:0"))
+    assert e.value.code == sfc.SFC_ELIMIT
+    p.close()
