@@ -360,7 +360,7 @@ int sfc_fetch_misses(sfc_cache* c) {
 int sfc_lookup(sfc_cache* c, float* d_out) {
   if (!c) return fail(SFC_EINVAL, "null cache");
   if (c->state != FETCHED) return fail(SFC_ESTATE, "sfc_lookup needs sfc_prepare and sfc_fetch_misses first");
-  if (!d_out) return fail(SFC_EINVAL, "null output");
+  if (c->n_bags > 0 && !d_out) return fail(SFC_EINVAL, "null output");
   if ((uintptr_t)d_out & 15) return fail(SFC_EINVAL, "output must be 16-byte aligned");
   hipStream_t s = c->st;
   EventPair ep{};
