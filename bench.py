@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-embedding hot path on one MI355X.
+
+One step = sfc_prepare + sfc_fetch_misses + sfc_lookup + sfc_backward_update over one seeded
+synthetic batch whose ids already sit in HBM.  Prints ONE JSON line: whole-job raw ids/s, the
+roofline of the dominant kernel (hipEvent-timed inside the timed region) and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build is the one-GPU hot path; there is no multi-GPU exchange to run. "
+            "Use --gpus 1.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import sfc_inputs as si
+    import paper_2104_08542_amd as sfc
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = si.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+    D, V, C = w.dim, w.vocab, w.cache_rows
+    R = 4 * D
+
+    t0 = time.time()
+    table = sfc.HostTable(V, D)
+    chunk = max(1, (1 << 26) // D)
+    for r0 in range(0, V, chunk):
+        r1 = min(V, r0 + chunk)
+        table.w_t[r0:r1].copy_(si.table_rows(w.seed, r0, r1, D, dev))
+    table.acc_t.fill_(w.init_acc)
+    log("host table [%d, %d] x2 pinned and filled in %.1fs" % (V, D, time.time() - t0))
+
+    cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lr=w.lr, eps=w.eps, device="cuda:0")
+    out = torch.empty(w.n_bags, D, dtype=torch.float32, device=dev)
+    grads = [w.batch_grads(i, dev) for i in range(4)]
+
+    def run_step(ids, off, g):
+        cache.prepare(ids, off)
+        cache.fetch_misses()
+        cache.lookup(out)
+        cache.backward_update(g)
+
+    # warm-up: fills the cache and reaches the steady-state hit rate
+    t0 = time.time()
+    for t in range(W):
+        ids, off = w.batch_ids(t, dev)
+        run_step(ids, off, grads[t % 4])
+    torch.cuda.synchronize()
+    log("warm-up %d steps in %.1fs" % (W, time.time() - t0))
+
+    batches = [w.batch_ids(W + t, dev) for t in range(K)]
+    n_ids_total = sum(b[0].numel() for b in batches)
+    torch.cuda.synchronize()
+
+    # pass 1: whole-job throughput, no instrumentation inside the timed region
+    t_start = time.perf_counter()
+    for t in range(K):
+        run_step(batches[t][0], batches[t][1], grads[t % 4])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+
+    # pass 2: K more steps with hipEvents around every call and the two backward kernels
+    # (same batches' successors, so the cache keeps evolving as in training)
+    batches2 = [w.batch_ids(W + K + t, dev) for t in range(K)]
+    torch.cuda.synchronize()
+    sfc.sfc_profile_enable(cache.h, True)
+    agg = dict(n_unique=0, n_hit=0, n_miss=0, n_evict=0, n_bypass=0, h2d_bytes=0, d2h_bytes=0)
+    ns = 0
+    for t in range(K):
+        run_step(batches2[t][0], batches2[t][1], grads[t % 4])
+        if t % max(1, K // 10) == 0:          # sample the device counters (each read synchronises)
+            st = cache.stats()
+            for k in agg:
+                agg[k] += st[k]
+            ns += 1
+    prof = sfc.sfc_profile_read(cache.h)
+    sfc.sfc_profile_enable(cache.h, False)
+    ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
+    avg = {k: v / ns for k, v in agg.items()}
+    N = n_ids_total / K
+    U = avg["n_unique"]
+    bags = w.n_bags
+
+    # algorithmic bytes per launch (rows counted once per unique id)
+    b_lookup = 4 * N + 4 * U + U * R + bags * R + (0 if w.one_hot else 8 * bags)
+    b_segsum = bags * R + 4 * N + (0 if w.one_hot else 8 * bags)
+    b_adagrad = 4 * U + 4 * U * R
+    kernels = {
+        "k_lookup": (b_lookup, ms["lookup"]),
+        "k_segment_sum": (b_segsum, ms["k_segment_sum"]),
+        "k_adagrad": (b_adagrad, ms["k_adagrad"]),
+    }
+    dom = max(kernels, key=lambda k: kernels[k][1])
+    ach = kernels[dom][0] / (kernels[dom][1] * 1e-3) / 1e9
+    pair_bytes = b_lookup + b_segsum + b_adagrad
+    pair_ms = ms["lookup"] + ms["backward_update"]
+    link_ms = ms["fetch_misses"]
+
+    result = {
+        "metric": "raw ids/sec through prepare+fetch_misses+lookup+backward_update",
+        "value": n_ids_total / wall,
+        "unit": "ids/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": wall / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": "%s: batch %d x %d fields%s, ids %s over %.0e rows, dim %d fp32, cache %d rows LRU, Adagrad"
+                        % (w.name, w.batch, w.fields,
+                           "" if w.one_hot else " (bags of %d-%d ids)" % (w.bag_lo, w.bag_hi),
+                           "uniform" if w.zipf_s is None else "Zipf(s=%.2f)" % w.zipf_s, V, D, C),
+            "ids_per_step": N, "unique_per_step": U,
+            "hit_rate": avg["n_hit"] / max(1.0, avg["n_hit"] + avg["n_miss"]),
+            "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
+            "bypass_per_step": avg["n_bypass"],
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": None,
+            "algorithmic_bytes_per_launch": kernels[dom][0], "avg_ms": kernels[dom][1],
+        },
+        "kernels": {k: {"algorithmic_bytes": v[0], "avg_ms": v[1],
+                        "GB/s": (v[0] / (v[1] * 1e-3) / 1e9 if v[1] else None)} for k, v in kernels.items()},
+        "lookup_plus_update": {"algorithmic_bytes": pair_bytes, "avg_ms": pair_ms,
+                               "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
+                               "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "call_ms": {k: ms[k] for k in ("prepare", "fetch_misses", "lookup", "backward_update")},
+        "host_link": {"h2d_bytes_per_step": avg["h2d_bytes"], "d2h_bytes_per_step": avg["d2h_bytes"],
+                      "GB/s": ((avg["h2d_bytes"] + avg["d2h_bytes"]) / (link_ms * 1e-3) / 1e9
+                               if link_ms else None)},
+    }
+
+    if not args.no_cpu_baseline:
+        # The oracle as it stands, single-threaded, on the same workload: first steps of the same
+        # seeded batch sequence from a cold oracle cache, run in place on the host table after
+        # the GPU run has been flushed into it (values differ from step 0, the work does not).
+        from oracle import Oracle
+        cache.flush()
+        orc = Oracle(C, D, table.w, table.acc, lr=w.lr, eps=w.eps)
+        done_ids, steps_done, cpu_t = 0, 0, 0.0
+        while cpu_t < args.cpu_seconds and steps_done < 50:
+            ids, off = w.batch_ids(steps_done, dev)
+            g = grads[steps_done % 4].cpu().numpy()
+            ids_np = ids.cpu().numpy()
+            off_np = None if off is None else off.cpu().numpy()
+            t1 = time.perf_counter()
+            orc.step(ids_np, g, off_np)
+            cpu_t += time.perf_counter() - t1
+            done_ids += ids_np.size
+            steps_done += 1
+            log("oracle step %d: %.2fs so far" % (steps_done, cpu_t))
+        result["cpu_baseline"] = {
+            "value": done_ids / cpu_t, "unit": "ids/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d steps of the same seeded batch sequence from a cold cache, "
+                      "%.1f s of single-thread oracle time (host has %d logical CPUs)"
+                      % (steps_done, cpu_t, os.cpu_count()),
+        }
+    cache.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -81,9 +81,10 @@ void* sfc_host_alloc(int64_t bytes);
 void sfc_host_free(void* p);
 
 /*
- * Create an empty cache (MixCache: "allocates a cache buffer in HBM ... which stores the working
- * embedding parameters", Host-Manager section).  The manager state (id -> slot index, per-slot
- * recency stamp) lives in HBM too.  Allocates all device memory the later calls use.
+ * Create an empty cache: the per-GPU cache buffer of MixCache (Host-Manager section), a fixed
+ * number of row slots in HBM holding the working rows and their optimizer state.  The manager
+ * state (id -> slot index, per-slot recency stamp) lives in HBM too.  Allocates all device
+ * memory the later calls use.
  */
 int sfc_cache_create(const sfc_config* cfg, sfc_cache** out);
 void sfc_cache_destroy(sfc_cache* c);
@@ -158,10 +159,11 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out);
 int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h_rows, float* h_acc);
 
 /*
- * Per-call device timing.  When enabled, hipEvents bracket the kernels of each of the four step
- * calls on the stream they run on.  sfc_profile_read waits for the streams and returns, for
- * which = 0..3 (prepare, fetch_misses, lookup, backward_update), the summed milliseconds and the
- * number of calls since the last read.
+ * Device timing.  When enabled, hipEvents bracket the work of each step call on the stream it
+ * runs on, and the two kernels inside sfc_backward_update separately.  sfc_profile_read waits
+ * for the streams and returns, for which = 0..5 (prepare, fetch_misses, lookup, backward_update,
+ * the segment-sum kernel, the Adagrad kernel), the summed milliseconds and the number of
+ * launches since the last read of that entry.
  */
 int sfc_profile_enable(sfc_cache* c, int32_t on);
 int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);

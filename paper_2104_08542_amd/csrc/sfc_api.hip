@@ -36,7 +36,7 @@ int fail(int code, const char* what, hipError_t e = hipSuccess) {
   } while (0)
 
 enum State { IDLE = 0, PREPARED = 1, FETCHED = 2 };
-enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_N = 4 };
+enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEGSUM = 4, P_ADAGRAD = 5, P_N = 6 };
 
 struct EventPair { hipEvent_t a, b; };
 
@@ -75,8 +75,8 @@ struct sfc_cache {
   // profiling
   bool prof = false;
   std::vector<EventPair> pending[P_N], spare;
-  double ms_sum[P_N] = {0, 0, 0, 0};
-  int64_t calls[P_N] = {0, 0, 0, 0};
+  double ms_sum[P_N] = {};
+  int64_t calls[P_N] = {};
 };
 
 namespace {
@@ -412,11 +412,16 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   hipStream_t s = c->st;
   EventPair ep{};
   int rc;
+  EventPair e1{}, e2{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
+  if ((rc = prof_begin(c, P_SEGSUM, s, &e1))) return rc;
   accumulate(c, d_grad);
+  if ((rc = prof_end(c, P_SEGSUM, s, &e1))) return rc;
+  if ((rc = prof_begin(c, P_ADAGRAD, s, &e2))) return rc;
   const int g = grid_for(c->n_ids * c->d4, 256, kGridCap);
   hipLaunchKernelGGL(k_adagrad, dim3(g), dim3(256), 0, s, c->g64, c->d_slot, (float4*)c->cw,
                      (float4*)c->ca, c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
+  if ((rc = prof_end(c, P_ADAGRAD, s, &e2))) return rc;
   hipLaunchKernelGGL(k_writeback_bypass, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0,
                      s, c->d_miss, c->d_unique, c->d_slot, (const float4*)c->cw,
                      (const float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
