@@ -110,16 +110,14 @@ def main():
 
     # algorithmic bytes per launch (rows counted once per unique id)
     b_lookup = 4 * N + 4 * U + U * R + bags * R + (0 if w.one_hot else 8 * bags)
-    b_segsum = bags * R + 4 * N + (0 if w.one_hot else 8 * bags)
-    b_adagrad = 4 * U + 4 * U * R
+    b_update = bags * R + 4 * N + 4 * U + 4 * U * R
     kernels = {
         "k_lookup": (b_lookup, ms["lookup"]),
-        "k_segment_sum": (b_segsum, ms["k_segment_sum"]),
-        "k_adagrad": (b_adagrad, ms["k_adagrad"]),
+        "k_seg_update": (b_update, ms["k_seg_update"]),
     }
     dom = max(kernels, key=lambda k: kernels[k][1])
     ach = kernels[dom][0] / (kernels[dom][1] * 1e-3) / 1e9
-    pair_bytes = b_lookup + b_segsum + b_adagrad
+    pair_bytes = b_lookup + b_update
     pair_ms = ms["lookup"] + ms["backward_update"]
     link_ms = ms["fetch_misses"]
 

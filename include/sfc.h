@@ -49,7 +49,7 @@ typedef struct sfc_cache sfc_cache; /* opaque */
 
 typedef struct {
   int64_t capacity_rows;      /* C >= 0: row slots of the cache buffer (0 = every row bypasses) */
-  int32_t dim;                /* D: floats per row, multiple of 4, <= 1024 */
+  int32_t dim;                /* D: floats per row, multiple of 4, <= 256 */
   int32_t policy;             /* SFC_POLICY_LRU_BATCH */
   int64_t max_ids_per_batch;  /* upper bound on n_ids of any step; sizes scratch and bypass rows */
   int64_t max_bags_per_batch; /* upper bound on n_bags of any step */
@@ -160,10 +160,10 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
 
 /*
  * Device timing.  When enabled, hipEvents bracket the work of each step call on the stream it
- * runs on, and the two kernels inside sfc_backward_update separately.  sfc_profile_read waits
- * for the streams and returns, for which = 0..5 (prepare, fetch_misses, lookup, backward_update,
- * the segment-sum kernel, the Adagrad kernel), the summed milliseconds and the number of
- * launches since the last read of that entry.
+ * runs on, and the fused segment-sum + Adagrad kernels inside sfc_backward_update separately.
+ * sfc_profile_read waits for the streams and returns, for which = 0..4 (prepare, fetch_misses,
+ * lookup, backward_update, segment-sum+Adagrad kernels), the summed milliseconds and the number
+ * of launches since the last read of that entry.
  */
 int sfc_profile_enable(sfc_cache* c, int32_t on);
 int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);

@@ -36,7 +36,7 @@ int fail(int code, const char* what, hipError_t e = hipSuccess) {
   } while (0)
 
 enum State { IDLE = 0, PREPARED = 1, FETCHED = 2 };
-enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEGSUM = 4, P_ADAGRAD = 5, P_N = 6 };
+enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEGSUM = 4, P_N = 5 };
 
 struct EventPair { hipEvent_t a, b; };
 
@@ -61,7 +61,13 @@ struct sfc_cache {
   int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
   int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
   int* victim_slot = nullptr; int64_t* victim_id = nullptr;  // [max_ids]
-  double* g64 = nullptr;                        // [max_ids, D] fp64 gradient scratch, zero at rest
+  int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
+  int64_t* perm64 = nullptr;                    // [max_ids] positions grouped by virtual id
+  int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
+  int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
+  int* age_mat = nullptr;                       // [kResolveGrid, kAgeBins] hits by age per block
+  double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] block-edge partial sums
+  int seg_B = 0;                                // perm64 entries per block of k_seg_reduce
   Ctr* ctr = nullptr;
   float *d_hw = nullptr, *d_ha = nullptr;       // device view of the Host table
   std::vector<void*> allocs;
@@ -136,6 +142,22 @@ int prof_collect(sfc_cache* c) {
   return SFC_OK;
 }
 
+// Segment-sum over perm64, then either the Adagrad update (EMIT = false) or the common-gradient
+// matrix (EMIT = true).  Two kernels: per-block runs, then the block-edge partials.
+template <bool EMIT>
+void seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
+  const int n = (int)c->n_ids;
+  if (n <= 0) return;
+  const int nblk = (n + c->seg_B - 1) / c->seg_B;
+  hipLaunchKernelGGL(k_seg_reduce<EMIT>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
+                     c->perm64, n, c->D, c->d_slot, (float4*)c->cw, (float4*)c->ca, c->cfg.lr,
+                     c->cfg.eps, (float4*)d_common, c->bp, c->bp_vid);
+  const int64_t threads = (int64_t)2 * nblk * c->d4;
+  hipLaunchKernelGGL(k_seg_finish<EMIT>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                     c->st, c->bp, c->bp_vid, 2 * nblk, c->D, c->d_slot, (float4*)c->cw,
+                     (float4*)c->ca, c->cfg.lr, c->cfg.eps, (float4*)d_common);
+}
+
 constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
 
 }  // namespace
@@ -182,8 +204,8 @@ void sfc_cache_destroy(sfc_cache* c) {
 int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if (!cfg || !out) return fail(SFC_EINVAL, "null config or output pointer");
   *out = nullptr;
-  if (cfg->capacity_rows < 0 || cfg->dim <= 0 || cfg->dim % 4 || cfg->dim > 1024)
-    return fail(SFC_EINVAL, "capacity_rows must be >= 0 and dim a multiple of 4 in [4, 1024]");
+  if (cfg->capacity_rows < 0 || cfg->dim <= 0 || cfg->dim % 4 || cfg->dim > 256)
+    return fail(SFC_EINVAL, "capacity_rows must be >= 0 and dim a multiple of 4 in [4, 256]");
   if (cfg->policy != SFC_POLICY_LRU_BATCH) return fail(SFC_EINVAL, "unknown policy");
   if (cfg->max_ids_per_batch < 1 || cfg->max_bags_per_batch < 1 || cfg->host_rows < 1)
     return fail(SFC_EINVAL, "max_ids_per_batch, max_bags_per_batch and host_rows must be >= 1");
@@ -240,7 +262,18 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->tile_eq, c->C / kPosChunk + 2))) goto bad;
     if ((rc = dalloc(c, &c->victim_slot, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->victim_id, c->max_ids))) goto bad;
-    if ((rc = dalloc(c, &c->g64, c->max_ids * c->D))) goto bad;
+    if ((rc = dalloc(c, &c->cnt, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->perm64, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
+    if ((rc = dalloc(c, &c->age_mat, (int64_t)kResolveGrid * kAgeBins))) goto bad;
+    c->seg_B = seg_geom(c->D).B;
+    {
+      const int64_t nblk = (c->max_ids + c->seg_B - 1) / c->seg_B;
+      if ((rc = dalloc(c, &c->bp, 2 * nblk * c->D))) goto bad;
+      if ((rc = dalloc(c, &c->bp_vid, 2 * nblk))) goto bad;
+    }
     if ((rc = dalloc(c, &c->ctr, 1))) goto bad;
 
     hipStream_t s = c->st;
@@ -251,7 +284,6 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
     fill<int64_t>(s, c->ukeys, hu, kEmpty);
     fill<int>(s, c->uminpos, hu, kIntMax);
-    fill<double>(s, c->g64, c->max_ids * c->D, 0.0);
     Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
     if ((e = hipMemcpyAsync(c->ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&c->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
@@ -295,8 +327,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   // per-step counters that the kernels accumulate into
   hipLaunchKernelGGL(k_fill<int>, dim3(1), dim3(64), 0, s, &c->ctr->n_hit, (int64_t)2, 0);  // n_hit, n_invalid
   if (n > 0) {
-    hipLaunchKernelGGL(k_uniq_insert, dim3((n + 1023) / 1024), dim3(256), 0, s, d_ids, n, c->V,
-                       c->ukeys, c->uminpos, hu, c->hslot, c->ctr);
+    hipLaunchKernelGGL(k_uniq_insert, dim3((n + kUniqChunk - 1) / kUniqChunk), dim3(256), 0, s,
+                       d_ids, n, c->V, c->ukeys, c->uminpos, hu, c->hslot, c->ctr);
     hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uminpos, n,
                        c->blk_cnt);
   }
@@ -306,25 +338,33 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, c->ctr);
   if (n > 0) {
     hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uminpos,
-                       c->ukeys, n, c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot);
-    hipLaunchKernelGGL(k_uniq_inverse, dim3((n + 1023) / 1024), dim3(256), 0, s, c->hslot, c->uvid,
-                       n, d_inverse);
+                       c->ukeys, n, c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt);
+    hipLaunchKernelGGL(k_uniq_inverse, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uvid, n,
+                       d_inverse, c->cnt);
+    if (d_offsets)
+      hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
+                         d_offsets, (int)n_bags, n, c->pos2bag);
   }
-  const int gv = grid_for(n, kVidTile, kGridCap);
-  hipLaunchKernelGGL(k_resolve, dim3(gv), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->ukeys,
+  const int gr = grid_for(n, kVidTile, kResolveGrid);
+  hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->ukeys,
                      c->uminpos, c->index, c->hi, c->stamp, c->hist, c->t, d_slot, c->tile_miss,
-                     c->ctr);
-  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->hist, c->t,
-                     c->cfg.lookahead, (int)c->C, c->hi, c->ctr);
+                     c->cnt, c->tile_cnt, c->age_mat, c->ctr);
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_mat, gr,
+                     c->hist, c->t, c->cfg.lookahead, (int)c->C, c->hi, c->ctr);
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
                      c->ctr);
   hipLaunchKernelGGL(k_victim_scan, dim3(1), dim3(1024), 0, s, c->tile_lt, c->tile_eq, c->ctr);
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
                      c->tile_eq, c->index, c->hi, c->victim_slot, c->victim_id, c->ctr);
-  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->tile_miss,
-                     c->victim_slot, d_slot, d_miss_vids, c->slot_id, c->stamp, c->index, c->hi,
-                     c->t, (int)c->C, c->ctr);
+  const int gv = grid_for(n, kVidTile, kGridCap);
+  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->tile_cnt,
+                     c->cursor, c->tile_miss, c->victim_slot, d_slot, d_miss_vids, c->slot_id,
+                     c->stamp, c->index, c->hi, c->t, (int)c->C, c->ctr);
+  if (n > 0)
+    hipLaunchKernelGGL(k_scatter, dim3(nchunk), dim3(256), 0, s, d_inverse,
+                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor,
+                       c->perm64);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
   HIPCHK(hipEventRecord(c->ev_prepared, s));
@@ -340,13 +380,9 @@ int sfc_fetch_misses(sfc_cache* c) {
   EventPair ep{};
   int rc;
   if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
-  const float4 *cw = (const float4*)c->cw, *ca = (const float4*)c->ca;
-  const int g = grid_for(c->n_ids * c->d4, 256, 1024);
-  hipLaunchKernelGGL(k_writeback_victims, dim3(g), dim3(256), 0, s, c->victim_slot, c->victim_id,
-                     cw, ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
-  hipLaunchKernelGGL(k_fetch_misses, dim3(g), dim3(256), 0, s, c->d_miss, c->d_unique, c->d_slot,
-                     (const float4*)c->d_hw, (const float4*)c->d_ha, (float4*)c->cw,
-                     (float4*)c->ca, c->d4, c->ctr);
+  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0, s,
+                     c->d_miss, c->d_unique, c->d_slot, c->victim_id, (float4*)c->cw,
+                     (float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
   if (s != c->st) {
@@ -380,26 +416,12 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
   return prof_end(c, P_LOOKUP, s, &ep);
 }
 
-static int accumulate(sfc_cache* c, const float* d_grad) {
-  const int64_t total = c->n_bags * c->d4;
-  if (total <= 0) return SFC_OK;
-  if (!c->d_offsets)
-    hipLaunchKernelGGL(k_accum_onehot, dim3((unsigned)((total + 1023) / 1024)), dim3(256), 0, c->st,
-                       (const float4*)d_grad, c->d_inverse, c->g64, total, c->d4);
-  else
-    hipLaunchKernelGGL(k_accum_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->st,
-                       (const float4*)d_grad, c->d_offsets, c->d_inverse, c->g64, total, c->d4);
-  return SFC_OK;
-}
-
 int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (!c) return fail(SFC_EINVAL, "null cache");
   if (c->state == IDLE) return fail(SFC_ESTATE, "sfc_segment_sum needs a preceding sfc_prepare");
   if ((c->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
-  accumulate(c, d_grad);
-  hipLaunchKernelGGL(k_emit_common, dim3(grid_for(c->n_ids * c->d4, 256, kGridCap)), dim3(256), 0,
-                     c->st, c->g64, (float4*)d_common_grad, c->d4, c->ctr);
+  seg_launch<true>(c, d_grad, d_common_grad);
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -410,18 +432,12 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if (c->n_bags > 0 && !d_grad) return fail(SFC_EINVAL, "null gradient");
   if ((uintptr_t)d_grad & 15) return fail(SFC_EINVAL, "gradient must be 16-byte aligned");
   hipStream_t s = c->st;
-  EventPair ep{};
+  EventPair ep{}, e1{};
   int rc;
-  EventPair e1{}, e2{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
   if ((rc = prof_begin(c, P_SEGSUM, s, &e1))) return rc;
-  accumulate(c, d_grad);
+  seg_launch<false>(c, d_grad, nullptr);
   if ((rc = prof_end(c, P_SEGSUM, s, &e1))) return rc;
-  if ((rc = prof_begin(c, P_ADAGRAD, s, &e2))) return rc;
-  const int g = grid_for(c->n_ids * c->d4, 256, kGridCap);
-  hipLaunchKernelGGL(k_adagrad, dim3(g), dim3(256), 0, s, c->g64, c->d_slot, (float4*)c->cw,
-                     (float4*)c->ca, c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
-  if ((rc = prof_end(c, P_ADAGRAD, s, &e2))) return rc;
   hipLaunchKernelGGL(k_writeback_bypass, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0,
                      s, c->d_miss, c->d_unique, c->d_slot, (const float4*)c->cw,
                      (const float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);

@@ -14,39 +14,82 @@ constexpr int kPosChunk = 2048;   // positions (or slots) per block in the scan 
 constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
 
 // ---------------------------------------------------------------------------------------------
-// VSI pass 1: insert every position's id into the batch table (open addressing, linear probing)
-// and keep the smallest position per key.  Remembers the table entry of each position.
-// Hot ids are read-mostly: a position only issues an atomic when the plain load has not yet
-// seen its key / a smaller position, so the hottest key costs loads, not serialised atomics.
+// VSI pass 1: insert every position's id into the batch table (open addressing, linear probing,
+// in HBM) and keep the smallest position per key; remember the table entry of each position.
+//
+// Same-address atomics serialise at the memory side (about 10 ns each on this chip), and the
+// hottest id of a power-law batch owns a fifth of all positions.  So each block first
+// deduplicates its 2048 positions in an LDS table (key -> smallest position in the block) and
+// only the distinct keys of the block go to HBM; there a device-coherent load comes first and
+// the atomic is issued only if the load has not already seen the key / a smaller position.
 // ---------------------------------------------------------------------------------------------
+constexpr int kUniqChunk = 2048;   // positions per block
+constexpr int kLdsTab = 4096;      // LDS table entries per block
+
+template <typename T>
+__device__ __forceinline__ T coherent_load(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__ ids, int n,
                                                       int64_t V, int64_t* ukeys, int* uminpos,
                                                       uint32_t hu, int* __restrict__ hslot,
                                                       Ctr* ctr) {
-  const int base = blockIdx.x * 1024;
+  __shared__ int64_t lkey[kLdsTab];
+  __shared__ int lmin[kLdsTab];     // smallest position of the key in this block; later: its HBM entry
+  for (int i = threadIdx.x; i < kLdsTab; i += 256) { lkey[i] = kEmpty; lmin[i] = kIntMax; }
+  __syncthreads();
+  const int base = blockIdx.x * kUniqChunk;
+  int ls[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = base + i * 256 + (int)threadIdx.x;
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j * 256 + (int)threadIdx.x;
     bool invalid = false;
+    ls[j] = 0;
     if (p < n) {
       int64_t key = ids[p];
       if (key < 0 || key >= V) { key = kNullKey; invalid = true; }
-      uint32_t h = bucket_of(key, hu);
-      for (uint32_t probes = 0; probes < hu; ++probes) {
-        int64_t k = ukeys[h];
+      uint32_t l = (uint32_t)mix64((uint64_t)key) & (kLdsTab - 1);
+      for (int probes = 0; probes < kLdsTab; ++probes) {
+        const int64_t k = lkey[l];
         if (k == key) break;
         if (k == kEmpty) {
-          int64_t old = (int64_t)atomicCAS((unsigned long long*)&ukeys[h],
-                                           (unsigned long long)kEmpty, (unsigned long long)key);
+          const int64_t old = (int64_t)atomicCAS((unsigned long long*)&lkey[l],
+                                                 (unsigned long long)kEmpty, (unsigned long long)key);
           if (old == kEmpty || old == key) break;
         }
-        h = h + 1 == hu ? 0 : h + 1;
+        l = (l + 1) & (kLdsTab - 1);
       }
-      if (uminpos[h] > p) atomicMin(&uminpos[h], p);
-      hslot[p] = (int)h;
+      if (lmin[l] > p) atomicMin(&lmin[l], p);
+      ls[j] = (int)l;
     }
     const uint64_t b = __ballot(invalid);
     if (b && lane_id() == 0) atomicAdd(&ctr->n_invalid, __popcll(b));
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < kLdsTab; e += 256) {
+    const int64_t key = lkey[e];
+    if (key == kEmpty) continue;
+    uint32_t h = bucket_of(key, hu);
+    for (uint32_t probes = 0; probes < hu; ++probes) {
+      const int64_t k = coherent_load(&ukeys[h]);
+      if (k == key) break;
+      if (k == kEmpty) {
+        const int64_t old = (int64_t)atomicCAS((unsigned long long*)&ukeys[h],
+                                               (unsigned long long)kEmpty, (unsigned long long)key);
+        if (old == kEmpty || old == key) break;
+      }
+      h = h + 1 == hu ? 0 : h + 1;
+    }
+    const int pm = lmin[e];
+    if (coherent_load(&uminpos[h]) > pm) atomicMin(&uminpos[h], pm);
+    lmin[e] = (int)h;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j * 256 + (int)threadIdx.x;
+    if (p < n) hslot[p] = lmin[ls[j]];
   }
 }
 
@@ -92,7 +135,8 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
                                                       const int* __restrict__ blk_off,
                                                       int64_t* __restrict__ unique_ids,
                                                       int* __restrict__ uvid,
-                                                      int* __restrict__ vid_hslot) {
+                                                      int* __restrict__ vid_hslot,
+                                                      int* __restrict__ cnt) {
   __shared__ int smem[20];
   const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
   int hs[8];
@@ -116,20 +160,94 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
       unique_ids[vid] = key == kNullKey ? (int64_t)-1 : key;
       uvid[hs[j]] = vid;
       vid_hslot[vid] = hs[j];
+      cnt[vid] = 0;
       ++vid;
     }
   }
 }
 
-// VSI pass 4: virtual id of every position.
+// VSI pass 4: virtual id of every position, and cnt[v] = number of positions of virtual id v.
+// Virtual ids are handed out in order of first appearance, so the frequent ids of a power-law
+// batch are (nearly all) among the lowest ones: those are counted in an LDS histogram per block
+// and flushed with one coalesced atomic per bin; the rest go to HBM atomics on distinct words.
+constexpr int kHotBins = 8192;
+
 __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hslot,
                                                        const int* __restrict__ uvid, int n,
-                                                       int* __restrict__ inverse) {
-  const int base = blockIdx.x * 1024;
+                                                       int* __restrict__ inverse, int* cnt) {
+  __shared__ int lh[kHotBins];
+  for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kPosChunk;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = base + i * 256 + (int)threadIdx.x;
-    if (p < n) inverse[p] = uvid[hslot[p]];
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j * 256 + (int)threadIdx.x;
+    if (p < n) {
+      const int v = uvid[hslot[p]];
+      inverse[p] = v;
+      if (v < kHotBins) atomicAdd(&lh[v], 1);
+      else atomicAdd(&cnt[v], 1);
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < kHotBins; b += 256) {
+    const int c = lh[b];
+    if (c) atomicAdd(&cnt[b], c);
+  }
+}
+
+// Multi-hot input: bag index of every position.
+__global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ offsets, int n_bags,
+                                                  int n, int* __restrict__ pos2bag) {
+  const int b = blockIdx.x * 256 + (int)threadIdx.x;
+  if (b >= n_bags) return;
+  int64_t lo = offsets[b], hi = offsets[b + 1];
+  if (lo < 0) lo = 0;
+  if (hi > n) hi = n;            // malformed offsets cannot write outside the buffer
+  for (int64_t q = lo; q < hi; ++q) pos2bag[q] = b;
+}
+
+// Grouping of positions by virtual id (counting sort): perm64[cursor[v]++] = (v << 32) | payload,
+// payload = position (one-hot) or bag index (multi-hot).  cursor[v] starts at the exclusive scan
+// of cnt.  Same LDS treatment of the low virtual ids as above; an id that occurs once needs no
+// atomic at all.  The order inside a group is the order in which the atomics land.
+__global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse,
+                                                  const int* __restrict__ pos2bag, int n,
+                                                  const int* __restrict__ cnt, int* cursor,
+                                                  int64_t* __restrict__ perm64) {
+  __shared__ int lh[kHotBins];
+  for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kPosChunk;
+  int vv[8], rr[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j * 256 + (int)threadIdx.x;
+    vv[j] = -1;
+    if (p < n) {
+      const int v = inverse[p];
+      if (v < kHotBins) {
+        vv[j] = v;
+        rr[j] = atomicAdd(&lh[v], 1);
+      } else {
+        const int64_t e = ((int64_t)v << 32) | (uint32_t)(pos2bag ? pos2bag[p] : p);
+        const int dst = cnt[v] == 1 ? cursor[v] : atomicAdd(&cursor[v], 1);
+        perm64[dst] = e;
+      }
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < kHotBins; b += 256) {
+    const int c = lh[b];
+    if (c) lh[b] = atomicAdd(&cursor[b], c);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (vv[j] >= 0) {
+      const int p = base + j * 256 + (int)threadIdx.x;
+      perm64[lh[vv[j]] + rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)(pos2bag ? pos2bag[p] : p);
+    }
   }
 }
 
@@ -198,27 +316,41 @@ __global__ __launch_bounds__(256) void k_index_reinsert(IdxEntry* index, uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Resolve: each unique id against the index.  Hits get their slot and the current stamp; the
-// recency histogram hist[stamp] = #slots with that stamp is kept exact.  Also returns the batch
-// table entries of this step to the empty state, so no per-step clear of that table is needed.
+// Resolve: each unique id against the index.  Hits get their slot and the current stamp.  The
+// recency histogram hist[stamp] = #slots with that stamp must stay exact; stamps of hits cluster
+// on the last few steps, i.e. on a few words of hist, so each block tallies its hits by age
+// (t - old stamp) in LDS and stores the tally as one row of age_mat; the plan kernel adds the
+// rows up.  Only ages beyond the LDS range use an atomic on hist.  Bin 0 of a row counts the
+// block's hits.  Also returns the batch-table entries of this step to the empty state, so that
+// table never needs a per-step clear, and sums cnt per tile for the segment offsets.
 // ---------------------------------------------------------------------------------------------
+constexpr int kAgeBins = 1024;
+constexpr int kResolveGrid = 128;   // rows of age_mat
+
 __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
                                                   const int* __restrict__ vid_hslot,
                                                   int64_t* ukeys, int* uminpos,
                                                   const IdxEntry* __restrict__ index, uint32_t hi,
                                                   int* stamp, int* hist, int t,
                                                   int* __restrict__ slot_out,
-                                                  int* __restrict__ tile_miss, Ctr* ctr) {
+                                                  int* __restrict__ tile_miss,
+                                                  const int* __restrict__ cnt,
+                                                  int* __restrict__ tile_cnt,
+                                                  int* __restrict__ age_mat, Ctr* ctr) {
   __shared__ int smem[20];
+  __shared__ int lage[kAgeBins];
+  for (int i = threadIdx.x; i < kAgeBins; i += 256) lage[i] = 0;
+  __syncthreads();
   const int U = ctr->U;
   for (int tile = blockIdx.x; tile * kVidTile < U; tile += gridDim.x) {
     const int v = tile * kVidTile + (int)threadIdx.x;
     bool hit = false, miss = false;
-    int old = 0;
+    int age = 0, c = 0;
     if (v < U) {
       const int h = vid_hslot[v];
       ukeys[h] = kEmpty;
       uminpos[h] = kIntMax;
+      c = cnt[v];
       const int64_t id = unique_ids[v];
       if (id < 0) {
         slot_out[v] = -1;
@@ -226,31 +358,29 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
         const int s = index_find(index, hi, id, nullptr, ctr);
         if (s >= 0) {
           slot_out[v] = s;
-          old = stamp[s];
+          const int old = stamp[s];
           stamp[s] = t;
+          age = t - old;
           hit = true;
+          if (age >= kAgeBins) atomicSub(&hist[old], 1);
         } else {
           slot_out[v] = kMissMark;
           miss = true;
         }
       }
     }
-    // hist[old] -= 1 per hit, one atomic per distinct old stamp in the wavefront
-    uint64_t m = __ballot(hit);
-    while (m) {
-      const int leader = __ffsll((unsigned long long)m) - 1;
-      const int lo = __shfl(old, leader, kWave);
-      const uint64_t same = __ballot(hit && old == lo);
-      if (lane_id() == leader) atomicSub(&hist[lo], __popcll(same));
-      m &= ~same;
-    }
+    // most hits were last used one step ago: count those per wavefront, the rest one by one
+    const uint64_t m1 = __ballot(hit && age == 1);
+    if (m1 && lane_id() == 0) atomicAdd(&lage[1], __popcll(m1));
+    if (hit && age > 1 && age < kAgeBins) atomicAdd(&lage[age], 1);
+    const uint64_t mh = __ballot(hit);
+    if (mh && lane_id() == 0) atomicAdd(&lage[0], __popcll(mh));
     const int nmiss = block_sum(miss ? 1 : 0, smem);
-    const int nhit = block_sum(hit ? 1 : 0, smem);
-    if (threadIdx.x == 0) {
-      tile_miss[tile] = nmiss;
-      if (nhit) { atomicAdd(&ctr->n_hit, nhit); atomicAdd(&hist[t], nhit); }
-    }
+    const int csum = block_sum(c, smem);
+    if (threadIdx.x == 0) { tile_miss[tile] = nmiss; tile_cnt[tile] = csum; }
   }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kAgeBins; i += 256) age_mat[blockIdx.x * kAgeBins + i] = lage[i];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -258,8 +388,11 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
 // the recency histogram: need = M - free; T is the stamp at which the running count of
 // evictable slots (stamp < limit, oldest first) passes need; r of the slots stamped T go too.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* hist, int t, int lookahead,
-                                               int C, uint32_t hi, Ctr* ctr) {
+__global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
+                                               const int* __restrict__ age_mat, int age_rows,
+                                               int* hist, int t, int lookahead, int C, uint32_t hi,
+                                               Ctr* ctr) {
+  static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
   __shared__ int s_found;
   // every thread reads the counters here; thread 0 overwrites them only after the last barrier
@@ -267,6 +400,15 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* hist, int t,
   const int f = ctr->f;
   const int oldest = ctr->oldest;
   const int ntiles = (U + kVidTile - 1) / kVidTile;
+  // hits by age: thread a owns age a.  hist[t] gains the hits, hist[t - a] loses its share.
+  {
+    const int a = (int)threadIdx.x;
+    int sum = 0;
+    for (int g = 0; g < age_rows; ++g) sum += age_mat[g * kAgeBins + a];
+    if (a == 0) { hist[t] += sum; ctr->n_hit = sum; }
+    else if (sum) hist[t - a] -= sum;
+  }
+  __syncthreads();
   int carry = 0;
   for (int b = 0; b < ntiles; b += 1024) {
     const int i = b + (int)threadIdx.x;
@@ -277,6 +419,15 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* hist, int t,
     carry += tot;
   }
   const int M = carry;
+  carry = 0;
+  for (int b = 0; b < ntiles; b += 1024) {
+    const int i = b + (int)threadIdx.x;
+    const int x = i < ntiles ? tile_cnt[i] : 0;
+    int tot;
+    const int e = block_excl_scan(x, tot, smem);
+    if (i < ntiles) tile_cnt[i] = carry + e;
+    carry += tot;
+  }
   const int free_slots = C - f;
   const int need = M - free_slots;
   const int limit = t - lookahead;       // candidates have stamp < limit
@@ -427,6 +578,9 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
 // watermark up, then transient bypass rows C + j.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict__ unique_ids,
+                                                        const int* __restrict__ cnt,
+                                                        const int* __restrict__ tile_coff,
+                                                        int* __restrict__ cursor,
                                                         const int* __restrict__ tile_moff,
                                                         const int* __restrict__ victim_slot,
                                                         int* __restrict__ slot_out,
@@ -441,6 +595,9 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
     const int v = tile * kVidTile + (int)threadIdx.x;
     const bool miss = v < U && slot_out[v] == kMissMark;
     int tot;
+    // start of the group of virtual id v in perm64 = exclusive scan of cnt
+    const int off = block_excl_scan(v < U ? cnt[v] : 0, tot, smem) + tile_coff[tile];
+    if (v < U) cursor[v] = off;
     const int i = block_excl_scan(miss ? 1 : 0, tot, smem) + tile_moff[tile];
     if (miss) {
       miss_vids[i] = v;

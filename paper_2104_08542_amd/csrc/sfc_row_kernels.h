@@ -3,7 +3,6 @@
 // consecutive chunks, so a wavefront moves 1 KiB of contiguous output per instruction and a
 // 128-byte row (D = 32) is one request of 8 lanes.
 #pragma once
-#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 #include "sfc_device.h"
 
 namespace sfc {
@@ -21,40 +20,35 @@ __device__ __forceinline__ void st_stream(float4* p, float4 v) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Host link (Algorithm 1 lines 5-6).  The Host table is pinned, device-mapped memory; the
-// kernels read / write it directly, 16 bytes per lane, rows contiguous.
+// Host link (Algorithm 1 lines 5-6).  The Host table is pinned, device-mapped memory; the kernel
+// reads / writes it directly, 16 bytes per lane, rows contiguous.  The k-th miss takes the slot
+// of the k-th victim (both lists are in ascending order of the assignment), so one thread group
+// does both directions for that slot: it loads the victim's row from HBM and the missed row
+// from Host, then stores each on the other side.  Reads and writes cross the link at the same
+// time instead of one after the other.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_writeback_victims(const int* __restrict__ victim_slot,
-                                                            const int64_t* __restrict__ victim_id,
-                                                            const float4* __restrict__ cw,
-                                                            const float4* __restrict__ ca,
-                                                            float4* __restrict__ hw,
-                                                            float4* __restrict__ ha, int d4,
-                                                            const Ctr* ctr) {
-  const int64_t total = (int64_t)ctr->K * d4;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int k = (int)(i / d4), c = (int)(i % d4);
-    const int64_t src = (int64_t)victim_slot[k] * d4 + c, dst = victim_id[k] * d4 + c;
-    hw[dst] = cw[src];
-    ha[dst] = ca[src];
-  }
-}
-
-__global__ __launch_bounds__(256) void k_fetch_misses(const int* __restrict__ miss_vids,
-                                                       const int64_t* __restrict__ unique_ids,
-                                                       const int* __restrict__ slot,
-                                                       const float4* __restrict__ hw,
-                                                       const float4* __restrict__ ha,
-                                                       float4* __restrict__ cw,
-                                                       float4* __restrict__ ca, int d4,
-                                                       const Ctr* ctr) {
+__global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_vids,
+                                                    const int64_t* __restrict__ unique_ids,
+                                                    const int* __restrict__ slot,
+                                                    const int64_t* __restrict__ victim_id,
+                                                    float4* __restrict__ cw, float4* __restrict__ ca,
+                                                    float4* __restrict__ hw, float4* __restrict__ ha,
+                                                    int d4, const Ctr* ctr) {
+  const int K = ctr->K;
   const int64_t total = (int64_t)ctr->M * d4;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int k = (int)(i / d4), c = (int)(i % d4);
     const int v = miss_vids[k];
     const int64_t src = unique_ids[v] * d4 + c, dst = (int64_t)slot[v] * d4 + c;
-    cw[dst] = hw[src];
-    ca[dst] = ha[src];
+    const float4 nw = hw[src], na = ha[src];
+    if (k < K) {
+      const int64_t back = victim_id[k] * d4 + c;
+      const float4 ow = cw[dst], oa = ca[dst];
+      hw[back] = ow;
+      ha[back] = oa;
+    }
+    cw[dst] = nw;
+    ca[dst] = na;
   }
 }
 
@@ -138,84 +132,234 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Gradient segment-sum (GPU-Worker / Backward): common[v] = sum of grad rows whose position has
-// virtual id v, accumulated in fp64 in a [U, D] scratch that is all zero between uses.
+// Gradient segment-sum fused with the sparse Adagrad update (GPU-Worker / Backward; Algorithm 1
+// line 14).  Input: perm64, the batch's positions grouped by virtual id, entry = (vid << 32) |
+// row of grad.  A block takes B consecutive entries (B * D = 8192 floats, 32 KiB):
+//   1. gathers their grad rows into LDS, all loads in flight at once;
+//   2. splits the B rows into ranges of 32; thread (range, column) sums runs of equal vid in
+//      fp64.  A run that begins and ends inside the range is complete: its sum replaces the
+//      run's first row in LDS.  A run cut by a range edge leaves an fp64 partial;
+//   3. the first D threads chain the partials across ranges; runs closed inside the block are
+//      complete as well, runs cut by the block edge go to bp[block][0 = head, 1 = tail] in HBM;
+//   4. complete runs are compacted and each gets its Adagrad update (or is emitted as a row of
+//      the common-gradient matrix), D/4 lanes per row.
+// k_seg_finish then chains the block-edge partials of the few long groups.  No atomics, and
+// the summation tree depends only on perm64.
+// A whole-range (whole-block) run stores its sum in the head slot and a zero in the tail slot
+// under the same vid, so equal vids are always adjacent in the partial lists.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void add4(double* dst, float4 g) {
-  unsafeAtomicAdd(dst + 0, (double)g.x);
-  unsafeAtomicAdd(dst + 1, (double)g.y);
-  unsafeAtomicAdd(dst + 2, (double)g.z);
-  unsafeAtomicAdd(dst + 3, (double)g.w);
+constexpr int kSegRows = 32;        // rows per range
+constexpr int kSegFloats = 8192;    // floats of grad per block in LDS
+
+struct SegGeom { int ranges, B; };
+__host__ __device__ inline SegGeom seg_geom(int D) {
+  int r = 256 / D;
+  if (r < 1) r = 1;
+  if (r > 16) r = 16;
+  SegGeom g; g.ranges = r; g.B = r * kSegRows;
+  return g;
 }
 
-__global__ __launch_bounds__(256) void k_accum_onehot(const float4* __restrict__ grad,
-                                                       const int* __restrict__ inverse,
-                                                       double* g64, int64_t total, int d4) {
-  const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int64_t i = base + k * 256;
-    if (i < total) {
-      const int b = (int)(i / d4), c = (int)(i % d4);
-      const float4 g = ld_stream(&grad[i]);
-      add4(g64 + ((int64_t)inverse[b] * d4 + c) * 4, g);
-    }
-  }
-}
-
-__global__ __launch_bounds__(256) void k_accum_bags(const float4* __restrict__ grad,
-                                                     const int64_t* __restrict__ offsets,
-                                                     const int* __restrict__ inverse, double* g64,
-                                                     int64_t total, int d4) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int64_t b = i / d4;
-  const int c = (int)(i % d4);
-  const float4 g = ld_stream(&grad[i]);
-  for (int64_t q = offsets[b], e = offsets[b + 1]; q < e; ++q)
-    add4(g64 + ((int64_t)inverse[q] * d4 + c) * 4, g);
-}
-
-// common_grad[v] = (float) g64[v]; the scratch returns to zero.
-__global__ __launch_bounds__(256) void k_emit_common(double* g64, float4* __restrict__ common,
-                                                      int d4, const Ctr* ctr) {
-  const int64_t total = (int64_t)ctr->U * d4;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    double4* p = reinterpret_cast<double4*>(g64) + i;
-    const double4 g = *p;
-    *p = make_double4(0., 0., 0., 0.);
-    common[i] = make_float4((float)g.x, (float)g.y, (float)g.z, (float)g.w);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Sparse Adagrad (Algorithm 1 line 14), once per unique row:
-//   acc += g*g ; w -= lr * g / (sqrt(acc) + eps)
-// ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void adagrad1(float& w, float& a, float g, float lr, float eps) {
   a = a + g * g;
   w = w - lr * g / (sqrtf(a) + eps);
 }
+__device__ __forceinline__ void adagrad4(float4* cw, float4* ca, int64_t r, float4 g, float lr,
+                                         float eps) {
+  float4 w = cw[r], a = ca[r];
+  adagrad1(w.x, a.x, g.x, lr, eps);
+  adagrad1(w.y, a.y, g.y, lr, eps);
+  adagrad1(w.z, a.z, g.z, lr, eps);
+  adagrad1(w.w, a.w, g.w, lr, eps);
+  cw[r] = w;
+  ca[r] = a;
+}
 
-__global__ __launch_bounds__(256) void k_adagrad(double* g64, const int* __restrict__ slot,
-                                                  float4* __restrict__ cw, float4* __restrict__ ca,
-                                                  float lr, float eps, int d4, const Ctr* ctr) {
-  const int64_t total = (int64_t)ctr->U * d4;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int v = (int)(i / d4), c = (int)(i % d4);
-    double4* p = reinterpret_cast<double4*>(g64) + i;
-    const double4 gd = *p;
-    *p = make_double4(0., 0., 0., 0.);
+template <bool EMIT>
+__global__ __launch_bounds__(256) void k_seg_reduce(const float4* __restrict__ grad,
+                                                     const int64_t* __restrict__ perm64, int n,
+                                                     int D, const int* __restrict__ slot,
+                                                     float4* __restrict__ cw,
+                                                     float4* __restrict__ ca, float lr, float eps,
+                                                     float4* __restrict__ common,
+                                                     double* __restrict__ bp,
+                                                     int* __restrict__ bp_vid) {
+  __shared__ float tile[kSegFloats];            // [B][D] grad rows; later the complete sums
+  __shared__ double part[2 * 256];              // [ranges][2][D] range-edge partials (ranges*D <= 256)
+  __shared__ int lvid[16 * kSegRows + 2];       // vid of entries e0-1 .. e0+B
+  __shared__ int lrow[16 * kSegRows];           // grad row of each entry
+  __shared__ int pvid[32], pstart[32];          // per partial slot: vid (-1 = none), first row
+  __shared__ int head[16 * kSegRows];           // 1 = complete run starts at this row; later: list
+  __shared__ int smem[20];
+  const SegGeom g = seg_geom(D);
+  const int B = g.B, ranges = g.ranges, d4 = D / 4;
+  const int tid = (int)threadIdx.x;
+  const int64_t e0 = (int64_t)blockIdx.x * B;
+
+  for (int i = tid; i < B + 2; i += 256) {
+    const int64_t e = e0 - 1 + i;
+    const int64_t pv = (e >= 0 && e < n) ? perm64[e] : (int64_t)-1;
+    lvid[i] = (int)(pv >> 32);
+    if (i >= 1 && i <= B) { lrow[i - 1] = (int)(uint32_t)pv; head[i - 1] = 0; }
+  }
+  if (tid < 32) pvid[tid] = -1;
+  __syncthreads();
+
+  // 1. gather (B * d4 = 2048 chunks of 16 bytes for the power-of-two dims: 8 per thread)
+  {
+    const int chunks = B * d4;
+    float4* tile4 = reinterpret_cast<float4*>(tile);
+    for (int base = 0; base < chunks; base += 256 * 8) {
+      float4 v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int ch = base + k * 256 + tid;
+        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ch < chunks) {
+          const int i = ch / d4;
+          if (lvid[i + 1] >= 0) v[k] = ld_stream(&grad[(int64_t)lrow[i] * d4 + (ch - i * d4)]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int ch = base + k * 256 + tid;
+        if (ch < chunks) tile4[ch] = v[k];
+      }
+    }
+  }
+  __syncthreads();
+
+  // 2. runs inside each range
+  {
+    const int r = tid / D, c = tid - r * D;
+    if (r < ranges) {
+      const int i0 = r * kSegRows;
+      double acc = 0.0;
+      int cur = lvid[i0 + 1], start = i0;
+      for (int i = i0; i <= i0 + kSegRows; ++i) {
+        const int v = i < i0 + kSegRows ? lvid[i + 1] : -2;     // -2 closes the last run
+        if (v != cur || i == i0 + kSegRows) {
+          if (cur >= 0) {
+            const bool begins = lvid[start] != cur;      // entry before the run differs
+            const bool ends = lvid[i + 1] != cur;        // entry after the run differs
+            if (begins && ends) {
+              tile[start * D + c] = (float)acc;
+              if (c == 0) head[start] = 1;
+            } else if (!begins) {
+              part[(2 * r) * D + c] = acc;
+              if (c == 0) { pvid[2 * r] = cur; pstart[2 * r] = start; }
+              if (!ends) {
+                part[(2 * r + 1) * D + c] = 0.0;
+                if (c == 0) { pvid[2 * r + 1] = cur; pstart[2 * r + 1] = start; }
+              }
+            } else {
+              part[(2 * r + 1) * D + c] = acc;
+              if (c == 0) { pvid[2 * r + 1] = cur; pstart[2 * r + 1] = start; }
+            }
+          }
+          cur = v; start = i; acc = 0.0;
+        }
+        if (i < i0 + kSegRows) acc += (double)tile[i * D + c];
+      }
+    }
+  }
+  __syncthreads();
+
+  // 3. chain the range-edge partials (slot order = range order; odd = tail, even = head)
+  if (tid < D) {
+    const int c = tid;
+    int bv0 = -1, bv1 = -1;
+    double b0 = 0.0, b1 = 0.0;
+    double run = 0.0;
+    int rv = -1, rstart = 0;
+    bool begun = false;
+    const int nslots = 2 * ranges;
+    for (int j = 0; j <= nslots; ++j) {
+      const int v = j < nslots ? pvid[j] : -1;
+      if (v != rv) {
+        if (rv >= 0) {
+          // the run's last slot is j-1: an even (head) slot means it ended inside the block
+          const bool ended = ((j - 1) & 1) == 0;
+          if (begun && ended) {
+            tile[rstart * D + c] = (float)run;
+            if (c == 0) head[rstart] = 1;
+          } else if (!begun) {
+            bv0 = rv; b0 = run;
+            if (!ended) { bv1 = rv; b1 = 0.0; }
+          } else {
+            bv1 = rv; b1 = run;
+          }
+        }
+        rv = v; run = 0.0;
+        if (v >= 0) { begun = (j & 1) == 1; rstart = pstart[j]; }
+      }
+      if (v >= 0) run += part[j * D + c];
+    }
+    const int64_t o = (int64_t)blockIdx.x * 2;
+    bp[(o + 0) * D + c] = b0;
+    bp[(o + 1) * D + c] = b1;
+    if (c == 0) { bp_vid[o] = bv0; bp_vid[o + 1] = bv1; }
+  }
+  __syncthreads();
+
+  // 4. compact the complete runs, then update / emit them D/4 lanes per row
+  int nl = 0;
+  {
+    int f0 = 0, f1 = 0;
+    const int i0 = 2 * tid, i1 = 2 * tid + 1;       // B <= 512
+    if (i0 < B) f0 = head[i0];
+    if (i1 < B) f1 = head[i1];
+    const int k = block_excl_scan(f0 + f1, nl, smem);
+    __syncthreads();                                  // all flags read before the list overwrites them
+    if (f0) head[k] = i0;
+    if (f1) head[k + f0] = i1;
+  }
+  __syncthreads();
+  {
+    const int groups = 256 / d4, gi = tid / d4, c4 = tid - gi * d4;
+    const float4* tile4 = reinterpret_cast<const float4*>(tile);
+    if (gi < groups) {
+      for (int k = gi; k < nl; k += groups) {
+        const int row = head[k];
+        const int v = lvid[row + 1];
+        const float4 gs = tile4[row * d4 + c4];
+        if (EMIT) {
+          common[(int64_t)v * d4 + c4] = gs;
+        } else {
+          const int s = slot[v];
+          if (s >= 0) adagrad4(cw, ca, (int64_t)s * d4 + c4, gs, lr, eps);
+        }
+      }
+    }
+  }
+}
+
+// Chains the block-edge partials: slot j = 2 * block + (0 head | 1 tail); equal vids are adjacent.
+template <bool EMIT>
+__global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ bp,
+                                                     const int* __restrict__ bp_vid, int nslots,
+                                                     int D, const int* __restrict__ slot,
+                                                     float4* __restrict__ cw,
+                                                     float4* __restrict__ ca, float lr, float eps,
+                                                     float4* __restrict__ common) {
+  const int d4 = D / 4;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t j = i / d4;
+  const int c4 = (int)(i - j * d4);
+  if (j >= nslots) return;
+  const int v = bp_vid[j];
+  if (v < 0 || (j > 0 && bp_vid[j - 1] == v)) return;     // not the first slot of its run
+  double s0 = 0., s1 = 0., s2 = 0., s3 = 0.;
+  for (int64_t k = j; k < nslots && bp_vid[k] == v; ++k) {
+    const double4 x = *reinterpret_cast<const double4*>(&bp[k * D + 4 * c4]);
+    s0 += x.x; s1 += x.y; s2 += x.z; s3 += x.w;
+  }
+  const float4 gs = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+  if (EMIT) {
+    common[(int64_t)v * d4 + c4] = gs;
+  } else {
     const int s = slot[v];
-    if (s < 0) continue;
-    const int64_t r = (int64_t)s * d4 + c;
-    float4 w = cw[r], a = ca[r];
-    adagrad1(w.x, a.x, (float)gd.x, lr, eps);
-    adagrad1(w.y, a.y, (float)gd.y, lr, eps);
-    adagrad1(w.z, a.z, (float)gd.z, lr, eps);
-    adagrad1(w.w, a.w, (float)gd.w, lr, eps);
-    cw[r] = w;
-    ca[r] = a;
+    if (s >= 0) adagrad4(cw, ca, (int64_t)s * d4 + c4, gs, lr, eps);
   }
 }
 
