@@ -152,8 +152,7 @@ void seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
   hipLaunchKernelGGL(k_seg_reduce<EMIT>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
                      c->perm64, n, c->D, c->d_slot, (float4*)c->cw, (float4*)c->ca, c->cfg.lr,
                      c->cfg.eps, (float4*)d_common, c->bp, c->bp_vid);
-  const int64_t threads = (int64_t)2 * nblk * c->d4;
-  hipLaunchKernelGGL(k_seg_finish<EMIT>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+  hipLaunchKernelGGL(k_seg_finish<EMIT>, dim3((unsigned)(2 * nblk)), dim3(256), 0,
                      c->st, c->bp, c->bp_vid, 2 * nblk, c->D, c->d_slot, (float4*)c->cw,
                      (float4*)c->ca, c->cfg.lr, c->cfg.eps, (float4*)d_common);
 }

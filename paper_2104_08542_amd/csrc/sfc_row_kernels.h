@@ -134,9 +134,9 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 // ---------------------------------------------------------------------------------------------
 // Gradient segment-sum fused with the sparse Adagrad update (GPU-Worker / Backward; Algorithm 1
 // line 14).  Input: perm64, the batch's positions grouped by virtual id, entry = (vid << 32) |
-// row of grad.  A block takes B consecutive entries (B * D = 8192 floats, 32 KiB):
+// row of grad.  A block takes B consecutive entries (B * D = 4096 floats, 16 KiB):
 //   1. gathers their grad rows into LDS, all loads in flight at once;
-//   2. splits the B rows into ranges of 32; thread (range, column) sums runs of equal vid in
+//   2. splits the B rows into ranges of 16; thread (range, column) sums runs of equal vid in
 //      fp64.  A run that begins and ends inside the range is complete: its sum replaces the
 //      run's first row in LDS.  A run cut by a range edge leaves an fp64 partial;
 //   3. the first D threads chain the partials across ranges; runs closed inside the block are
@@ -148,8 +148,8 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 // A whole-range (whole-block) run stores its sum in the head slot and a zero in the tail slot
 // under the same vid, so equal vids are always adjacent in the partial lists.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSegRows = 32;        // rows per range
-constexpr int kSegFloats = 8192;    // floats of grad per block in LDS
+constexpr int kSegRows = 16;        // rows per range
+constexpr int kSegFloats = 4096;    // floats of grad per block in LDS
 
 struct SegGeom { int ranges, B; };
 __host__ __device__ inline SegGeom seg_geom(int D) {
@@ -205,14 +205,14 @@ __global__ __launch_bounds__(256) void k_seg_reduce(const float4* __restrict__ g
   if (tid < 32) pvid[tid] = -1;
   __syncthreads();
 
-  // 1. gather (B * d4 = 2048 chunks of 16 bytes for the power-of-two dims: 8 per thread)
+  // 1. gather (B * d4 = 1024 chunks of 16 bytes for the power-of-two dims: 4 per thread)
   {
     const int chunks = B * d4;
     float4* tile4 = reinterpret_cast<float4*>(tile);
-    for (int base = 0; base < chunks; base += 256 * 8) {
-      float4 v[8];
+    for (int base = 0; base < chunks; base += 256 * 4) {
+      float4 v[4];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < 4; ++k) {
         const int ch = base + k * 256 + tid;
         v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (ch < chunks) {
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) void k_seg_reduce(const float4* __restrict__ g
         }
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < 4; ++k) {
         const int ch = base + k * 256 + tid;
         if (ch < chunks) tile4[ch] = v[k];
       }
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256) void k_seg_reduce(const float4* __restrict__ g
   int nl = 0;
   {
     int f0 = 0, f1 = 0;
-    const int i0 = 2 * tid, i1 = 2 * tid + 1;       // B <= 512
+    const int i0 = 2 * tid, i1 = 2 * tid + 1;       // B <= 256
     if (i0 < B) f0 = head[i0];
     if (i1 < B) f1 = head[i1];
     const int k = block_excl_scan(f0 + f1, nl, smem);
@@ -319,22 +319,49 @@ __global__ __launch_bounds__(256) void k_seg_reduce(const float4* __restrict__ g
     const int groups = 256 / d4, gi = tid / d4, c4 = tid - gi * d4;
     const float4* tile4 = reinterpret_cast<const float4*>(tile);
     if (gi < groups) {
-      for (int k = gi; k < nl; k += groups) {
-        const int row = head[k];
-        const int v = lvid[row + 1];
-        const float4 gs = tile4[row * d4 + c4];
-        if (EMIT) {
-          common[(int64_t)v * d4 + c4] = gs;
-        } else {
-          const int s = slot[v];
-          if (s >= 0) adagrad4(cw, ca, (int64_t)s * d4 + c4, gs, lr, eps);
+      // four rows per pass: all row loads are issued before the first update is computed
+      for (int k0 = gi; k0 < nl; k0 += 4 * groups) {
+        float4 gs[4], w[4], a[4];
+        int64_t r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int k = k0 + u * groups;
+          r[u] = -1;
+          if (k < nl) {
+            const int row = head[k];
+            const int v = lvid[row + 1];
+            gs[u] = tile4[row * d4 + c4];
+            if (EMIT) {
+              common[(int64_t)v * d4 + c4] = gs[u];
+            } else {
+              const int s = slot[v];
+              if (s >= 0) { r[u] = (int64_t)s * d4 + c4; w[u] = cw[r[u]]; a[u] = ca[r[u]]; }
+            }
+          }
+        }
+        if (!EMIT) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            if (r[u] >= 0) {
+              adagrad1(w[u].x, a[u].x, gs[u].x, lr, eps);
+              adagrad1(w[u].y, a[u].y, gs[u].y, lr, eps);
+              adagrad1(w[u].z, a[u].z, gs[u].z, lr, eps);
+              adagrad1(w[u].w, a[u].w, gs[u].w, lr, eps);
+              cw[r[u]] = w[u];
+              ca[r[u]] = a[u];
+            }
+          }
         }
       }
     }
   }
 }
 
-// Chains the block-edge partials: slot j = 2 * block + (0 head | 1 tail); equal vids are adjacent.
+// Chains the block-edge partials: slot j = 2 * block + (0 head | 1 tail); equal vids are adjacent
+// and a long group (the hottest id spans thousands of blocks) is one long run of slots.  One
+// thread block per slot; only the first slot of a run works: it finds the run's end by binary
+// search (the predicate "same vid" is true on the run and false after it), its 256 threads sum
+// the run's partials in a strided, fixed order and combine through LDS.
 template <bool EMIT>
 __global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ bp,
                                                      const int* __restrict__ bp_vid, int nslots,
@@ -342,24 +369,39 @@ __global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ b
                                                      float4* __restrict__ cw,
                                                      float4* __restrict__ ca, float lr, float eps,
                                                      float4* __restrict__ common) {
-  const int d4 = D / 4;
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t j = i / d4;
-  const int c4 = (int)(i - j * d4);
-  if (j >= nslots) return;
+  __shared__ double red[256 * 4];
+  const int j = (int)blockIdx.x;
   const int v = bp_vid[j];
   if (v < 0 || (j > 0 && bp_vid[j - 1] == v)) return;     // not the first slot of its run
-  double s0 = 0., s1 = 0., s2 = 0., s3 = 0.;
-  for (int64_t k = j; k < nslots && bp_vid[k] == v; ++k) {
-    const double4 x = *reinterpret_cast<const double4*>(&bp[k * D + 4 * c4]);
-    s0 += x.x; s1 += x.y; s2 += x.z; s3 += x.w;
+  int lo = j, hi = nslots;                                 // bp_vid[lo] == v, run ends in (lo, hi]
+  while (hi - lo > 1) {
+    const int mid = lo + (hi - lo) / 2;
+    if (bp_vid[mid] == v) lo = mid; else hi = mid;
   }
-  const float4 gs = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
-  if (EMIT) {
-    common[(int64_t)v * d4 + c4] = gs;
-  } else {
-    const int s = slot[v];
-    if (s >= 0) adagrad4(cw, ca, (int64_t)s * d4 + c4, gs, lr, eps);
+  const int end = hi;
+  const int d4 = D / 4, tid = (int)threadIdx.x;
+  const int lanes = 256 / d4, q = tid / d4, c4 = tid - q * d4;
+  double s0 = 0., s1 = 0., s2 = 0., s3 = 0.;
+  if (q < lanes) {
+    for (int k = j + q; k < end; k += lanes) {
+      const double4 x = *reinterpret_cast<const double4*>(&bp[(int64_t)k * D + 4 * c4]);
+      s0 += x.x; s1 += x.y; s2 += x.z; s3 += x.w;
+    }
+  }
+  red[tid * 4 + 0] = s0; red[tid * 4 + 1] = s1; red[tid * 4 + 2] = s2; red[tid * 4 + 3] = s3;
+  __syncthreads();
+  if (q == 0) {
+    for (int o = 1; o < lanes; ++o) {
+      const double* r = &red[(o * d4 + c4) * 4];
+      s0 += r[0]; s1 += r[1]; s2 += r[2]; s3 += r[3];
+    }
+    const float4 gs = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+    if (EMIT) {
+      common[(int64_t)v * d4 + c4] = gs;
+    } else {
+      const int s = slot[v];
+      if (s >= 0) adagrad4(cw, ca, (int64_t)s * d4 + c4, gs, lr, eps);
+    }
   }
 }
 
