@@ -19,7 +19,7 @@ FLAGS = [
 def build(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + FLAGS + [SRC, "-o", tmp]
+    cmd = [hipcc] + FLAGS + os.environ.get("SFC_EXTRA_FLAGS", "").split() + [SRC, "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

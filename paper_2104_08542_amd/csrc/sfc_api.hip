@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -64,10 +65,11 @@ struct sfc_cache {
   int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
   int64_t* perm64 = nullptr;                    // [max_ids] positions grouped by virtual id
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
+  int* pos_slot = nullptr;                      // [max_ids] cache slot of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
   int* age_mat = nullptr;                       // [kResolveGrid, kAgeBins] hits by age per block
-  double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] block-edge partial sums
-  int seg_B = 0;                                // perm64 entries per block of k_seg_reduce
+  double* bp = nullptr; int* bp_vid = nullptr;  // [2 * wavefronts, D] edge partial sums of k_seg_stream
+  float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
   Ctr* ctr = nullptr;
   float *d_hw = nullptr, *d_ha = nullptr;       // device view of the Host table
   std::vector<void*> allocs;
@@ -144,17 +146,16 @@ int prof_collect(sfc_cache* c) {
 
 // Segment-sum over perm64, then either the Adagrad update (EMIT = false) or the common-gradient
 // matrix (EMIT = true).  Two kernels: per-block runs, then the block-edge partials.
-template <bool EMIT>
+// common[v] = segment sum of d_grad over perm64: the stream, then the block-edge partials.
 void seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
   const int n = (int)c->n_ids;
   if (n <= 0) return;
-  const int nblk = (n + c->seg_B - 1) / c->seg_B;
-  hipLaunchKernelGGL(k_seg_reduce<EMIT>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
-                     c->perm64, n, c->D, c->d_slot, (float4*)c->cw, (float4*)c->ca, c->cfg.lr,
-                     c->cfg.eps, (float4*)d_common, c->bp, c->bp_vid);
-  hipLaunchKernelGGL(k_seg_finish<EMIT>, dim3((unsigned)(2 * nblk)), dim3(256), 0,
-                     c->st, c->bp, c->bp_vid, 2 * nblk, c->D, c->d_slot, (float4*)c->cw,
-                     (float4*)c->ca, c->cfg.lr, c->cfg.eps, (float4*)d_common);
+  const SegGeom g = seg_geom(c->D, n);
+  const int nblk = (g.waves + 3) / 4;
+  hipLaunchKernelGGL(k_seg_stream, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
+                     c->perm64, n, c->d4, g.G, g.L, (float4*)d_common, c->bp, c->bp_vid);
+  hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, c->bp,
+                     c->bp_vid, 2 * nblk, c->d4, (float4*)d_common);
 }
 
 constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
@@ -265,15 +266,17 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->perm64, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->pos_slot, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->age_mat, (int64_t)kResolveGrid * kAgeBins))) goto bad;
-    c->seg_B = seg_geom(c->D).B;
     {
-      const int64_t nblk = (c->max_ids + c->seg_B - 1) / c->seg_B;
-      if ((rc = dalloc(c, &c->bp, 2 * nblk * c->D))) goto bad;
-      if ((rc = dalloc(c, &c->bp_vid, 2 * nblk))) goto bad;
+      const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;   // the wave count never exceeds that of max_ids
+      const int64_t nwmax = nw > 4104 ? nw : 4104;
+      if ((rc = dalloc(c, &c->bp, 2 * nwmax * c->D))) goto bad;
+      if ((rc = dalloc(c, &c->bp_vid, 2 * nwmax))) goto bad;
     }
     if ((rc = dalloc(c, &c->ctr, 1))) goto bad;
+    if ((rc = dalloc(c, &c->gsum, c->max_ids * c->D))) goto bad;
 
     hipStream_t s = c->st;
     fill<int64_t>(s, c->slot_id, c->C, (int64_t)-1);
@@ -363,7 +366,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3(nchunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor,
-                       c->perm64);
+                       c->perm64, d_slot, c->pos_slot);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
   HIPCHK(hipEventRecord(c->ev_prepared, s));
@@ -403,13 +406,16 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
   if ((rc = prof_begin(c, P_LOOKUP, s, &ep))) return rc;
   const int64_t total = c->n_bags * c->d4;
   if (total > 0) {
-    if (!c->d_offsets)
-      hipLaunchKernelGGL(k_lookup_onehot, dim3((unsigned)((total + 1023) / 1024)), dim3(256), 0, s,
-                         c->d_inverse, c->d_slot, (const float4*)c->cw, (float4*)d_out, total, c->d4);
-    else
+    if (!c->d_offsets) {
+      const int d4 = c->d4, sh = (d4 & (d4 - 1)) == 0 ? __builtin_ctz(d4) : -1;
+      hipLaunchKernelGGL(k_lookup_onehot, dim3((unsigned)((c->n_bags + kLookupBags - 1) / kLookupBags)),
+                         dim3(256), 0, s, c->pos_slot, (const float4*)c->cw, (float4*)d_out,
+                         (int)c->n_bags, d4, sh);
+    } else {
       hipLaunchKernelGGL(k_lookup_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                         c->d_offsets, c->d_inverse, c->d_slot, (const float4*)c->cw,
-                         (float4*)d_out, total, c->d4);
+                         c->d_offsets, c->pos_slot, (const float4*)c->cw, (float4*)d_out, total,
+                         c->d4);
+    }
   }
   HIPCHK(hipGetLastError());
   return prof_end(c, P_LOOKUP, s, &ep);
@@ -420,7 +426,7 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (c->state == IDLE) return fail(SFC_ESTATE, "sfc_segment_sum needs a preceding sfc_prepare");
   if ((c->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
-  seg_launch<true>(c, d_grad, d_common_grad);
+  seg_launch(c, d_grad, d_common_grad);
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -435,7 +441,10 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   int rc;
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
   if ((rc = prof_begin(c, P_SEGSUM, s, &e1))) return rc;
-  seg_launch<false>(c, d_grad, nullptr);
+  seg_launch(c, d_grad, c->gsum);
+  hipLaunchKernelGGL(k_adagrad_rows, dim3(grid_for(c->n_ids * c->d4, 1024, kGridCap)), dim3(256), 0,
+                     s, (const float4*)c->gsum, c->d_slot, (float4*)c->cw, (float4*)c->ca,
+                     c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
   if ((rc = prof_end(c, P_SEGSUM, s, &e1))) return rc;
   hipLaunchKernelGGL(k_writeback_bypass, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0,
                      s, c->d_miss, c->d_unique, c->d_slot, (const float4*)c->cw,

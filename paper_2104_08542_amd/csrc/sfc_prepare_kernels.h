@@ -211,10 +211,13 @@ __global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ off
 // payload = position (one-hot) or bag index (multi-hot).  cursor[v] starts at the exclusive scan
 // of cnt.  Same LDS treatment of the low virtual ids as above; an id that occurs once needs no
 // atomic at all.  The order inside a group is the order in which the atomics land.
+// Also writes pos_slot[p] = slot[inverse[p]] for the forward gather.
 __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse,
                                                   const int* __restrict__ pos2bag, int n,
                                                   const int* __restrict__ cnt, int* cursor,
-                                                  int64_t* __restrict__ perm64) {
+                                                  int64_t* __restrict__ perm64,
+                                                  const int* __restrict__ slot,
+                                                  int* __restrict__ pos_slot) {
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
@@ -226,6 +229,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
     vv[j] = -1;
     if (p < n) {
       const int v = inverse[p];
+      pos_slot[p] = slot[v];              // the forward gather reads slots per position
       if (v < kHotBins) {
         vv[j] = v;
         rr[j] = atomicAdd(&lh[v], 1);

@@ -89,30 +89,58 @@ __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Forward gather (Algorithm 1 lines 9 and 11 fused): out[b] = cache row of slot[inverse[b]].
+// Forward gather (Algorithm 1 lines 9 and 11 fused): out[b] = cache row of the slot of position b.
+// pos_slot[p] = slot[inverse[p]] is written by the prepare step, so the gather is one level of
+// indirection.  A block stages the slots of its 256 bags in LDS with one coalesced load, then
+// every thread has eight 16-byte row chunks in flight before the first store; a wavefront's
+// stores are 1 KiB contiguous and non-temporal (the output is consumed by the model, not by us).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_lookup_onehot(const int* __restrict__ inverse,
-                                                        const int* __restrict__ slot,
+constexpr int kLookupBags = 256;
+
+// d4 is a runtime value; when it is a power of two (sh >= 0) index math is shifts and masks
+__device__ __forceinline__ void split_chunk(unsigned ch, int d4, int sh, unsigned& r, unsigned& c) {
+  if (sh >= 0) { r = ch >> sh; c = ch & (unsigned)(d4 - 1); }
+  else { r = ch / (unsigned)d4; c = ch - r * (unsigned)d4; }
+}
+
+__global__ __launch_bounds__(256) void k_lookup_onehot(const int* __restrict__ pos_slot,
                                                         const float4* __restrict__ cw,
-                                                        float4* __restrict__ out, int64_t total,
-                                                        int d4) {
-  const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+                                                        float4* __restrict__ out, int n_bags,
+                                                        int d4, int sh) {
+  __shared__ int ls[kLookupBags];
+  const int b0 = (int)blockIdx.x * kLookupBags;
+  {
+    const int b = b0 + (int)threadIdx.x;
+    ls[threadIdx.x] = b < n_bags ? pos_slot[b] : -1;
+  }
+  __syncthreads();
+  int nb = n_bags - b0;
+  if (nb > kLookupBags) nb = kLookupBags;
+  const unsigned chunks = (unsigned)nb * (unsigned)d4;
+  float4* dst = out + (int64_t)b0 * d4;
+  for (unsigned base = 0; base < chunks; base += 256 * 8) {
+    float4 v[8];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int64_t i = base + k * 256;
-    if (i < total) {
-      const int b = (int)(i / d4), c = (int)(i % d4);
-      const int s = slot[inverse[b]];
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (s >= 0) v = cw[(int64_t)s * d4 + c];
-      st_stream(&out[i], v);
+    for (int k = 0; k < 8; ++k) {
+      const unsigned ch = base + k * 256 + threadIdx.x;
+      v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (ch < chunks) {
+        unsigned r, c;
+        split_chunk(ch, d4, sh, r, c);
+        const int s = ls[r];
+        if (s >= 0) v[k] = cw[(int64_t)s * d4 + c];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const unsigned ch = base + k * 256 + threadIdx.x;
+      if (ch < chunks) st_stream(&dst[ch], v[k]);
     }
   }
 }
 
 __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__ offsets,
-                                                      const int* __restrict__ inverse,
-                                                      const int* __restrict__ slot,
+                                                      const int* __restrict__ pos_slot,
                                                       const float4* __restrict__ cw,
                                                       float4* __restrict__ out, int64_t total,
                                                       int d4) {
@@ -122,7 +150,7 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
   const int c = (int)(i % d4);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int64_t q = offsets[b], e = offsets[b + 1]; q < e; ++q) {
-    const int s = slot[inverse[q]];
+    const int s = pos_slot[q];
     if (s >= 0) {
       const float4 v = cw[(int64_t)s * d4 + c];
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
@@ -132,243 +160,226 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Gradient segment-sum fused with the sparse Adagrad update (GPU-Worker / Backward; Algorithm 1
-// line 14).  Input: perm64, the batch's positions grouped by virtual id, entry = (vid << 32) |
-// row of grad.  A block takes B consecutive entries (B * D = 4096 floats, 16 KiB):
-//   1. gathers their grad rows into LDS, all loads in flight at once;
-//   2. splits the B rows into ranges of 16; thread (range, column) sums runs of equal vid in
-//      fp64.  A run that begins and ends inside the range is complete: its sum replaces the
-//      run's first row in LDS.  A run cut by a range edge leaves an fp64 partial;
-//   3. the first D threads chain the partials across ranges; runs closed inside the block are
-//      complete as well, runs cut by the block edge go to bp[block][0 = head, 1 = tail] in HBM;
-//   4. complete runs are compacted and each gets its Adagrad update (or is emitted as a row of
-//      the common-gradient matrix), D/4 lanes per row.
-// k_seg_finish then chains the block-edge partials of the few long groups.  No atomics, and
-// the summation tree depends only on perm64.
-// A whole-range (whole-block) run stores its sum in the head slot and a zero in the tail slot
-// under the same vid, so equal vids are always adjacent in the partial lists.
+// Gradient segment-sum (GPU-Worker / Backward): common[v] = sum of the grad rows of the positions
+// with virtual id v.  Input: perm64, the batch's positions grouped by virtual id, entry =
+// (vid << 32) | row of grad.  The kernel is a barrier-free stream over perm64:
+//   - a row is D/4 lanes of 16 bytes, so a wavefront holds G = 64 / (D/4) lane groups; group g of
+//     wavefront w owns the span of L consecutive entries starting at (w*G + g)*L;
+//   - a group walks its span four entries at a time, the grad rows of the next four already in
+//     flight, and sums runs of equal vid in fp64 registers.  A run that begins and ends inside
+//     the span is complete when it closes: it is rounded to fp32 once and stored as row vid of
+//     the common-gradient matrix;
+//   - a run cut by the span's edge leaves an fp64 partial (head / tail).  The G groups of the
+//     wavefront chain their partials through LDS once, at the end; runs cut by the wavefront's
+//     edge are chained once more across the block's four wavefronts; what is cut by the
+//     block's edge goes to bp[block][0 = head, 1 = tail] in HBM and k_seg_finish chains those.
+// No atomics; the summation tree depends only on perm64, n and D.
+// A run that covers a whole span (wavefront) stores its sum in the head slot and a zero in the
+// tail slot under the same vid, so equal vids are always adjacent in the partial lists.
+//
+// The Adagrad update is a separate kernel over the common-gradient matrix (k_adagrad_rows).
+// Fusing it into the stream (update the cached row when its run closes) was measured slower on
+// MI355X: the dependent chain entry -> slot -> cached row sits inside the streaming loop and
+// the extra registers cost a wavefront of occupancy per SIMD, which outweighs the 60 MB of
+// common-gradient traffic that fusion saves.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSegRows = 16;        // rows per range
-constexpr int kSegFloats = 4096;    // floats of grad per block in LDS
+#ifndef SFC_SEG_CHUNK
+#define SFC_SEG_CHUNK 4
+#endif
+constexpr int kSegChunk = SFC_SEG_CHUNK;        // entries per group per loop iteration
 
-struct SegGeom { int ranges, B; };
-__host__ __device__ inline SegGeom seg_geom(int D) {
-  int r = 256 / D;
-  if (r < 1) r = 1;
-  if (r > 16) r = 16;
-  SegGeom g; g.ranges = r; g.B = r * kSegRows;
+struct SegGeom { int G, L, waves; };
+// L is chosen so that the stream has about 16 wavefronts per compute unit, never below 32 entries.
+inline SegGeom seg_geom(int D, int64_t n) {
+  SegGeom g;
+  g.G = 64 / (D / 4);
+  if (g.G < 1) g.G = 1;
+  const int64_t target_waves = 256 * 16;
+  int64_t L = (n + g.G * target_waves - 1) / (g.G * target_waves);
+  if (L < 32) L = 32;
+  L = (L + kSegChunk - 1) / kSegChunk * kSegChunk;
+  g.L = (int)L;
+  g.waves = (int)((n + (int64_t)g.G * L - 1) / ((int64_t)g.G * L));
   return g;
 }
 
-__device__ __forceinline__ void adagrad1(float& w, float& a, float g, float lr, float eps) {
-  a = a + g * g;
-  w = w - lr * g / (sqrtf(a) + eps);
+struct D4 { double x, y, z, w; };
+__device__ __forceinline__ void d4_zero(D4& a) { a.x = a.y = a.z = a.w = 0.0; }
+__device__ __forceinline__ void d4_add(D4& a, float4 v) {
+  a.x += (double)v.x; a.y += (double)v.y; a.z += (double)v.z; a.w += (double)v.w;
 }
-__device__ __forceinline__ void adagrad4(float4* cw, float4* ca, int64_t r, float4 g, float lr,
-                                         float eps) {
-  float4 w = cw[r], a = ca[r];
-  adagrad1(w.x, a.x, g.x, lr, eps);
-  adagrad1(w.y, a.y, g.y, lr, eps);
-  adagrad1(w.z, a.z, g.z, lr, eps);
-  adagrad1(w.w, a.w, g.w, lr, eps);
-  cw[r] = w;
-  ca[r] = a;
+__device__ __forceinline__ float4 d4_round(const D4& a) {
+  return make_float4((float)a.x, (float)a.y, (float)a.z, (float)a.w);
 }
 
-template <bool EMIT>
-__global__ __launch_bounds__(256) void k_seg_reduce(const float4* __restrict__ grad,
+// Chains a list of partial slots (even = head of a span, odd = its tail; vid -1 = none).  Runs that
+// begin at an odd slot and end at an even one lie inside the list: they are complete and stored.
+// A run open at the left edge is returned as (bv0, b0), one open at the right edge as (bv1, b1);
+// a run open at both edges returns its sum in b0 and a zero marker in b1.
+__device__ __forceinline__ void chain_slots(int nslots, const int* __restrict__ vids,
+                                            const double* __restrict__ sums, int D, int d4, int c4,
+                                            float4* __restrict__ common, int& bv0, D4& b0, int& bv1,
+                                            D4& b1) {
+  bv0 = -1; bv1 = -1;
+  d4_zero(b0); d4_zero(b1);
+  D4 run; d4_zero(run);
+  int rv = -1;
+  bool rbegun = false;
+  for (int j = 0; j <= nslots; ++j) {
+    const int v = j < nslots ? vids[j] : -1;
+    if (v != rv) {
+      if (rv >= 0) {
+        const bool ended = ((j - 1) & 1) == 0;      // the run's last slot was a head slot
+        if (rbegun && ended) {
+          common[(int64_t)rv * d4 + c4] = d4_round(run);
+        } else if (!rbegun) {
+          bv0 = rv; b0 = run;
+          if (!ended) bv1 = rv;
+        } else {
+          bv1 = rv; b1 = run;
+        }
+      }
+      rv = v; d4_zero(run);
+      rbegun = (j & 1) == 1;
+    }
+    if (v >= 0) {
+      const double* q = &sums[j * D + 4 * c4];
+      run.x += q[0]; run.y += q[1]; run.z += q[2]; run.w += q[3];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ grad,
                                                      const int64_t* __restrict__ perm64, int n,
-                                                     int D, const int* __restrict__ slot,
-                                                     float4* __restrict__ cw,
-                                                     float4* __restrict__ ca, float lr, float eps,
+                                                     int d4, int G, int L,
                                                      float4* __restrict__ common,
                                                      double* __restrict__ bp,
                                                      int* __restrict__ bp_vid) {
-  __shared__ float tile[kSegFloats];            // [B][D] grad rows; later the complete sums
-  __shared__ double part[2 * 256];              // [ranges][2][D] range-edge partials (ranges*D <= 256)
-  __shared__ int lvid[16 * kSegRows + 2];       // vid of entries e0-1 .. e0+B
-  __shared__ int lrow[16 * kSegRows];           // grad row of each entry
-  __shared__ int pvid[32], pstart[32];          // per partial slot: vid (-1 = none), first row
-  __shared__ int head[16 * kSegRows];           // 1 = complete run starts at this row; later: list
-  __shared__ int smem[20];
-  const SegGeom g = seg_geom(D);
-  const int B = g.B, ranges = g.ranges, d4 = D / 4;
-  const int tid = (int)threadIdx.x;
-  const int64_t e0 = (int64_t)blockIdx.x * B;
+  // per wavefront: [2G slots][D] doubles (2*G*D <= 512) and the slots' vids
+  __shared__ double part[4][512];
+  __shared__ int pvid[4][128];
+  __shared__ double wpart[8 * 256];     // [4 wavefronts][2][D]
+  __shared__ int wvid[8];
+  const int lane = lane_id(), wib = (int)(threadIdx.x >> 6);
+  const int wave = (int)blockIdx.x * 4 + wib;
+  const int g = lane / d4, c4 = lane - g * d4;
+  const int D = d4 * 4;
+  const bool active = g < G;
+  const int64_t sb = ((int64_t)wave * G + g) * L;           // span of this group: [sb, se)
+  int64_t se = sb + L;
+  if (se > n) se = n;
+  const bool nonempty = active && sb < n;
 
-  for (int i = tid; i < B + 2; i += 256) {
-    const int64_t e = e0 - 1 + i;
-    const int64_t pv = (e >= 0 && e < n) ? perm64[e] : (int64_t)-1;
-    lvid[i] = (int)(pv >> 32);
-    if (i >= 1 && i <= B) { lrow[i - 1] = (int)(uint32_t)pv; head[i - 1] = 0; }
-  }
-  if (tid < 32) pvid[tid] = -1;
-  __syncthreads();
+  int cur = -1;           // vid of the open run
+  bool begun = false;     // the open run began inside this span
+  D4 acc; d4_zero(acc);
+  int head_v = -1; D4 head_s; d4_zero(head_s);     // run that continues from before the span
+  int tail_v = -1; D4 tail_s; d4_zero(tail_s);     // run that continues past the span
 
-  // 1. gather (B * d4 = 1024 chunks of 16 bytes for the power-of-two dims: 4 per thread)
-  {
-    const int chunks = B * d4;
-    float4* tile4 = reinterpret_cast<float4*>(tile);
-    for (int base = 0; base < chunks; base += 256 * 4) {
-      float4 v[4];
+  if (nonempty) {
+    const int prev_v = sb > 0 ? (int)(perm64[sb - 1] >> 32) : -1;
+    // software pipeline: pe / x = entries and grad rows of the chunk being processed (issued one
+    // iteration earlier), pn = the next chunk's entries
+    int64_t pe[kSegChunk], pn[kSegChunk];
+    float4 x[kSegChunk];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int ch = base + k * 256 + tid;
-        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ch < chunks) {
-          const int i = ch / d4;
-          if (lvid[i + 1] >= 0) v[k] = ld_stream(&grad[(int64_t)lrow[i] * d4 + (ch - i * d4)]);
+    for (int k = 0; k < kSegChunk; ++k) pe[k] = sb + k < se ? perm64[sb + k] : (int64_t)-1;
+#pragma unroll
+    for (int k = 0; k < kSegChunk; ++k) {
+      x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (pe[k] >= 0) x[k] = ld_stream(&grad[(int64_t)(uint32_t)pe[k] * d4 + c4]);
+    }
+#pragma unroll
+    for (int k = 0; k < kSegChunk; ++k)
+      pn[k] = sb + kSegChunk + k < se ? perm64[sb + kSegChunk + k] : (int64_t)-1;
+    cur = (int)(pe[0] >> 32);
+    begun = prev_v != cur;
+
+    for (int64_t e = sb; e < se; e += kSegChunk) {
+      // issue the next chunk's rows and the chunk after that's entries
+      float4 xn[kSegChunk];
+      int64_t pnn[kSegChunk];
+#pragma unroll
+      for (int k = 0; k < kSegChunk; ++k) {
+        xn[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (pn[k] >= 0) xn[k] = ld_stream(&grad[(int64_t)(uint32_t)pn[k] * d4 + c4]);
+      }
+#pragma unroll
+      for (int k = 0; k < kSegChunk; ++k) {
+        const int64_t q = e + 2 * kSegChunk + k;
+        pnn[k] = q < se ? perm64[q] : (int64_t)-1;
+      }
+#pragma unroll
+      for (int k = 0; k < kSegChunk; ++k) {
+        if (pe[k] >= 0) {
+          const int v = (int)(pe[k] >> 32);
+          if (v != cur) {
+            if (begun) common[(int64_t)cur * d4 + c4] = d4_round(acc);
+            else { head_v = cur; head_s = acc; }
+            cur = v; begun = true; d4_zero(acc);
+          }
+          d4_add(acc, x[k]);
         }
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int ch = base + k * 256 + tid;
-        if (ch < chunks) tile4[ch] = v[k];
-      }
+      for (int k = 0; k < kSegChunk; ++k) { pe[k] = pn[k]; pn[k] = pnn[k]; x[k] = xn[k]; }
+    }
+    // close the span: the open run either ends here or continues into the next span
+    const int next_v = se < n ? (int)(perm64[se] >> 32) : -1;
+    if (next_v != cur) {
+      if (begun) common[(int64_t)cur * d4 + c4] = d4_round(acc);
+      else { head_v = cur; head_s = acc; }
+    } else if (begun) {
+      tail_v = cur; tail_s = acc;
+    } else {
+      head_v = cur; head_s = acc; tail_v = cur;          // whole span: zero marker in the tail
     }
   }
-  __syncthreads();
 
-  // 2. runs inside each range
-  {
-    const int r = tid / D, c = tid - r * D;
-    if (r < ranges) {
-      const int i0 = r * kSegRows;
-      double acc = 0.0;
-      int cur = lvid[i0 + 1], start = i0;
-      for (int i = i0; i <= i0 + kSegRows; ++i) {
-        const int v = i < i0 + kSegRows ? lvid[i + 1] : -2;     // -2 closes the last run
-        if (v != cur || i == i0 + kSegRows) {
-          if (cur >= 0) {
-            const bool begins = lvid[start] != cur;      // entry before the run differs
-            const bool ends = lvid[i + 1] != cur;        // entry after the run differs
-            if (begins && ends) {
-              tile[start * D + c] = (float)acc;
-              if (c == 0) head[start] = 1;
-            } else if (!begins) {
-              part[(2 * r) * D + c] = acc;
-              if (c == 0) { pvid[2 * r] = cur; pstart[2 * r] = start; }
-              if (!ends) {
-                part[(2 * r + 1) * D + c] = 0.0;
-                if (c == 0) { pvid[2 * r + 1] = cur; pstart[2 * r + 1] = start; }
-              }
-            } else {
-              part[(2 * r + 1) * D + c] = acc;
-              if (c == 0) { pvid[2 * r + 1] = cur; pstart[2 * r + 1] = start; }
-            }
-          }
-          cur = v; start = i; acc = 0.0;
-        }
-        if (i < i0 + kSegRows) acc += (double)tile[i * D + c];
-      }
-    }
+  // chain the 2G partial slots of this wavefront (slot order = span order; even = head, odd = tail)
+  if (active) {
+    double* ph = &part[wib][(2 * g) * D + 4 * c4];
+    ph[0] = head_s.x; ph[1] = head_s.y; ph[2] = head_s.z; ph[3] = head_s.w;
+    ph += D;
+    ph[0] = tail_s.x; ph[1] = tail_s.y; ph[2] = tail_s.z; ph[3] = tail_s.w;
+    if (c4 == 0) { pvid[wib][2 * g] = head_v; pvid[wib][2 * g + 1] = tail_v; }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  if (lane < d4) {
+    int bv0, bv1;
+    D4 b0, b1;
+    chain_slots(2 * G, pvid[wib], part[wib], D, d4, c4, common, bv0, b0, bv1, b1);
+    // the wavefront's own head / tail become slots 2*wib, 2*wib+1 of the block's chain
+    double* o0 = &wpart[(2 * wib) * D + 4 * c4];
+    o0[0] = b0.x; o0[1] = b0.y; o0[2] = b0.z; o0[3] = b0.w;
+    double* o1 = o0 + D;
+    o1[0] = b1.x; o1[1] = b1.y; o1[2] = b1.z; o1[3] = b1.w;
+    if (c4 == 0) { wvid[2 * wib] = bv0; wvid[2 * wib + 1] = bv1; }
   }
   __syncthreads();
-
-  // 3. chain the range-edge partials (slot order = range order; odd = tail, even = head)
-  if (tid < D) {
-    const int c = tid;
-    int bv0 = -1, bv1 = -1;
-    double b0 = 0.0, b1 = 0.0;
-    double run = 0.0;
-    int rv = -1, rstart = 0;
-    bool begun = false;
-    const int nslots = 2 * ranges;
-    for (int j = 0; j <= nslots; ++j) {
-      const int v = j < nslots ? pvid[j] : -1;
-      if (v != rv) {
-        if (rv >= 0) {
-          // the run's last slot is j-1: an even (head) slot means it ended inside the block
-          const bool ended = ((j - 1) & 1) == 0;
-          if (begun && ended) {
-            tile[rstart * D + c] = (float)run;
-            if (c == 0) head[rstart] = 1;
-          } else if (!begun) {
-            bv0 = rv; b0 = run;
-            if (!ended) { bv1 = rv; b1 = 0.0; }
-          } else {
-            bv1 = rv; b1 = run;
-          }
-        }
-        rv = v; run = 0.0;
-        if (v >= 0) { begun = (j & 1) == 1; rstart = pstart[j]; }
-      }
-      if (v >= 0) run += part[j * D + c];
-    }
+  if (threadIdx.x < (unsigned)d4) {
+    int bv0, bv1;
+    D4 b0, b1;
+    chain_slots(8, wvid, wpart, D, d4, c4, common, bv0, b0, bv1, b1);
     const int64_t o = (int64_t)blockIdx.x * 2;
-    bp[(o + 0) * D + c] = b0;
-    bp[(o + 1) * D + c] = b1;
-    if (c == 0) { bp_vid[o] = bv0; bp_vid[o + 1] = bv1; }
-  }
-  __syncthreads();
-
-  // 4. compact the complete runs, then update / emit them D/4 lanes per row
-  int nl = 0;
-  {
-    int f0 = 0, f1 = 0;
-    const int i0 = 2 * tid, i1 = 2 * tid + 1;       // B <= 256
-    if (i0 < B) f0 = head[i0];
-    if (i1 < B) f1 = head[i1];
-    const int k = block_excl_scan(f0 + f1, nl, smem);
-    __syncthreads();                                  // all flags read before the list overwrites them
-    if (f0) head[k] = i0;
-    if (f1) head[k + f0] = i1;
-  }
-  __syncthreads();
-  {
-    const int groups = 256 / d4, gi = tid / d4, c4 = tid - gi * d4;
-    const float4* tile4 = reinterpret_cast<const float4*>(tile);
-    if (gi < groups) {
-      // four rows per pass: all row loads are issued before the first update is computed
-      for (int k0 = gi; k0 < nl; k0 += 4 * groups) {
-        float4 gs[4], w[4], a[4];
-        int64_t r[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int k = k0 + u * groups;
-          r[u] = -1;
-          if (k < nl) {
-            const int row = head[k];
-            const int v = lvid[row + 1];
-            gs[u] = tile4[row * d4 + c4];
-            if (EMIT) {
-              common[(int64_t)v * d4 + c4] = gs[u];
-            } else {
-              const int s = slot[v];
-              if (s >= 0) { r[u] = (int64_t)s * d4 + c4; w[u] = cw[r[u]]; a[u] = ca[r[u]]; }
-            }
-          }
-        }
-        if (!EMIT) {
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (r[u] >= 0) {
-              adagrad1(w[u].x, a[u].x, gs[u].x, lr, eps);
-              adagrad1(w[u].y, a[u].y, gs[u].y, lr, eps);
-              adagrad1(w[u].z, a[u].z, gs[u].z, lr, eps);
-              adagrad1(w[u].w, a[u].w, gs[u].w, lr, eps);
-              cw[r[u]] = w[u];
-              ca[r[u]] = a[u];
-            }
-          }
-        }
-      }
-    }
+    double* o0 = &bp[(o + 0) * D + 4 * c4];
+    o0[0] = b0.x; o0[1] = b0.y; o0[2] = b0.z; o0[3] = b0.w;
+    double* o1 = &bp[(o + 1) * D + 4 * c4];
+    o1[0] = b1.x; o1[1] = b1.y; o1[2] = b1.z; o1[3] = b1.w;
+    if (c4 == 0) { bp_vid[o] = bv0; bp_vid[o + 1] = bv1; }
   }
 }
 
 // Chains the block-edge partials: slot j = 2 * block + (0 head | 1 tail); equal vids are adjacent
-// and a long group (the hottest id spans thousands of blocks) is one long run of slots.  One
+// and a long group (the hottest id spans hundreds of blocks) is one long run of slots.  One
 // thread block per slot; only the first slot of a run works: it finds the run's end by binary
-// search (the predicate "same vid" is true on the run and false after it), its 256 threads sum
-// the run's partials in a strided, fixed order and combine through LDS.
-template <bool EMIT>
+// search (the predicate "same vid" is true on the run and false after it), its lane groups sum
+// the run's partials in a strided, fixed order, four loads in flight, and combine through LDS.
 __global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ bp,
                                                      const int* __restrict__ bp_vid, int nslots,
-                                                     int D, const int* __restrict__ slot,
-                                                     float4* __restrict__ cw,
-                                                     float4* __restrict__ ca, float lr, float eps,
-                                                     float4* __restrict__ common) {
+                                                     int d4, float4* __restrict__ common) {
   __shared__ double red[256 * 4];
   const int j = (int)blockIdx.x;
   const int v = bp_vid[j];
@@ -378,30 +389,72 @@ __global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ b
     const int mid = lo + (hi - lo) / 2;
     if (bp_vid[mid] == v) lo = mid; else hi = mid;
   }
-  const int end = hi;
-  const int d4 = D / 4, tid = (int)threadIdx.x;
-  const int lanes = 256 / d4, q = tid / d4, c4 = tid - q * d4;
+  const int end = hi, D = d4 * 4, tid = (int)threadIdx.x;
+  const int groups = 256 / d4, g = tid / d4, c4 = tid - g * d4;
   double s0 = 0., s1 = 0., s2 = 0., s3 = 0.;
-  if (q < lanes) {
-    for (int k = j + q; k < end; k += lanes) {
-      const double4 x = *reinterpret_cast<const double4*>(&bp[(int64_t)k * D + 4 * c4]);
-      s0 += x.x; s1 += x.y; s2 += x.z; s3 += x.w;
+  if (g < groups) {
+    const double4 zero = make_double4(0., 0., 0., 0.);
+    for (int k = j + g; k < end; k += 4 * groups) {
+      double4 x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kk = k + u * groups;
+        x[u] = kk < end ? *reinterpret_cast<const double4*>(&bp[(int64_t)kk * D + 4 * c4]) : zero;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { s0 += x[u].x; s1 += x[u].y; s2 += x[u].z; s3 += x[u].w; }
     }
   }
-  red[tid * 4 + 0] = s0; red[tid * 4 + 1] = s1; red[tid * 4 + 2] = s2; red[tid * 4 + 3] = s3;
+  double* r = &red[tid * 4];
+  r[0] = s0; r[1] = s1; r[2] = s2; r[3] = s3;
   __syncthreads();
-  if (q == 0) {
-    for (int o = 1; o < lanes; ++o) {
-      const double* r = &red[(o * d4 + c4) * 4];
-      s0 += r[0]; s1 += r[1]; s2 += r[2]; s3 += r[3];
+  if (g == 0) {
+    for (int o = 1; o < groups; ++o) {
+      const double* q = &red[(o * d4 + c4) * 4];
+      s0 += q[0]; s1 += q[1]; s2 += q[2]; s3 += q[3];
     }
-    const float4 gs = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
-    if (EMIT) {
-      common[(int64_t)v * d4 + c4] = gs;
-    } else {
-      const int s = slot[v];
-      if (s >= 0) adagrad4(cw, ca, (int64_t)s * d4 + c4, gs, lr, eps);
+    common[(int64_t)v * d4 + c4] = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sparse Adagrad (Algorithm 1 line 14), once per unique row:
+//   acc += g*g ; w -= lr * g / (sqrt(acc) + eps)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void adagrad1(float& w, float& a, float g, float lr, float eps) {
+  a = a + g * g;
+  w = w - lr * g / (sqrtf(a) + eps);
+}
+__device__ __forceinline__ void adagrad4v(float4& w, float4& a, float4 g, float lr, float eps) {
+  adagrad1(w.x, a.x, g.x, lr, eps);
+  adagrad1(w.y, a.y, g.y, lr, eps);
+  adagrad1(w.z, a.z, g.z, lr, eps);
+  adagrad1(w.w, a.w, g.w, lr, eps);
+}
+
+// Adagrad over the common-gradient matrix (one row per virtual id), four rows per thread in flight.
+__global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__ common,
+                                                       const int* __restrict__ slot,
+                                                       float4* __restrict__ cw,
+                                                       float4* __restrict__ ca, float lr, float eps,
+                                                       int d4, const Ctr* ctr) {
+  const int64_t total = (int64_t)ctr->U * d4;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 4 * stride) {
+    float4 g[4], w[4], a[4];
+    int64_t r[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + u * stride;
+      r[u] = -1;
+      if (i < total) {
+        const int s = slot[(int)(i / d4)];
+        if (s >= 0) { r[u] = (int64_t)s * d4 + (i % d4); g[u] = common[i]; w[u] = cw[r[u]]; a[u] = ca[r[u]]; }
+      }
     }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (r[u] >= 0) { adagrad4v(w[u], a[u], g[u], lr, eps); cw[r[u]] = w[u]; ca[r[u]] = a[u]; }
   }
 }
 

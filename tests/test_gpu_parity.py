@@ -111,6 +111,30 @@ def test_medium_zipf_many_tiles():
     p.finish(); p.close()
 
 
+@pytest.mark.parametrize("D", [4, 8, 16, 64, 80, 128, 256])
+def test_row_widths(D):
+    # every lane-group geometry of the row kernels (D/4 lanes per row, also a D that does not
+    # divide the wavefront), with a hot id, mid-frequency ids and singletons in one batch
+    V, n = 6000, 5000
+    p = Pair(V, D, C=1200, max_ids=n + 37)
+    for t in range(3):
+        ids = si.zipf_ids(n + 37 * (t % 2), 1.3, V, 60 + D, t).numpy()
+        p.step(ids, si.grads(ids.size, D, 60 + D, t).numpy())
+    p.finish(); p.close()
+
+
+def test_long_groups_cross_many_spans():
+    # three ids own almost all of 300k positions: their groups span hundreds of wavefronts
+    V, D, n = 500, 32, 300_000
+    p = Pair(V, D, C=500, max_ids=n)
+    rng = np.random.default_rng(11)
+    r = rng.random(n)
+    ids = np.where(r < 0.5, 3, np.where(r < 0.8, 5, np.where(r < 0.97, 8, rng.integers(0, V, n))))
+    p.step(ids, si.grads(n, D, 12, 0).numpy())
+    p.step(ids[::-1].copy(), si.grads(n, D, 12, 1).numpy())
+    p.finish(); p.close()
+
+
 def test_same_stream_for_copies():
     V, D, n = 4000, 32, 2000
     p = Pair(V, D, C=1000, max_ids=2048, side_stream=False)
