@@ -22,6 +22,20 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE counters, calibrated against a plain copy)
+    as recorded in profiles/hbm_traffic.txt by an earlier rocprofv3 --pmc run; None if absent."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")) as f:
+            for line in f:
+                p = line.split()
+                if len(p) >= 4 and p[0] == workload and p[1] == kernel:
+                    return float(p[2]) + float(p[3])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -30,6 +44,8 @@ def main():
     ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="end with three plain 1 GiB device copies (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the one-GPU hot path; there is no multi-GPU exchange to run. "
@@ -109,14 +125,17 @@ def main():
     bags = w.n_bags
 
     # algorithmic bytes per launch (rows counted once per unique id)
-    b_lookup = 4 * N + 4 * U + U * R + bags * R + (0 if w.one_hot else 8 * bags)
-    b_update = bags * R + 4 * N + 4 * U + 4 * U * R
+    extra = 0 if w.one_hot else 8 * bags
+    b_lookup = 4 * N + 4 * U + U * R + bags * R + extra
+    b_update = bags * R + 4 * N + 4 * U + 4 * U * R + extra          # sfc_backward_update as a whole
     kernels = {
         "k_lookup": (b_lookup, ms["lookup"]),
-        "k_seg_update": (b_update, ms["k_seg_update"]),
+        "k_seg_stream": (bags * R + 4 * N + U * R + extra, ms["k_seg_stream"]),   # grad + grouping in, common out
+        "k_adagrad_rows": (4 * U + U * R + 4 * U * R, ms["k_adagrad_rows"]),
     }
     dom = max(kernels, key=lambda k: kernels[k][1])
     ach = kernels[dom][0] / (kernels[dom][1] * 1e-3) / 1e9
+    traffic = measured_traffic(w.name, dom)
     pair_bytes = b_lookup + b_update
     pair_ms = ms["lookup"] + ms["backward_update"]
     link_ms = ms["fetch_misses"]
@@ -141,7 +160,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": ach / HBM_PEAK_GBS, "traffic": None,
+            "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
             "algorithmic_bytes_per_launch": kernels[dom][0], "avg_ms": kernels[dom][1],
         },
         "kernels": {k: {"algorithmic_bytes": v[0], "avg_ms": v[1],
@@ -150,6 +169,7 @@ def main():
                                "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
                                "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "call_ms": {k: ms[k] for k in ("prepare", "fetch_misses", "lookup", "backward_update")},
+        "kernel_ms": {k: ms[k] for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows")},
         "host_link": {"h2d_bytes_per_step": avg["h2d_bytes"], "d2h_bytes_per_step": avg["d2h_bytes"],
                       "GB/s": ((avg["h2d_bytes"] + avg["d2h_bytes"]) / (link_ms * 1e-3) / 1e9
                                if link_ms else None)},
@@ -180,6 +200,15 @@ def main():
                       "%.1f s of single-thread oracle time (host has %d logical CPUs)"
                       % (steps_done, cpu_t, os.cpu_count()),
         }
+    if args.calibrate_copy:
+        # a plain copy-like kernel of known size, with an instantiation nothing else in this
+        # process uses (uint8 xor): 2^30 bytes read + 2^30 bytes written per launch, 3 launches
+        a = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.bitwise_xor(a, 3, out=b)
+        torch.cuda.synchronize()
+        del a, b
     cache.close()
     print(json.dumps(result), flush=True)
 

@@ -160,10 +160,10 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
 
 /*
  * Device timing.  When enabled, hipEvents bracket the work of each step call on the stream it
- * runs on, and the fused segment-sum + Adagrad kernels inside sfc_backward_update separately.
- * sfc_profile_read waits for the streams and returns, for which = 0..4 (prepare, fetch_misses,
- * lookup, backward_update, segment-sum+Adagrad kernels), the summed milliseconds and the number
- * of launches since the last read of that entry.
+ * runs on, and the three kernels inside sfc_backward_update separately.  sfc_profile_read waits
+ * for the streams and returns, for which = 0..6 (prepare, fetch_misses, lookup, backward_update,
+ * segment-sum stream kernel, segment-sum finish kernel, Adagrad kernel), the summed milliseconds
+ * and the number of launches since the last read of that entry.
  */
 int sfc_profile_enable(sfc_cache* c, int32_t on);
 int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);

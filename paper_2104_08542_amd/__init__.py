@@ -175,7 +175,8 @@ def sfc_profile_enable(h, on: bool):
     _check(_lib.sfc_profile_enable(ctypes.c_void_p(h), 1 if on else 0))
 
 
-PROFILE_CALLS = ("prepare", "fetch_misses", "lookup", "backward_update", "k_seg_update")
+PROFILE_CALLS = ("prepare", "fetch_misses", "lookup", "backward_update", "k_seg_stream",
+                 "k_seg_finish", "k_adagrad_rows")
 
 
 def sfc_profile_read(h) -> dict:

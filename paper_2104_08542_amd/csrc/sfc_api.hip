@@ -37,7 +37,8 @@ int fail(int code, const char* what, hipError_t e = hipSuccess) {
   } while (0)
 
 enum State { IDLE = 0, PREPARED = 1, FETCHED = 2 };
-enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEGSUM = 4, P_N = 5 };
+enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEG_STREAM = 4, P_SEG_FINISH = 5,
+       P_ADAGRAD = 6, P_N = 7 };
 
 struct EventPair { hipEvent_t a, b; };
 
@@ -147,15 +148,21 @@ int prof_collect(sfc_cache* c) {
 // Segment-sum over perm64, then either the Adagrad update (EMIT = false) or the common-gradient
 // matrix (EMIT = true).  Two kernels: per-block runs, then the block-edge partials.
 // common[v] = segment sum of d_grad over perm64: the stream, then the block-edge partials.
-void seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
+int seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
   const int n = (int)c->n_ids;
-  if (n <= 0) return;
+  if (n <= 0) return SFC_OK;
   const SegGeom g = seg_geom(c->D, n);
   const int nblk = (g.waves + 3) / 4;
+  EventPair e1{}, e2{};
+  int rc;
+  if ((rc = prof_begin(c, P_SEG_STREAM, c->st, &e1))) return rc;
   hipLaunchKernelGGL(k_seg_stream, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
                      c->perm64, n, c->d4, g.G, g.L, (float4*)d_common, c->bp, c->bp_vid);
+  if ((rc = prof_end(c, P_SEG_STREAM, c->st, &e1))) return rc;
+  if ((rc = prof_begin(c, P_SEG_FINISH, c->st, &e2))) return rc;
   hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, c->bp,
                      c->bp_vid, 2 * nblk, c->d4, (float4*)d_common);
+  return prof_end(c, P_SEG_FINISH, c->st, &e2);
 }
 
 constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
@@ -426,7 +433,8 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (c->state == IDLE) return fail(SFC_ESTATE, "sfc_segment_sum needs a preceding sfc_prepare");
   if ((c->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
-  seg_launch(c, d_grad, d_common_grad);
+  int rc = seg_launch(c, d_grad, d_common_grad);
+  if (rc) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -440,12 +448,12 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   EventPair ep{}, e1{};
   int rc;
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
-  if ((rc = prof_begin(c, P_SEGSUM, s, &e1))) return rc;
-  seg_launch(c, d_grad, c->gsum);
+  if ((rc = seg_launch(c, d_grad, c->gsum))) return rc;
+  if ((rc = prof_begin(c, P_ADAGRAD, s, &e1))) return rc;
   hipLaunchKernelGGL(k_adagrad_rows, dim3(grid_for(c->n_ids * c->d4, 1024, kGridCap)), dim3(256), 0,
                      s, (const float4*)c->gsum, c->d_slot, (float4*)c->cw, (float4*)c->ca,
                      c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
-  if ((rc = prof_end(c, P_SEGSUM, s, &e1))) return rc;
+  if ((rc = prof_end(c, P_ADAGRAD, s, &e1))) return rc;
   hipLaunchKernelGGL(k_writeback_bypass, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0,
                      s, c->d_miss, c->d_unique, c->d_slot, (const float4*)c->cw,
                      (const float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
