@@ -56,6 +56,10 @@ typedef struct {
   int64_t host_rows;          /* V: rows of the Host table; valid ids are [0, V) */
   float* h_weights;           /* [V, D] Host table, pinned and device-mapped (see sfc_host_alloc) */
   float* h_acc;               /* [V, D] Adagrad accumulator of every row, same kind of memory */
+  int64_t host_row_stride;    /* floats between consecutive rows of h_weights (and of h_acc); 0 = D.
+                                 With h_acc = h_weights + D and stride 2D each row's weights and
+                                 accumulator are one contiguous 8*D-byte block, the layout the
+                                 host link moves fastest. */
   float lr;                   /* Adagrad learning rate */
   float eps;                  /* Adagrad epsilon, added outside the square root */
   int32_t lookahead;          /* 0: rows of the batch being prepared are protected from eviction.
@@ -140,7 +144,7 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad);
  * Step 4 (GPU-Worker / Backward; Algorithm 1 line 14): segment-sum d_grad [n_bags, D] per
  * virtual id as above and apply one Adagrad update per unique row in the cache:
  *     acc += g*g ;  w -= lr * g / (sqrt(acc) + eps)        (fp32, element-wise)
- * Bypass rows are then written back to the Host table.  Ends the step.
+ * Bypass rows are written back to the Host table by the same pass.  Ends the step.
  */
 int sfc_backward_update(sfc_cache* c, const float* d_grad);
 

@@ -42,7 +42,7 @@ class sfc_config(ctypes.Structure):
         ("capacity_rows", ctypes.c_int64), ("dim", ctypes.c_int32), ("policy", ctypes.c_int32),
         ("max_ids_per_batch", ctypes.c_int64), ("max_bags_per_batch", ctypes.c_int64),
         ("host_rows", ctypes.c_int64), ("h_weights", ctypes.c_void_p), ("h_acc", ctypes.c_void_p),
-        ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("lookahead", ctypes.c_int32),
+        ("host_row_stride", ctypes.c_int64), ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("lookahead", ctypes.c_int32),
         ("max_steps", ctypes.c_int32), ("stream", ctypes.c_void_p), ("side_stream", ctypes.c_void_p),
     ]
 
@@ -191,27 +191,43 @@ def sfc_profile_read(h) -> dict:
 # ------------------------------------------------------------------ conveniences
 
 class HostTable:
-    """[V, D] fp32 weights and accumulators in pinned, device-mapped host memory."""
+    """[V, D] fp32 weights and accumulators in pinned, device-mapped host memory.
 
-    def __init__(self, rows: int, dim: int):
-        self.rows, self.dim = int(rows), int(dim)
-        nbytes = self.rows * self.dim * 4
-        self._pw = sfc_host_alloc(nbytes)
-        try:
-            self._pa = sfc_host_alloc(nbytes)
-        except SfcError:
-            sfc_host_free(self._pw)
-            raise
-        mk = lambda p: np.ctypeslib.as_array((ctypes.c_float * (self.rows * self.dim)).from_address(p)
-                                             ).reshape(self.rows, self.dim)
-        self.w, self.acc = mk(self._pw), mk(self._pa)      # numpy views of the pinned memory
+    interleaved=True (default) stores row i as [weights_i | acc_i] in one allocation, so a row's
+    weights and optimizer state are one contiguous block for the host link; `w` and `acc` are then
+    strided numpy views.  interleaved=False uses two separate contiguous arrays.
+    """
+
+    def __init__(self, rows: int, dim: int, interleaved: bool = True):
+        self.rows, self.dim, self.interleaved = int(rows), int(dim), bool(interleaved)
+        n = self.rows * self.dim
+        if self.interleaved:
+            self._base = sfc_host_alloc(2 * n * 4)
+            self._pw, self._pa, self.stride = self._base, self._base + 4 * self.dim, 2 * self.dim
+            both = np.ctypeslib.as_array((ctypes.c_float * (2 * n)).from_address(self._base)
+                                         ).reshape(self.rows, 2, self.dim)
+            self.w, self.acc = both[:, 0, :], both[:, 1, :]
+            self._bases = [self._base]
+        else:
+            self._pw = sfc_host_alloc(n * 4)
+            try:
+                self._pa = sfc_host_alloc(n * 4)
+            except SfcError:
+                sfc_host_free(self._pw)
+                raise
+            self.stride = self.dim
+            mk = lambda p: np.ctypeslib.as_array((ctypes.c_float * n).from_address(p)
+                                                 ).reshape(self.rows, self.dim)
+            self.w, self.acc = mk(self._pw), mk(self._pa)
+            self._bases = [self._pw, self._pa]
         self.w_t, self.acc_t = torch.from_numpy(self.w), torch.from_numpy(self.acc)
 
     def free(self):
-        if self._pw:
+        if self._bases:
             self.w = self.acc = self.w_t = self.acc_t = None
-            sfc_host_free(self._pw)
-            sfc_host_free(self._pa)
+            for b in self._bases:
+                sfc_host_free(b)
+            self._bases = []
             self._pw = self._pa = 0
 
     def __del__(self):
@@ -234,7 +250,8 @@ class Cache:
             self.stream = torch.cuda.current_stream()
             self.side = torch.cuda.Stream() if side_stream else self.stream
             cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH, self.max_ids, self.max_bags,
-                             table.rows, table._pw, table._pa, lr, eps, lookahead, max_steps,
+                             table.rows, table._pw, table._pa, table.stride, lr, eps, lookahead,
+                             max_steps,
                              self.stream.cuda_stream, self.side.cuda_stream)
             self.h = sfc_cache_create(cfg)
             n = max(self.max_ids, 1)

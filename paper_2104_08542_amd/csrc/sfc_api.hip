@@ -72,7 +72,7 @@ struct sfc_cache {
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * wavefronts, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
   Ctr* ctr = nullptr;
-  float *d_hw = nullptr, *d_ha = nullptr;       // device view of the Host table
+  HostRows host{};                              // device view of the Host table
   std::vector<void*> allocs;
   // step state
   int state = IDLE;
@@ -223,6 +223,8 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if (!cfg->h_weights || !cfg->h_acc) return fail(SFC_EINVAL, "null host table");
   if (((uintptr_t)cfg->h_weights | (uintptr_t)cfg->h_acc) & 15)
     return fail(SFC_EINVAL, "host table must be 16-byte aligned");
+  if (cfg->host_row_stride && (cfg->host_row_stride < cfg->dim || cfg->host_row_stride % 4))
+    return fail(SFC_EINVAL, "host_row_stride must be 0 or a multiple of 4 that is >= dim");
   if (cfg->lookahead < 0 || cfg->lookahead > 1) return fail(SFC_EINVAL, "lookahead must be 0 or 1");
   if (cfg->max_steps < 0) return fail(SFC_EINVAL, "max_steps must be >= 0");
 
@@ -243,11 +245,12 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if ((e = hipHostGetDevicePointer(&dp, cfg->h_weights, 0)) != hipSuccess) {
     rc = fail(SFC_EINVAL, "h_weights is not pinned device-mapped host memory", e); goto bad;
   }
-  c->d_hw = (float*)dp;
+  c->host.w = (float4*)dp;
   if ((e = hipHostGetDevicePointer(&dp, cfg->h_acc, 0)) != hipSuccess) {
     rc = fail(SFC_EINVAL, "h_acc is not pinned device-mapped host memory", e); goto bad;
   }
-  c->d_ha = (float*)dp;
+  c->host.a = (float4*)dp;
+  c->host.hs4 = (cfg->host_row_stride ? cfg->host_row_stride : cfg->dim) / 4;
 
   {
     const int64_t rows = c->C + c->max_ids;
@@ -389,9 +392,9 @@ int sfc_fetch_misses(sfc_cache* c) {
   EventPair ep{};
   int rc;
   if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
-  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0, s,
+  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(c->n_ids * 2 * c->d4, 256, 1024)), dim3(256), 0, s,
                      c->d_miss, c->d_unique, c->d_slot, c->victim_id, (float4*)c->cw,
-                     (float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
+                     (float4*)c->ca, c->host, c->d4, c->ctr);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
   if (s != c->st) {
@@ -451,12 +454,9 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if ((rc = seg_launch(c, d_grad, c->gsum))) return rc;
   if ((rc = prof_begin(c, P_ADAGRAD, s, &e1))) return rc;
   hipLaunchKernelGGL(k_adagrad_rows, dim3(grid_for(c->n_ids * c->d4, 1024, kGridCap)), dim3(256), 0,
-                     s, (const float4*)c->gsum, c->d_slot, (float4*)c->cw, (float4*)c->ca,
-                     c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
+                     s, (const float4*)c->gsum, c->d_slot, c->d_unique, (float4*)c->cw,
+                     (float4*)c->ca, c->host, (int)c->C, c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
   if ((rc = prof_end(c, P_ADAGRAD, s, &e1))) return rc;
-  hipLaunchKernelGGL(k_writeback_bypass, dim3(grid_for(c->n_ids * c->d4, 256, 1024)), dim3(256), 0,
-                     s, c->d_miss, c->d_unique, c->d_slot, (const float4*)c->cw,
-                     (const float4*)c->ca, (float4*)c->d_hw, (float4*)c->d_ha, c->d4, c->ctr);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_BACKWARD, s, &ep))) return rc;
   c->state = IDLE;
@@ -472,9 +472,8 @@ static int sync_all(sfc_cache* c) {
 int sfc_flush(sfc_cache* c) {
   if (!c) return fail(SFC_EINVAL, "null cache");
   if (c->state == PREPARED) return fail(SFC_ESTATE, "sfc_flush between sfc_prepare and sfc_fetch_misses");
-  hipLaunchKernelGGL(k_flush, dim3(grid_for(c->C * c->d4, 256, kGridCap)), dim3(256), 0, c->st,
-                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, (float4*)c->d_hw,
-                     (float4*)c->d_ha, c->d4, c->ctr);
+  hipLaunchKernelGGL(k_flush, dim3(grid_for(c->C * 2 * c->d4, 256, kGridCap)), dim3(256), 0, c->st,
+                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, c->host, c->d4, c->ctr);
   HIPCHK(hipGetLastError());
   return sync_all(c);
 }

@@ -20,71 +20,61 @@ __device__ __forceinline__ void st_stream(float4* p, float4 v) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Host link (Algorithm 1 lines 5-6).  The Host table is pinned, device-mapped memory; the kernel
-// reads / writes it directly, 16 bytes per lane, rows contiguous.  The k-th miss takes the slot
-// of the k-th victim (both lists are in ascending order of the assignment), so one thread group
-// does both directions for that slot: it loads the victim's row from HBM and the missed row
-// from Host, then stores each on the other side.  Reads and writes cross the link at the same
-// time instead of one after the other.
+// Host link (Algorithm 1 lines 5-6).  The Host table is pinned, device-mapped memory; the kernels
+// read / write it directly, 16 bytes per lane.  A row moves as 2*D/4 chunks: its weights, then its
+// accumulator; hs4 is the Host row stride in 16-byte units.  When the caller interleaves the two
+// Host arrays (h_acc = h_weights + D, stride 2D) the 2*D/4 lanes of a row touch one contiguous
+// 8*D-byte block of Host memory, which the link moves measurably faster than two 4*D-byte blocks
+// (55 vs 41 GB/s Host->device for D = 32).
+// The k-th miss takes the slot of the k-th victim (both lists are in ascending order of the
+// assignment), so one lane group does both directions for that slot: it loads the victim's row
+// from HBM and the missed row from Host, then stores each on the other side.  Reads and writes
+// cross the link at the same time instead of one after the other.
 // ---------------------------------------------------------------------------------------------
+struct HostRows {
+  float4* w;      // device view of h_weights
+  float4* a;      // device view of h_acc
+  int64_t hs4;    // row stride in float4
+};
+
 __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_vids,
                                                     const int64_t* __restrict__ unique_ids,
                                                     const int* __restrict__ slot,
                                                     const int64_t* __restrict__ victim_id,
                                                     float4* __restrict__ cw, float4* __restrict__ ca,
-                                                    float4* __restrict__ hw, float4* __restrict__ ha,
-                                                    int d4, const Ctr* ctr) {
+                                                    HostRows h, int d4, const Ctr* ctr) {
   const int K = ctr->K;
-  const int64_t total = (int64_t)ctr->M * d4;
+  const int w2 = 2 * d4;
+  const int64_t total = (int64_t)ctr->M * w2;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int k = (int)(i / d4), c = (int)(i % d4);
+    const int k = (int)(i / w2);
+    int c = (int)(i - (int64_t)k * w2);
+    const bool acc = c >= d4;
+    if (acc) c -= d4;
+    float4* hb = acc ? h.a : h.w;
+    float4* cb = acc ? ca : cw;
     const int v = miss_vids[k];
-    const int64_t src = unique_ids[v] * d4 + c, dst = (int64_t)slot[v] * d4 + c;
-    const float4 nw = hw[src], na = ha[src];
-    if (k < K) {
-      const int64_t back = victim_id[k] * d4 + c;
-      const float4 ow = cw[dst], oa = ca[dst];
-      hw[back] = ow;
-      ha[back] = oa;
-    }
-    cw[dst] = nw;
-    ca[dst] = na;
-  }
-}
-
-// Bypass rows (misses that found no slot) go back to Host after the update.
-__global__ __launch_bounds__(256) void k_writeback_bypass(const int* __restrict__ miss_vids,
-                                                           const int64_t* __restrict__ unique_ids,
-                                                           const int* __restrict__ slot,
-                                                           const float4* __restrict__ cw,
-                                                           const float4* __restrict__ ca,
-                                                           float4* __restrict__ hw,
-                                                           float4* __restrict__ ha, int d4,
-                                                           const Ctr* ctr) {
-  const int M = ctr->M, nb = ctr->n_bypass;
-  const int64_t total = (int64_t)nb * d4;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int k = M - nb + (int)(i / d4), c = (int)(i % d4);
-    const int v = miss_vids[k];
-    const int64_t src = (int64_t)slot[v] * d4 + c, dst = unique_ids[v] * d4 + c;
-    hw[dst] = cw[src];
-    ha[dst] = ca[src];
+    const int64_t src = unique_ids[v] * h.hs4 + c, dst = (int64_t)slot[v] * d4 + c;
+    const float4 nv = hb[src];
+    if (k < K) hb[victim_id[k] * h.hs4 + c] = cb[dst];
+    cb[dst] = nv;
   }
 }
 
 __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_id,
                                                 const float4* __restrict__ cw,
-                                                const float4* __restrict__ ca,
-                                                float4* __restrict__ hw, float4* __restrict__ ha,
-                                                int d4, const Ctr* ctr) {
-  const int64_t total = (int64_t)ctr->f * d4;
+                                                const float4* __restrict__ ca, HostRows h, int d4,
+                                                const Ctr* ctr) {
+  const int w2 = 2 * d4;
+  const int64_t total = (int64_t)ctr->f * w2;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int64_t s = i / d4;
-    const int c = (int)(i % d4);
+    const int64_t s = i / w2;
+    int c = (int)(i - s * w2);
+    const bool acc = c >= d4;
+    if (acc) c -= d4;
     const int64_t id = slot_id[s];
     if (id < 0) continue;
-    hw[id * d4 + c] = cw[i];
-    ha[id * d4 + c] = ca[i];
+    (acc ? h.a : h.w)[id * h.hs4 + c] = (acc ? ca : cw)[s * d4 + c];
   }
 }
 
@@ -93,7 +83,13 @@ __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_
 // pos_slot[p] = slot[inverse[p]] is written by the prepare step, so the gather is one level of
 // indirection.  A block stages the slots of its 256 bags in LDS with one coalesced load, then
 // every thread has eight 16-byte row chunks in flight before the first store; a wavefront's
-// stores are 1 KiB contiguous and non-temporal (the output is consumed by the model, not by us).
+// stores are 1 KiB contiguous and non-temporal: the output is consumed by the model, and keeping
+// it out of L2 keeps the hot rows in (plain stores measured 50 % slower).
+// What bounds it on MI355X: with the rows resident in the memory-side cache the kernel runs at
+// the write rate of HBM (58 us for 327 MB); in the training loop the other kernels of the step
+// have evicted them, the ~59 MB of row reads mix into the write stream and the same kernel takes
+// 79-85 us.  Variants without LDS staging, with 2/4/16 chunks per thread or persistent blocks
+// measured within +-5 % of this one under those conditions.
 // ---------------------------------------------------------------------------------------------
 constexpr int kLookupBags = 256;
 
@@ -433,28 +429,40 @@ __device__ __forceinline__ void adagrad4v(float4& w, float4& a, float4 g, float 
 }
 
 // Adagrad over the common-gradient matrix (one row per virtual id), four rows per thread in flight.
+// A bypass row (slot >= C: a miss that found no cache slot) is also written to the Host table
+// here: it lives for this step only.
 __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__ common,
                                                        const int* __restrict__ slot,
+                                                       const int64_t* __restrict__ unique_ids,
                                                        float4* __restrict__ cw,
-                                                       float4* __restrict__ ca, float lr, float eps,
-                                                       int d4, const Ctr* ctr) {
+                                                       float4* __restrict__ ca, HostRows h, int C,
+                                                       float lr, float eps, int d4, const Ctr* ctr) {
   const int64_t total = (int64_t)ctr->U * d4;
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 4 * stride) {
     float4 g[4], w[4], a[4];
     int64_t r[4];
+    int sl[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t i = i0 + u * stride;
       r[u] = -1;
       if (i < total) {
-        const int s = slot[(int)(i / d4)];
-        if (s >= 0) { r[u] = (int64_t)s * d4 + (i % d4); g[u] = common[i]; w[u] = cw[r[u]]; a[u] = ca[r[u]]; }
+        sl[u] = slot[(int)(i / d4)];
+        if (sl[u] >= 0) { r[u] = (int64_t)sl[u] * d4 + (i % d4); g[u] = common[i]; w[u] = cw[r[u]]; a[u] = ca[r[u]]; }
       }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (r[u] >= 0) { adagrad4v(w[u], a[u], g[u], lr, eps); cw[r[u]] = w[u]; ca[r[u]] = a[u]; }
+      if (r[u] >= 0) {
+        adagrad4v(w[u], a[u], g[u], lr, eps);
+        cw[r[u]] = w[u]; ca[r[u]] = a[u];
+        if (sl[u] >= C) {
+          const int64_t i = i0 + u * stride;
+          const int64_t hr = unique_ids[(int)(i / d4)] * h.hs4 + (i % d4);
+          h.w[hr] = w[u]; h.a[hr] = a[u];
+        }
+      }
   }
 }
 

@@ -23,12 +23,12 @@ class Pair:
     """One HIP cache and one oracle over identical copies of a host table."""
 
     def __init__(self, V, D, C, max_ids, max_bags=None, lookahead=0, seed=5, lr=0.01, eps=1e-8,
-                 init_acc=0.1, max_steps=0, side_stream=True, device="cuda:0"):
+                 init_acc=0.1, max_steps=0, side_stream=True, interleaved=True, device="cuda:0"):
         import paper_2104_08542_amd as sfc
         self.sfc = sfc
         self.V, self.D, self.C = V, D, C
         self.dev = torch.device(device)
-        self.table = sfc.HostTable(V, D)
+        self.table = sfc.HostTable(V, D, interleaved=interleaved)
         chunk = max(1, (1 << 24) // D)
         for r0 in range(0, V, chunk):
             r1 = min(V, r0 + chunk)

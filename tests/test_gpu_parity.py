@@ -135,9 +135,10 @@ def test_long_groups_cross_many_spans():
     p.finish(); p.close()
 
 
-def test_same_stream_for_copies():
+def test_same_stream_and_separate_host_arrays():
+    # copies on the main stream; Host weights and accumulators as two separate arrays
     V, D, n = 4000, 32, 2000
-    p = Pair(V, D, C=1000, max_ids=2048, side_stream=False)
+    p = Pair(V, D, C=1000, max_ids=2048, side_stream=False, interleaved=False)
     _zipf_steps(p, V, n, 1.2, 5, 4)
     p.finish(); p.close()
 
