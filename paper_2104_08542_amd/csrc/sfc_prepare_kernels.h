@@ -20,11 +20,16 @@ constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
 // Same-address atomics serialise at the memory side (about 10 ns each on this chip), and the
 // hottest id of a power-law batch owns a fifth of all positions.  So each block first
 // deduplicates its 2048 positions in an LDS table (key -> smallest position in the block) and
-// only the distinct keys of the block go to HBM; there a device-coherent load comes first and
-// the atomic is issued only if the load has not already seen the key / a smaller position.
+// only the distinct keys of the block go to HBM, four per thread in flight.  There a plain load
+// comes first (the table entry of a key never changes once set, and a stale smallest-position
+// word can only be too large), and an atomic is issued only when the load has not already seen
+// the key / a small enough position.
+// hslot[p] = HBM table entry of position p; bit 31 marks the one position per (block, key) that
+// can still be the key's first appearance, so the later passes test only those.
 // ---------------------------------------------------------------------------------------------
 constexpr int kUniqChunk = 2048;   // positions per block
 constexpr int kLdsTab = 4096;      // LDS table entries per block
+constexpr unsigned kCandBit = 0x80000000u;
 
 template <typename T>
 __device__ __forceinline__ T coherent_load(const T* p) {
@@ -36,8 +41,12 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
                                                       uint32_t hu, int* __restrict__ hslot,
                                                       Ctr* ctr) {
   __shared__ int64_t lkey[kLdsTab];
-  __shared__ int lmin[kLdsTab];     // smallest position of the key in this block; later: its HBM entry
-  for (int i = threadIdx.x; i < kLdsTab; i += 256) { lkey[i] = kEmpty; lmin[i] = kIntMax; }
+  __shared__ int lval[kLdsTab];               // smallest position of the key in this block; later its HBM entry
+  __shared__ unsigned short lst[kUniqChunk];  // occupied LDS entries, compacted
+  __shared__ unsigned cand[kUniqChunk / 32];  // bit per position of the block: block-local first of its key
+  __shared__ int smem[20];
+  for (int i = threadIdx.x; i < kLdsTab; i += 256) { lkey[i] = kEmpty; lval[i] = kIntMax; }
+  if (threadIdx.x < kUniqChunk / 32) cand[threadIdx.x] = 0;
   __syncthreads();
   const int base = blockIdx.x * kUniqChunk;
   int ls[8];
@@ -60,36 +69,79 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
         }
         l = (l + 1) & (kLdsTab - 1);
       }
-      if (lmin[l] > p) atomicMin(&lmin[l], p);
+      if (lval[l] > p) atomicMin(&lval[l], p);
       ls[j] = (int)l;
     }
     const uint64_t b = __ballot(invalid);
     if (b && lane_id() == 0) atomicAdd(&ctr->n_invalid, __popcll(b));
   }
   __syncthreads();
-  for (int e = threadIdx.x; e < kLdsTab; e += 256) {
-    const int64_t key = lkey[e];
-    if (key == kEmpty) continue;
-    uint32_t h = bucket_of(key, hu);
-    for (uint32_t probes = 0; probes < hu; ++probes) {
-      const int64_t k = coherent_load(&ukeys[h]);
-      if (k == key) break;
-      if (k == kEmpty) {
-        const int64_t old = (int64_t)atomicCAS((unsigned long long*)&ukeys[h],
-                                               (unsigned long long)kEmpty, (unsigned long long)key);
-        if (old == kEmpty || old == key) break;
+  // compact the occupied entries (16 consecutive entries per thread)
+  int nocc;
+  {
+    unsigned occ = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (lkey[threadIdx.x * 16 + k] != kEmpty) occ |= 1u << k;
+    int at = block_excl_scan(__popc(occ), nocc, smem);
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (occ & (1u << k)) lst[at++] = (unsigned short)(threadIdx.x * 16 + k);
+  }
+  __syncthreads();
+  // distinct keys of the block -> HBM table, four per thread in flight
+  for (int i0 = threadIdx.x; i0 < nocc; i0 += 256 * 4) {
+    int e[4], pm[4];
+    int64_t key[4], k0[4];
+    uint32_t h[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * 256;
+      e[u] = -1;
+      if (i < nocc) {
+        e[u] = lst[i];
+        key[u] = lkey[e[u]];
+        pm[u] = lval[e[u]];
+        h[u] = bucket_of(key[u], hu);
+        k0[u] = ukeys[h[u]];
       }
-      h = h + 1 == hu ? 0 : h + 1;
     }
-    const int pm = lmin[e];
-    if (coherent_load(&uminpos[h]) > pm) atomicMin(&uminpos[h], pm);
-    lmin[e] = (int)h;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (e[u] < 0) continue;
+      int64_t k = k0[u];
+      for (uint32_t probes = 0; probes < hu; ++probes) {
+        if (k == key[u]) break;
+        if (k == kEmpty) {
+          k = (int64_t)atomicCAS((unsigned long long*)&ukeys[h[u]], (unsigned long long)kEmpty,
+                                 (unsigned long long)key[u]);
+          if (k == kEmpty || k == key[u]) break;
+        }
+        h[u] = h[u] + 1 == hu ? 0 : h[u] + 1;
+        k = coherent_load(&ukeys[h[u]]);
+      }
+    }
+    int m0[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) m0[u] = e[u] >= 0 ? uminpos[h[u]] : 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (e[u] < 0) continue;
+      if (m0[u] > pm[u] && coherent_load(&uminpos[h[u]]) > pm[u]) atomicMin(&uminpos[h[u]], pm[u]);
+      lval[e[u]] = (int)h[u];
+      const int q = pm[u] - base;
+      atomicOr(&cand[q >> 5], 1u << (q & 31));
+    }
   }
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int p = base + j * 256 + (int)threadIdx.x;
-    if (p < n) hslot[p] = lmin[ls[j]];
+    const int q = j * 256 + (int)threadIdx.x;
+    const int p = base + q;
+    if (p < n) {
+      const unsigned c = (cand[q >> 5] >> (q & 31)) & 1u;
+      hslot[p] = (int)((unsigned)lval[ls[j]] | (c ? kCandBit : 0u));
+    }
   }
 }
 
@@ -103,7 +155,10 @@ __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslo
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int p = base + j;
-    if (p < n) c += (uminpos[hslot[p]] == p);
+    if (p < n) {
+      const unsigned hs = (unsigned)hslot[p];
+      if ((hs & kCandBit) && uminpos[hs & ~kCandBit] == p) ++c;
+    }
   }
   const int tot = block_sum(c, smem);
   if (threadIdx.x == 0) blk_cnt[blockIdx.x] = tot;
@@ -147,8 +202,9 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
     const int p = base + j;
     hs[j] = 0;
     if (p < n) {
-      hs[j] = hslot[p];
-      if (uminpos[hs[j]] == p) { flags |= 1u << j; ++c; }
+      const unsigned raw = (unsigned)hslot[p];
+      hs[j] = (int)(raw & ~kCandBit);
+      if ((raw & kCandBit) && uminpos[hs[j]] == p) { flags |= 1u << j; ++c; }
     }
   }
   int tot;
@@ -183,7 +239,7 @@ __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hs
   for (int j = 0; j < 8; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     if (p < n) {
-      const int v = uvid[hslot[p]];
+      const int v = uvid[(unsigned)hslot[p] & ~kCandBit];
       inverse[p] = v;
       if (v < kHotBins) atomicAdd(&lh[v], 1);
       else atomicAdd(&cnt[v], 1);
@@ -241,9 +297,14 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
     }
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < kHotBins; b += 256) {
-    const int c = lh[b];
-    if (c) lh[b] = atomicAdd(&cursor[b], c);
+  for (int b0 = threadIdx.x; b0 < kHotBins; b0 += 256 * 4) {
+    int c[4], r[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) c[u] = lh[b0 + u * 256];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) r[u] = c[u] ? atomicAdd(&cursor[b0 + u * 256], c[u]) : 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (c[u]) lh[b0 + u * 256] = r[u];
   }
   __syncthreads();
 #pragma unroll
@@ -329,7 +390,7 @@ __global__ __launch_bounds__(256) void k_index_reinsert(IdxEntry* index, uint32_
 // table never needs a per-step clear, and sums cnt per tile for the segment offsets.
 // ---------------------------------------------------------------------------------------------
 constexpr int kAgeBins = 1024;
-constexpr int kResolveGrid = 128;   // rows of age_mat
+constexpr int kResolveGrid = 256;   // rows of age_mat
 
 __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
                                                   const int* __restrict__ vid_hslot,
@@ -408,6 +469,7 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
   {
     const int a = (int)threadIdx.x;
     int sum = 0;
+#pragma unroll 8
     for (int g = 0; g < age_rows; ++g) sum += age_mat[g * kAgeBins + a];
     if (a == 0) { hist[t] += sum; ctr->n_hit = sum; }
     else if (sum) hist[t - a] -= sum;
