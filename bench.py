@@ -102,11 +102,11 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
 
-    # pass 2: K more steps with hipEvents around every call and the two backward kernels
-    # (same batches' successors, so the cache keeps evolving as in training)
+    # pass 2: K more steps with hipEvents around every step call (the next batches of the same
+    # sequence, so the cache keeps evolving as in training); device counters sampled on the way
     batches2 = [w.batch_ids(W + K + t, dev) for t in range(K)]
     torch.cuda.synchronize()
-    sfc.sfc_profile_enable(cache.h, True)
+    sfc.sfc_profile_enable(cache.h, 1)
     agg = dict(n_unique=0, n_hit=0, n_miss=0, n_evict=0, n_bypass=0, h2d_bytes=0, d2h_bytes=0)
     ns = 0
     for t in range(K):
@@ -117,7 +117,16 @@ def main():
                 agg[k] += st[k]
             ns += 1
     prof = sfc.sfc_profile_read(cache.h)
-    sfc.sfc_profile_enable(cache.h, False)
+    # pass 3: K more steps with events around the kernels inside backward_update as well
+    batches3 = [w.batch_ids(W + 2 * K + t, dev) for t in range(K)]
+    torch.cuda.synchronize()
+    sfc.sfc_profile_enable(cache.h, 2)
+    for t in range(K):
+        run_step(batches3[t][0], batches3[t][1], grads[t % 4])
+    prof3 = sfc.sfc_profile_read(cache.h)
+    for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows"):
+        prof[k] = prof3[k]
+    sfc.sfc_profile_enable(cache.h, 0)
     ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
     avg = {k: v / ns for k, v in agg.items()}
     N = n_ids_total / K

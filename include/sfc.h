@@ -163,13 +163,14 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out);
 int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h_rows, float* h_acc);
 
 /*
- * Device timing.  When enabled, hipEvents bracket the work of each step call on the stream it
- * runs on, and the three kernels inside sfc_backward_update separately.  sfc_profile_read waits
- * for the streams and returns, for which = 0..6 (prepare, fetch_misses, lookup, backward_update,
- * segment-sum stream kernel, segment-sum finish kernel, Adagrad kernel), the summed milliseconds
- * and the number of launches since the last read of that entry.
+ * Device timing.  level 1: hipEvents bracket the work of each step call on the stream it runs
+ * on.  level 2: also each of the three kernels inside sfc_backward_update (the extra events
+ * lengthen the call a little, so call timings are best read at level 1).  level 0: off.
+ * sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare, fetch_misses,
+ * lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel, Adagrad kernel),
+ * the summed milliseconds and the number of launches since the last read of that entry.
  */
-int sfc_profile_enable(sfc_cache* c, int32_t on);
+int sfc_profile_enable(sfc_cache* c, int32_t level);
 int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);
 
 const char* sfc_strerror(int code);

@@ -171,8 +171,8 @@ def sfc_cache_state(h, capacity_rows, dim, rows=False):
     return (sid, stp, w, a) if rows else (sid, stp)
 
 
-def sfc_profile_enable(h, on: bool):
-    _check(_lib.sfc_profile_enable(ctypes.c_void_p(h), 1 if on else 0))
+def sfc_profile_enable(h, level: int):
+    _check(_lib.sfc_profile_enable(ctypes.c_void_p(h), int(level)))
 
 
 PROFILE_CALLS = ("prepare", "fetch_misses", "lookup", "backward_update", "k_seg_stream",

@@ -56,7 +56,7 @@ struct sfc_cache {
   int* stamp = nullptr;                         // [C]
   IdxEntry* index = nullptr; uint32_t hi = 0;   // cache index
   int* hist = nullptr; int hist_len = 0;        // [max_steps + 2]
-  int64_t* ukeys = nullptr; int* uminpos = nullptr; int* uvid = nullptr;  // batch table [2*max_ids]
+  UEntry* utab = nullptr; int* uvid = nullptr;  // batch table [2*max_ids]: key + first position; vid
   int* hslot = nullptr;                         // [max_ids]
   int* vid_hslot = nullptr;                     // [max_ids]
   int* blk_cnt = nullptr;                       // [max_ids / kPosChunk + 1]
@@ -82,7 +82,7 @@ struct sfc_cache {
   int64_t* d_unique = nullptr; int32_t* d_inverse = nullptr; int32_t* d_slot = nullptr;
   int32_t* d_miss = nullptr;
   // profiling
-  bool prof = false;
+  int prof = 0;                                 // 0 off, 1 step calls, 2 also the kernels inside them
   std::vector<EventPair> pending[P_N], spare;
   double ms_sum[P_N] = {};
   int64_t calls[P_N] = {};
@@ -116,16 +116,17 @@ int grid_for(int64_t items, int per_block, int cap) {
   return (int)b;
 }
 
+bool prof_on(const sfc_cache* c, int which) { return c->prof >= (which > P_BACKWARD ? 2 : 1); }
+
 int prof_begin(sfc_cache* c, int which, hipStream_t s, EventPair* ep) {
-  if (!c->prof) return SFC_OK;
+  if (!prof_on(c, which)) return SFC_OK;
   if (!c->spare.empty()) { *ep = c->spare.back(); c->spare.pop_back(); }
   else { HIPCHK(hipEventCreate(&ep->a)); HIPCHK(hipEventCreate(&ep->b)); }
   HIPCHK(hipEventRecord(ep->a, s));
-  (void)which;
   return SFC_OK;
 }
 int prof_end(sfc_cache* c, int which, hipStream_t s, EventPair* ep) {
-  if (!c->prof) return SFC_OK;
+  if (!prof_on(c, which)) return SFC_OK;
   HIPCHK(hipEventRecord(ep->b, s));
   c->pending[which].push_back(*ep);
   return SFC_OK;
@@ -261,8 +262,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->stamp, c->C))) goto bad;
     if ((rc = dalloc(c, &c->index, (int64_t)c->hi))) goto bad;
     if ((rc = dalloc(c, &c->hist, (int64_t)c->hist_len))) goto bad;
-    if ((rc = dalloc(c, &c->ukeys, hu))) goto bad;
-    if ((rc = dalloc(c, &c->uminpos, hu))) goto bad;
+    if ((rc = dalloc(c, &c->utab, hu))) goto bad;
     if ((rc = dalloc(c, &c->uvid, hu))) goto bad;
     if ((rc = dalloc(c, &c->hslot, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->vid_hslot, c->max_ids))) goto bad;
@@ -294,8 +294,8 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     IdxEntry empty; empty.key = kEmpty; empty.slot = -1; empty.pad = 0;
     fill<IdxEntry>(s, c->index, (int64_t)c->hi, empty);
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
-    fill<int64_t>(s, c->ukeys, hu, kEmpty);
-    fill<int>(s, c->uminpos, hu, kIntMax);
+    UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
+    fill<UEntry>(s, c->utab, hu, uempty);
     Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
     if ((e = hipMemcpyAsync(c->ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&c->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
@@ -340,8 +340,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   hipLaunchKernelGGL(k_fill<int>, dim3(1), dim3(64), 0, s, &c->ctr->n_hit, (int64_t)2, 0);  // n_hit, n_invalid
   if (n > 0) {
     hipLaunchKernelGGL(k_uniq_insert, dim3((n + kUniqChunk - 1) / kUniqChunk), dim3(256), 0, s,
-                       d_ids, n, c->V, c->ukeys, c->uminpos, hu, c->hslot, c->ctr);
-    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uminpos, n,
+                       d_ids, n, c->V, c->utab, hu, c->hslot, c->ctr);
+    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
                        c->blk_cnt);
   }
   hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->ctr);
@@ -349,8 +349,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->slot_id, c->ctr);
   hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, c->ctr);
   if (n > 0) {
-    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uminpos,
-                       c->ukeys, n, c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt);
+    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
+                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt);
     hipLaunchKernelGGL(k_uniq_inverse, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uvid, n,
                        d_inverse, c->cnt);
     if (d_offsets)
@@ -358,8 +358,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                          d_offsets, (int)n_bags, n, c->pos2bag);
   }
   const int gr = grid_for(n, kVidTile, kResolveGrid);
-  hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->ukeys,
-                     c->uminpos, c->index, c->hi, c->stamp, c->hist, c->t, d_slot, c->tile_miss,
+  hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
+                     c->index, c->hi, c->stamp, c->hist, c->t, d_slot, c->tile_miss,
                      c->cnt, c->tile_cnt, c->age_mat, c->ctr);
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_mat, gr,
                      c->hist, c->t, c->cfg.lookahead, (int)c->C, c->hi, c->ctr);
@@ -508,7 +508,7 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
 
 int sfc_profile_enable(sfc_cache* c, int32_t on) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  c->prof = on != 0;
+  c->prof = on < 0 ? 0 : (on > 2 ? 2 : on);
   return SFC_OK;
 }
 

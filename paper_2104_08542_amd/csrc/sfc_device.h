@@ -33,6 +33,14 @@ struct Ctr {
   int pad;
 };
 
+// Entry of the per-step batch table: key and the smallest position that carries it, one 16-byte
+// access for both.
+struct __attribute__((aligned(16))) UEntry {
+  int64_t key;    // id, kEmpty or kNullKey
+  int32_t minpos; // kIntMax when unset
+  int32_t pad;
+};
+
 struct __attribute__((aligned(16))) IdxEntry {
   int64_t key;    // id, kEmpty or kTomb
   int32_t slot;

@@ -37,9 +37,8 @@ __device__ __forceinline__ T coherent_load(const T* p) {
 }
 
 __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__ ids, int n,
-                                                      int64_t V, int64_t* ukeys, int* uminpos,
-                                                      uint32_t hu, int* __restrict__ hslot,
-                                                      Ctr* ctr) {
+                                                      int64_t V, UEntry* utab, uint32_t hu,
+                                                      int* __restrict__ hslot, Ctr* ctr) {
   __shared__ int64_t lkey[kLdsTab];
   __shared__ int lval[kLdsTab];               // smallest position of the key in this block; later its HBM entry
   __shared__ unsigned short lst[kUniqChunk];  // occupied LDS entries, compacted
@@ -50,13 +49,19 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
   __syncthreads();
   const int base = blockIdx.x * kUniqChunk;
   int ls[8];
+  int64_t idv[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {          // all eight loads in flight before the LDS work starts
+    const int p = base + j * 256 + (int)threadIdx.x;
+    idv[j] = p < n ? ids[p] : 0;
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     bool invalid = false;
     ls[j] = 0;
     if (p < n) {
-      int64_t key = ids[p];
+      int64_t key = idv[j];
       if (key < 0 || key >= V) { key = kNullKey; invalid = true; }
       uint32_t l = (uint32_t)mix64((uint64_t)key) & (kLdsTab - 1);
       for (int probes = 0; probes < kLdsTab; ++probes) {
@@ -89,9 +94,10 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
       if (occ & (1u << k)) lst[at++] = (unsigned short)(threadIdx.x * 16 + k);
   }
   __syncthreads();
-  // distinct keys of the block -> HBM table, four per thread in flight
+  // distinct keys of the block -> HBM table, four per thread in flight; one 16-byte load brings
+  // the entry's key and its smallest position so far
   for (int i0 = threadIdx.x; i0 < nocc; i0 += 256 * 4) {
-    int e[4], pm[4];
+    int e[4], pm[4], m0[4];
     int64_t key[4], k0[4];
     uint32_t h[4];
 #pragma unroll
@@ -103,31 +109,50 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
         key[u] = lkey[e[u]];
         pm[u] = lval[e[u]];
         h[u] = bucket_of(key[u], hu);
-        k0[u] = ukeys[h[u]];
+        const int4 raw = *reinterpret_cast<const int4*>(&utab[h[u]]);
+        k0[u] = ((int64_t)(uint32_t)raw.y << 32) | (uint32_t)raw.x;
+        m0[u] = raw.z;
+      }
+    }
+    // first probe: where the plain load saw an empty entry, try to claim it; all four in flight
+    bool done[4], mine[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      mine[u] = false;
+      done[u] = e[u] < 0 || k0[u] == key[u];
+      if (!done[u] && k0[u] == kEmpty) {
+        k0[u] = (int64_t)atomicCAS((unsigned long long*)&utab[h[u]].key, (unsigned long long)kEmpty,
+                                   (unsigned long long)key[u]);
+        m0[u] = kIntMax;          // whoever owns the entry now, its position word is re-read below
+        mine[u] = k0[u] == kEmpty; // claimed by this thread: nothing to re-read, the atomic is due
       }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      if (e[u] < 0) continue;
-      int64_t k = k0[u];
+      if (done[u] || k0[u] == kEmpty || k0[u] == key[u]) continue;
+      // the entry belongs to another key: walk on (rare at load factor <= 1/2)
       for (uint32_t probes = 0; probes < hu; ++probes) {
+        h[u] = h[u] + 1 == hu ? 0 : h[u] + 1;
+        int64_t k = coherent_load(&utab[h[u]].key);
         if (k == key[u]) break;
         if (k == kEmpty) {
-          k = (int64_t)atomicCAS((unsigned long long*)&ukeys[h[u]], (unsigned long long)kEmpty,
+          k = (int64_t)atomicCAS((unsigned long long*)&utab[h[u]].key, (unsigned long long)kEmpty,
                                  (unsigned long long)key[u]);
           if (k == kEmpty || k == key[u]) break;
         }
-        h[u] = h[u] + 1 == hu ? 0 : h[u] + 1;
-        k = coherent_load(&ukeys[h[u]]);
       }
+      m0[u] = kIntMax;
     }
-    int m0[4];
+    // a plain load may be stale (too large), never too small: ask the memory side before the atomic
+    int m1[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) m0[u] = e[u] >= 0 ? uminpos[h[u]] : 0;
+    for (int u = 0; u < 4; ++u)
+      m1[u] = mine[u] ? kIntMax
+                      : ((e[u] >= 0 && m0[u] > pm[u]) ? coherent_load(&utab[h[u]].minpos) : 0);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (e[u] < 0) continue;
-      if (m0[u] > pm[u] && coherent_load(&uminpos[h[u]]) > pm[u]) atomicMin(&uminpos[h[u]], pm[u]);
+      if (m0[u] > pm[u] && m1[u] > pm[u]) atomicMin(&utab[h[u]].minpos, pm[u]);
       lval[e[u]] = (int)h[u];
       const int q = pm[u] - base;
       atomicOr(&cand[q >> 5], 1u << (q & 31));
@@ -147,7 +172,7 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
 
 // VSI pass 2: per chunk of positions, how many are the first appearance of their id.
 __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslot,
-                                                     const int* __restrict__ uminpos, int n,
+                                                     const UEntry* __restrict__ utab, int n,
                                                      int* __restrict__ blk_cnt) {
   __shared__ int smem[20];
   const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
@@ -157,7 +182,7 @@ __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslo
     const int p = base + j;
     if (p < n) {
       const unsigned hs = (unsigned)hslot[p];
-      if ((hs & kCandBit) && uminpos[hs & ~kCandBit] == p) ++c;
+      if ((hs & kCandBit) && utab[hs & ~kCandBit].minpos == p) ++c;
     }
   }
   const int tot = block_sum(c, smem);
@@ -185,8 +210,7 @@ __global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* ctr
 
 // VSI pass 3: first appearances get consecutive virtual ids in position order.
 __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hslot,
-                                                      const int* __restrict__ uminpos,
-                                                      const int64_t* __restrict__ ukeys, int n,
+                                                      const UEntry* __restrict__ utab, int n,
                                                       const int* __restrict__ blk_off,
                                                       int64_t* __restrict__ unique_ids,
                                                       int* __restrict__ uvid,
@@ -204,7 +228,7 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
     if (p < n) {
       const unsigned raw = (unsigned)hslot[p];
       hs[j] = (int)(raw & ~kCandBit);
-      if ((raw & kCandBit) && uminpos[hs[j]] == p) { flags |= 1u << j; ++c; }
+      if ((raw & kCandBit) && utab[hs[j]].minpos == p) { flags |= 1u << j; ++c; }
     }
   }
   int tot;
@@ -212,7 +236,7 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     if (flags & (1u << j)) {
-      const int64_t key = ukeys[hs[j]];
+      const int64_t key = utab[hs[j]].key;
       unique_ids[vid] = key == kNullKey ? (int64_t)-1 : key;
       uvid[hs[j]] = vid;
       vid_hslot[vid] = hs[j];
@@ -235,11 +259,19 @@ __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hs
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
   const int base = blockIdx.x * kPosChunk;
+  int hv[8], vv[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {          // eight loads in flight per level of indirection
+    const int p = base + j * 256 + (int)threadIdx.x;
+    hv[j] = p < n ? (int)((unsigned)hslot[p] & ~kCandBit) : -1;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) vv[j] = hv[j] >= 0 ? uvid[hv[j]] : -1;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
-    if (p < n) {
-      const int v = uvid[(unsigned)hslot[p] & ~kCandBit];
+    const int v = vv[j];
+    if (v >= 0) {
       inverse[p] = v;
       if (v < kHotBins) atomicAdd(&lh[v], 1);
       else atomicAdd(&cnt[v], 1);
@@ -278,23 +310,31 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
   const int base = blockIdx.x * kPosChunk;
-  int vv[8], rr[8];
+  int vv[8], rr[8], sv[8], cv[8], pay[8];
+  // three levels of indirection, eight loads in flight at each: position -> vid -> slot / count
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
-    vv[j] = -1;
-    if (p < n) {
-      const int v = inverse[p];
-      pos_slot[p] = slot[v];              // the forward gather reads slots per position
-      if (v < kHotBins) {
-        vv[j] = v;
-        rr[j] = atomicAdd(&lh[v], 1);
-      } else {
-        const int64_t e = ((int64_t)v << 32) | (uint32_t)(pos2bag ? pos2bag[p] : p);
-        const int dst = cnt[v] == 1 ? cursor[v] : atomicAdd(&cursor[v], 1);
-        perm64[dst] = e;
-      }
-    }
+    vv[j] = p < n ? inverse[p] : -1;
+    pay[j] = (p < n && pos2bag) ? pos2bag[p] : p;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    sv[j] = vv[j] >= 0 ? slot[vv[j]] : -1;
+    cv[j] = vv[j] >= kHotBins ? cnt[vv[j]] : 0;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {          // cold ids: a single occurrence needs no atomic
+    rr[j] = 0;
+    if (vv[j] >= kHotBins) rr[j] = cv[j] == 1 ? cursor[vv[j]] : atomicAdd(&cursor[vv[j]], 1);
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j * 256 + (int)threadIdx.x;
+    if (vv[j] < 0) continue;
+    pos_slot[p] = sv[j];                 // the forward gather reads slots per position
+    if (vv[j] < kHotBins) rr[j] = atomicAdd(&lh[vv[j]], 1);
+    else perm64[rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
   }
   __syncthreads();
   for (int b0 = threadIdx.x; b0 < kHotBins; b0 += 256 * 4) {
@@ -308,12 +348,9 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   }
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if (vv[j] >= 0) {
-      const int p = base + j * 256 + (int)threadIdx.x;
-      perm64[lh[vv[j]] + rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)(pos2bag ? pos2bag[p] : p);
-    }
-  }
+  for (int j = 0; j < 8; ++j)
+    if (vv[j] >= 0 && vv[j] < kHotBins)
+      perm64[lh[vv[j]] + rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -393,8 +430,7 @@ constexpr int kAgeBins = 1024;
 constexpr int kResolveGrid = 256;   // rows of age_mat
 
 __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
-                                                  const int* __restrict__ vid_hslot,
-                                                  int64_t* ukeys, int* uminpos,
+                                                  const int* __restrict__ vid_hslot, UEntry* utab,
                                                   const IdxEntry* __restrict__ index, uint32_t hi,
                                                   int* stamp, int* hist, int t,
                                                   int* __restrict__ slot_out,
@@ -407,42 +443,61 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
   for (int i = threadIdx.x; i < kAgeBins; i += 256) lage[i] = 0;
   __syncthreads();
   const int U = ctr->U;
-  for (int tile = blockIdx.x; tile * kVidTile < U; tile += gridDim.x) {
-    const int v = tile * kVidTile + (int)threadIdx.x;
-    bool hit = false, miss = false;
-    int age = 0, c = 0;
-    if (v < U) {
-      const int h = vid_hslot[v];
-      ukeys[h] = kEmpty;
-      uminpos[h] = kIntMax;
-      c = cnt[v];
-      const int64_t id = unique_ids[v];
-      if (id < 0) {
-        slot_out[v] = -1;
-      } else {
-        const int s = index_find(index, hi, id, nullptr, ctr);
-        if (s >= 0) {
-          slot_out[v] = s;
-          const int old = stamp[s];
-          stamp[s] = t;
-          age = t - old;
-          hit = true;
-          if (age >= kAgeBins) atomicSub(&hist[old], 1);
-        } else {
-          slot_out[v] = kMissMark;
-          miss = true;
-        }
+  // four tiles per iteration, so that each level of the chain vid -> id -> index entry -> stamp
+  // has four loads in flight per thread
+  for (int tile0 = blockIdx.x * 4; tile0 * kVidTile < U; tile0 += gridDim.x * 4) {
+    int hs[4], cc[4], sl[4], old[4];
+    int64_t id[4];
+    uint32_t hb[4];
+    int4 ent[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int v = (tile0 + k) * kVidTile + (int)threadIdx.x;
+      hs[k] = -1; cc[k] = 0; id[k] = -1;
+      if (v < U) { hs[k] = vid_hslot[v]; cc[k] = cnt[v]; id[k] = unique_ids[v]; }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (hs[k] >= 0) { UEntry z; z.key = kEmpty; z.minpos = kIntMax; z.pad = 0; utab[hs[k]] = z; }
+      if (id[k] >= 0) {
+        hb[k] = bucket_of(id[k], hi);
+        ent[k] = *reinterpret_cast<const int4*>(&index[hb[k]]);
       }
     }
-    // most hits were last used one step ago: count those per wavefront, the rest one by one
-    const uint64_t m1 = __ballot(hit && age == 1);
-    if (m1 && lane_id() == 0) atomicAdd(&lage[1], __popcll(m1));
-    if (hit && age > 1 && age < kAgeBins) atomicAdd(&lage[age], 1);
-    const uint64_t mh = __ballot(hit);
-    if (mh && lane_id() == 0) atomicAdd(&lage[0], __popcll(mh));
-    const int nmiss = block_sum(miss ? 1 : 0, smem);
-    const int csum = block_sum(c, smem);
-    if (threadIdx.x == 0) { tile_miss[tile] = nmiss; tile_cnt[tile] = csum; }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      sl[k] = -1;
+      if (id[k] >= 0) {
+        const int64_t k0 = ((int64_t)(uint32_t)ent[k].y << 32) | (uint32_t)ent[k].x;
+        if (k0 == id[k]) sl[k] = ent[k].z;
+        else if (k0 != kEmpty) sl[k] = index_find(index, hi, id[k], nullptr, ctr);   // walk on
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) old[k] = sl[k] >= 0 ? stamp[sl[k]] : 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int tile = tile0 + k;
+      if (tile * kVidTile >= U) break;               // uniform over the block
+      const int v = tile * kVidTile + (int)threadIdx.x;
+      const bool hit = sl[k] >= 0, miss = id[k] >= 0 && sl[k] < 0;
+      int age = 0;
+      if (v < U) slot_out[v] = hit ? sl[k] : (miss ? kMissMark : -1);
+      if (hit) {
+        stamp[sl[k]] = t;
+        age = t - old[k];
+        if (age >= kAgeBins) atomicSub(&hist[old[k]], 1);
+      }
+      // most hits were last used one step ago: count those per wavefront, the rest one by one
+      const uint64_t m1 = __ballot(hit && age == 1);
+      if (m1 && lane_id() == 0) atomicAdd(&lage[1], __popcll(m1));
+      if (hit && age > 1 && age < kAgeBins) atomicAdd(&lage[age], 1);
+      const uint64_t mh = __ballot(hit);
+      if (mh && lane_id() == 0) atomicAdd(&lage[0], __popcll(mh));
+      const int nmiss = block_sum(miss ? 1 : 0, smem);
+      const int csum = block_sum(cc[k], smem);
+      if (threadIdx.x == 0) { tile_miss[tile] = nmiss; tile_cnt[tile] = csum; }
+    }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < kAgeBins; i += 256) age_mat[blockIdx.x * kAgeBins + i] = lage[i];
