@@ -62,3 +62,40 @@ def test_target_configuration_full_size():
     p.finish()
     _say("flushed tables compared after %.0fs" % (time.time() - t0))
     p.close()
+
+
+def test_multihot_configuration_shape():
+    """Batch shape of the multi-hot configuration (32768 x 26 bags of 1-20 ids, dim 64) with the
+    vocabulary cut to 4e6 rows so that the oracle's table stays small; the cache holds the whole
+    table, as in that configuration (compulsory misses only)."""
+    w = si.WORKLOADS["c3"]
+    V = 4_000_000
+    t0 = time.time()
+    p = Pair(V, w.dim, V, w.max_ids, max_bags=w.n_bags, seed=w.seed)
+    for t in range(2):
+        off = si.bag_offsets(w.n_bags, w.bag_lo, w.bag_hi, w.seed, t).numpy()
+        ids = si.zipf_ids(int(off[-1]), w.zipf_s, V, w.seed, t).numpy()
+        pr = p.step(ids, w.batch_grads(t).numpy(), offsets=off, check_state=False)
+        _say("multi-hot step %d: N=%d U=%d, %.0fs" % (t, ids.size, pr.stats["n_unique"], time.time() - t0))
+        assert pr.stats["n_evict"] == 0 and pr.stats["n_bypass"] == 0
+    p.finish()
+    p.close()
+
+
+def test_low_locality_configuration_shape():
+    """Batch shape of the low-locality stress configuration (131072 x 39 uniform ids, dim 16):
+    nearly every position is its own virtual id and nearly every id misses; vocabulary and cache
+    cut 25x (4e7 rows, 8e5 slots) at the same cache/vocabulary ratio."""
+    w = si.WORKLOADS["c4"]
+    V, C = 40_000_000, 800_000
+    t0 = time.time()
+    p = Pair(V, w.dim, C, w.max_ids, seed=w.seed)
+    for t in range(3):
+        ids = si.uniform_ids(w.max_ids, V, w.seed, t).numpy()
+        pr = p.step(ids, w.batch_grads(t).numpy(), check_state=(t == 2), check_rows=False)
+        _say("low-locality step %d: U=%d miss=%d evict=%d bypass=%d, %.0fs" % (
+            t, pr.stats["n_unique"], pr.stats["n_miss"], pr.stats["n_evict"], pr.stats["n_bypass"],
+            time.time() - t0))
+    assert pr.stats["n_bypass"] > 0          # 5e6 new ids per step against 8e5 slots
+    p.finish()
+    p.close()
