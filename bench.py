@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
+    ap.add_argument("--lookahead", type=int, default=1, choices=[0, 1],
+                    help="1: prepare/fetch of step t+1 overlap lookup/update of step t (default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -73,44 +75,65 @@ def main():
     table.acc_t.fill_(w.init_acc)
     log("host table [%d, %d] x2 pinned and filled in %.1fs" % (V, D, time.time() - t0))
 
-    cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lr=w.lr, eps=w.eps, device="cuda:0")
+    cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lr=w.lr, eps=w.eps, lookahead=args.lookahead,
+                      device="cuda:0")
     out = torch.empty(w.n_bags, D, dtype=torch.float32, device=dev)
     grads = [w.batch_grads(i, dev) for i in range(4)]
+    step_no = [0]          # next batch of the seeded sequence
 
-    def run_step(ids, off, g):
-        cache.prepare(ids, off)
+    def next_batch():
+        b = w.batch_ids(step_no[0], dev)
+        step_no[0] += 1
+        return b
+
+    # One step = prepare + fetch_misses + lookup + backward_update.  With lookahead 1 the prepare
+    # and fetch issued in an iteration belong to the next step and overlap this step's lookup and
+    # update; every iteration still issues exactly one of each call.
+    if args.lookahead:
+        b0 = next_batch()
+        cache.prepare(b0[0], b0[1])
         cache.fetch_misses()
-        cache.lookup(out)
-        cache.backward_update(g)
+
+    def run_steps(batches, k0=0):
+        for i, b in enumerate(batches):
+            g = grads[(k0 + i) % 4]
+            if args.lookahead:
+                cache.lookup(out)
+                cache.prepare(b[0], b[1])
+                cache.fetch_misses()
+                cache.backward_update(g)
+            else:
+                cache.prepare(b[0], b[1])
+                cache.fetch_misses()
+                cache.lookup(out)
+                cache.backward_update(g)
 
     # warm-up: fills the cache and reaches the steady-state hit rate
     t0 = time.time()
     for t in range(W):
-        ids, off = w.batch_ids(t, dev)
-        run_step(ids, off, grads[t % 4])
+        run_steps([next_batch()], t)
     torch.cuda.synchronize()
     log("warm-up %d steps in %.1fs" % (W, time.time() - t0))
 
-    batches = [w.batch_ids(W + t, dev) for t in range(K)]
+    batches = [next_batch() for _ in range(K)]
     n_ids_total = sum(b[0].numel() for b in batches)
     torch.cuda.synchronize()
 
     # pass 1: whole-job throughput, no instrumentation inside the timed region
     t_start = time.perf_counter()
-    for t in range(K):
-        run_step(batches[t][0], batches[t][1], grads[t % 4])
+    run_steps(batches)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
 
     # pass 2: K more steps with hipEvents around every step call (the next batches of the same
     # sequence, so the cache keeps evolving as in training); device counters sampled on the way
-    batches2 = [w.batch_ids(W + K + t, dev) for t in range(K)]
+    batches2 = [next_batch() for _ in range(K)]
     torch.cuda.synchronize()
     sfc.sfc_profile_enable(cache.h, 1)
     agg = dict(n_unique=0, n_hit=0, n_miss=0, n_evict=0, n_bypass=0, h2d_bytes=0, d2h_bytes=0)
     ns = 0
     for t in range(K):
-        run_step(batches2[t][0], batches2[t][1], grads[t % 4])
+        run_steps([batches2[t]], t)
         if t % max(1, K // 10) == 0:          # sample the device counters (each read synchronises)
             st = cache.stats()
             for k in agg:
@@ -118,11 +141,10 @@ def main():
             ns += 1
     prof = sfc.sfc_profile_read(cache.h)
     # pass 3: K more steps with events around the kernels inside backward_update as well
-    batches3 = [w.batch_ids(W + 2 * K + t, dev) for t in range(K)]
+    batches3 = [next_batch() for _ in range(K)]
     torch.cuda.synchronize()
     sfc.sfc_profile_enable(cache.h, 2)
-    for t in range(K):
-        run_step(batches3[t][0], batches3[t][1], grads[t % 4])
+    run_steps(batches3)
     prof3 = sfc.sfc_profile_read(cache.h)
     for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows"):
         prof[k] = prof3[k]
@@ -165,7 +187,7 @@ def main():
             "ids_per_step": N, "unique_per_step": U,
             "hit_rate": avg["n_hit"] / max(1.0, avg["n_hit"] + avg["n_miss"]),
             "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
-            "bypass_per_step": avg["n_bypass"],
+            "bypass_per_step": avg["n_bypass"], "lookahead": args.lookahead,
         },
         "roofline": {
             "bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -189,6 +211,9 @@ def main():
         # seeded batch sequence from a cold oracle cache, run in place on the host table after
         # the GPU run has been flushed into it (values differ from step 0, the work does not).
         from oracle import Oracle
+        if args.lookahead:                    # retire the step that is still in flight
+            cache.lookup(out)
+            cache.backward_update(grads[0])
         cache.flush()
         orc = Oracle(C, D, table.w, table.acc, lr=w.lr, eps=w.eps)
         done_ids, steps_done, cpu_t = 0, 0, 0.0

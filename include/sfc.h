@@ -3,7 +3,9 @@
  * (Virtual Sparse Id + MixCache + gather + gradient segment-sum + sparse
  * Adagrad), implemented with HIP kernels for gfx950 (MI355X).
  *
- * One training step is four calls, in this order (Algorithm 1, lines 3-14,
+ * One training step is four calls, in this order (with lookahead = 1 the first two of step t+1 may
+ * precede the last of step t; sfc_lookup, sfc_segment_sum and sfc_backward_update always act on
+ * the oldest step that has been fetched and not yet updated) (Algorithm 1, lines 3-14,
  * with the multi-GPU lines 7, 10 and 13 and the dense model of line 12 left to
  * the caller):
  *
@@ -62,8 +64,14 @@ typedef struct {
                                  host link moves fastest. */
   float lr;                   /* Adagrad learning rate */
   float eps;                  /* Adagrad epsilon, added outside the square root */
-  int32_t lookahead;          /* 0: rows of the batch being prepared are protected from eviction.
-                                 1: rows of the previous batch are protected as well. */
+  int32_t lookahead;          /* 0: rows of the batch being prepared are protected from eviction;
+                                 calls of a step go prepare, fetch_misses, lookup, backward_update.
+                                 1: rows of the previous batch are protected as well, and
+                                 sfc_prepare / sfc_fetch_misses of step t+1 may be called before
+                                 sfc_backward_update of step t: they run on side_stream while the
+                                 main stream works on step t (the paper's pipeline of Host-Manager
+                                 and GPU-Worker).  The caller then alternates two sets of prepare
+                                 buffers. */
   int32_t max_steps;          /* steps this cache may run (sizes the recency histogram); 0 = 1<<20 */
   void* stream;               /* hipStream_t for prepare / lookup / backward_update */
   void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */

@@ -237,8 +237,26 @@ class HostTable:
             pass
 
 
+class StepBuffers:
+    """Device buffers of one prepared step (the d_* outputs of sfc_prepare) and its sizes."""
+
+    def __init__(self, n, device):
+        self.unique_ids = torch.empty(n, dtype=torch.int64, device=device)
+        self.inverse = torch.empty(n, dtype=torch.int32, device=device)
+        self.slot = torch.empty(n, dtype=torch.int32, device=device)
+        self.miss_vids = torch.empty(n, dtype=torch.int32, device=device)
+        self.n_ids = self.n_bags = 0
+        self.keep = None          # the caller's ids / offsets stay alive as long as the step does
+
+
 class Cache:
-    """One sfc_cache with its output buffers; methods mirror the C calls of a step."""
+    """One sfc_cache with its output buffers; methods mirror the C calls of a step.
+
+    lookahead = 0: prepare, fetch_misses, lookup, backward_update in that order.
+    lookahead = 1: prepare / fetch_misses of step t+1 may be issued before backward_update of
+    step t (they run on the side stream meanwhile); lookup and backward_update always act on the
+    oldest step that has not been updated.  Two sets of output buffers alternate.
+    """
 
     def __init__(self, table: HostTable, capacity_rows: int, max_ids: int, max_bags: Optional[int] = None,
                  lr=0.01, eps=1e-8, lookahead=0, max_steps=0, device="cuda:0", side_stream=True):
@@ -246,21 +264,18 @@ class Cache:
         self.device = torch.device(device)
         self.max_ids = int(max_ids)
         self.max_bags = int(max_bags if max_bags is not None else max_ids)
+        self.lookahead = int(lookahead)
         with torch.cuda.device(self.device):
             self.stream = torch.cuda.current_stream()
-            self.side = torch.cuda.Stream() if side_stream else self.stream
+            self.side = torch.cuda.Stream() if (side_stream or lookahead) else self.stream
             cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH, self.max_ids, self.max_bags,
                              table.rows, table._pw, table._pa, table.stride, lr, eps, lookahead,
-                             max_steps,
-                             self.stream.cuda_stream, self.side.cuda_stream)
+                             max_steps, self.stream.cuda_stream, self.side.cuda_stream)
             self.h = sfc_cache_create(cfg)
-            n = max(self.max_ids, 1)
-            self.unique_ids = torch.empty(n, dtype=torch.int64, device=self.device)
-            self.inverse = torch.empty(n, dtype=torch.int32, device=self.device)
-            self.slot = torch.empty(n, dtype=torch.int32, device=self.device)
-            self.miss_vids = torch.empty(n, dtype=torch.int32, device=self.device)
-        self.n_ids = self.n_bags = 0
-        self._keep = None
+            self.bufs = [StepBuffers(max(self.max_ids, 1), self.device) for _ in range(self.lookahead + 1)]
+        self._next = 0
+        self.last = self.bufs[0]        # most recently prepared step
+        self.inflight = []              # prepared and not yet updated, oldest first
 
     def close(self):
         if getattr(self, "h", None):
@@ -273,30 +288,51 @@ class Cache:
         except Exception:
             pass
 
-    def prepare(self, ids: torch.Tensor, offsets: Optional[torch.Tensor] = None):
-        self.n_ids = ids.numel()
-        self.n_bags = self.n_ids if offsets is None else offsets.numel() - 1
-        self._keep = (ids, offsets)
-        sfc_prepare(self.h, ids, self.n_ids, offsets, self.n_bags, self.unique_ids, self.inverse,
-                    self.slot, self.miss_vids)
+    # outputs of the most recent prepare
+    unique_ids = property(lambda self: self.last.unique_ids)
+    inverse = property(lambda self: self.last.inverse)
+    slot = property(lambda self: self.last.slot)
+    miss_vids = property(lambda self: self.last.miss_vids)
+    n_ids = property(lambda self: self.last.n_ids)
+    n_bags = property(lambda self: self.last.n_bags)
+
+    def prepare(self, ids: torch.Tensor, offsets: Optional[torch.Tensor] = None) -> StepBuffers:
+        b = self.bufs[self._next]
+        n_ids = ids.numel()
+        n_bags = n_ids if offsets is None else offsets.numel() - 1
+        sfc_prepare(self.h, ids, n_ids, offsets, n_bags, b.unique_ids, b.inverse, b.slot, b.miss_vids)
+        b.n_ids, b.n_bags, b.keep = n_ids, n_bags, (ids, offsets)
+        if b in self.inflight:            # a step that was only read is dropped by the library
+            self.inflight.remove(b)
+        self.inflight.append(b)
+        self.last = b
+        self._next = (self._next + 1) % len(self.bufs)
+        return b
 
     def fetch_misses(self):
         sfc_fetch_misses(self.h)
 
+    def _current(self) -> StepBuffers:
+        return self.inflight[0] if self.inflight else self.last
+
     def lookup(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        b = self._current()
         if out is None:
-            out = torch.empty(self.n_bags, self.D, dtype=torch.float32, device=self.device)
+            out = torch.empty(b.n_bags, self.D, dtype=torch.float32, device=self.device)
         sfc_lookup(self.h, out)
         return out
 
     def segment_sum(self, grad: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        b = self._current()
         if out is None:
-            out = torch.empty(max(self.n_ids, 1), self.D, dtype=torch.float32, device=self.device)
+            out = torch.empty(max(b.n_ids, 1), self.D, dtype=torch.float32, device=self.device)
         sfc_segment_sum(self.h, grad, out)
         return out
 
     def backward_update(self, grad: torch.Tensor):
         sfc_backward_update(self.h, grad)
+        if self.inflight:
+            self.inflight.pop(0)
 
     def flush(self):
         sfc_flush(self.h)

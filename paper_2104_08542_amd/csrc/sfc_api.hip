@@ -2,6 +2,12 @@
 // enqueues the kernels of each step call on the caller's streams.  No call after
 // sfc_cache_create allocates device memory or waits for the device, except the ones the header
 // documents as synchronising.
+//
+// A step in flight is a StepCtx: the caller's buffers, the step's device counters, its grouping
+// of positions, its victim list and its bypass region.  lookahead = 0 has one context and runs the
+// prepare on the main stream; lookahead = 1 has two, runs prepare and fetch of step t+1 on the side
+// stream while lookup / backward_update of step t run on the main stream (the paper's pipeline of
+// Host-Manager and GPU-Worker stages).
 #include "../../include/sfc.h"
 
 #include <hip/hip_runtime.h>
@@ -36,22 +42,46 @@ int fail(int code, const char* what, hipError_t e = hipSuccess) {
     if (e_ != hipSuccess) return fail(SFC_EHIP, #call, e_);     \
   } while (0)
 
-enum State { IDLE = 0, PREPARED = 1, FETCHED = 2 };
+// life of a step context
+enum State { FREE = 0, PREPARED = 1, FETCH_DEFERRED = 2, FETCHED = 3 };
 enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEG_STREAM = 4, P_SEG_FINISH = 5,
        P_ADAGRAD = 6, P_N = 7 };
 
 struct EventPair { hipEvent_t a, b; };
+
+struct StepCtx {
+  int state = FREE;
+  int t = 0;                          // step number
+  int64_t n_ids = 0, n_bags = 0;
+  const int64_t* d_offsets = nullptr; // caller's buffers of this step
+  int64_t* d_unique = nullptr;
+  int32_t *d_inverse = nullptr, *d_slot = nullptr, *d_miss = nullptr;
+  Ctr* ctr = nullptr;                 // device counters of this step
+  int64_t* perm64 = nullptr;          // [max_ids] positions grouped by virtual id
+  int* pos_slot = nullptr;            // [max_ids] cache row of each position
+  int* victim_slot = nullptr;         // [max_ids]
+  int64_t* victim_id = nullptr;       // [max_ids]
+  int boff = 0;                       // bypass slot C + j lives at row C + boff + j
+  volatile int* h_nbypass = nullptr;  // pinned Host word written by the plan kernel (-1 = not yet)
+  int* d_nbypass = nullptr;           // its device address
+  hipEvent_t ev_prepared = nullptr;   // the step's prepare kernels have run
+  hipEvent_t ev_fetched = nullptr;    // the step's rows are in place
+  bool fetched_on_main = false;
+  bool updated = false;               // backward_update has been enqueued for this step
+};
+
+constexpr int kMaxCtx = 2;
 
 }  // namespace
 
 struct sfc_cache {
   sfc_config cfg{};
   int64_t C = 0, V = 0, max_ids = 0, max_bags = 0;
-  int D = 0, d4 = 0;
+  int D = 0, d4 = 0, nctx = 1;
   hipStream_t st = nullptr, side = nullptr;
-  hipEvent_t ev_prepared = nullptr, ev_fetched = nullptr;
+  hipEvent_t ev_tmp = nullptr;                  // cross-stream ordering inside one call
   // device memory
-  float *cw = nullptr, *ca = nullptr;           // [(C + max_ids), D]
+  float *cw = nullptr, *ca = nullptr;           // [(C + nctx * max_ids), D]
   int64_t* slot_id = nullptr;                   // [C]
   int* stamp = nullptr;                         // [C]
   IdxEntry* index = nullptr; uint32_t hi = 0;   // cache index
@@ -62,25 +92,19 @@ struct sfc_cache {
   int* blk_cnt = nullptr;                       // [max_ids / kPosChunk + 1]
   int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
   int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
-  int* victim_slot = nullptr; int64_t* victim_id = nullptr;  // [max_ids]
   int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
-  int64_t* perm64 = nullptr;                    // [max_ids] positions grouped by virtual id
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
-  int* pos_slot = nullptr;                      // [max_ids] cache slot of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
   int* age_mat = nullptr;                       // [kResolveGrid, kAgeBins] hits by age per block
-  double* bp = nullptr; int* bp_vid = nullptr;  // [2 * wavefronts, D] edge partial sums of k_seg_stream
+  double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
-  Ctr* ctr = nullptr;
   HostRows host{};                              // device view of the Host table
+  int* h_words = nullptr;                       // pinned Host words (bypass counts)
   std::vector<void*> allocs;
-  // step state
-  int state = IDLE;
-  int t = 0;
-  int64_t n_ids = 0, n_bags = 0;
-  const int64_t* d_offsets = nullptr;
-  int64_t* d_unique = nullptr; int32_t* d_inverse = nullptr; int32_t* d_slot = nullptr;
-  int32_t* d_miss = nullptr;
+  // steps
+  StepCtx ctx[kMaxCtx];
+  int t = 0;                                    // steps prepared so far
+  int last_prepared = -1;                       // context of the most recent sfc_prepare
   // profiling
   int prof = 0;                                 // 0 off, 1 step calls, 2 also the kernels inside them
   std::vector<EventPair> pending[P_N], spare;
@@ -146,11 +170,50 @@ int prof_collect(sfc_cache* c) {
   return SFC_OK;
 }
 
-// Segment-sum over perm64, then either the Adagrad update (EMIT = false) or the common-gradient
-// matrix (EMIT = true).  Two kernels: per-block runs, then the block-edge partials.
-// common[v] = segment sum of d_grad over perm64: the stream, then the block-edge partials.
-int seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
-  const int n = (int)c->n_ids;
+constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
+
+// The step that lookup / segment_sum / backward_update act on: the oldest one whose rows are (or
+// are about to be) in place and that has not been updated yet.
+StepCtx* training_ctx(sfc_cache* c) {
+  StepCtx* best = nullptr;
+  for (int k = 0; k < c->nctx; ++k) {
+    StepCtx* x = &c->ctx[k];
+    if ((x->state == FETCHED || x->state == FETCH_DEFERRED) && !x->updated && (!best || x->t < best->t))
+      best = x;
+  }
+  return best;
+}
+
+// Host<->cache copies of one step, on stream s.
+int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s) {
+  EventPair ep{};
+  int rc;
+  // the copies read the step's counters, miss list and victim list: its prepare comes first
+  // (on the same stream that is automatic; a fetch deferred to the main stream must wait)
+  HIPCHK(hipStreamWaitEvent(s, x->ev_prepared, 0));
+  if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
+  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, 1024)), dim3(256), 0, s,
+                     x->d_miss, x->d_unique, x->d_slot, x->victim_id, (float4*)c->cw,
+                     (float4*)c->ca, c->host, c->d4, (int)c->C, x->boff, x->ctr);
+  HIPCHK(hipGetLastError());
+  if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
+  HIPCHK(hipEventRecord(x->ev_fetched, s));
+  x->fetched_on_main = s == c->st;
+  x->state = FETCHED;
+  return SFC_OK;
+}
+
+// Before main-stream work that reads the step's rows: run a deferred fetch, or wait for the side
+// stream's one.
+int rows_ready(sfc_cache* c, StepCtx* x) {
+  if (x->state == FETCH_DEFERRED) return launch_swap(c, x, c->st);
+  if (!x->fetched_on_main) HIPCHK(hipStreamWaitEvent(c->st, x->ev_fetched, 0));
+  return SFC_OK;
+}
+
+// common[v] = segment sum of d_grad over the step's grouping: the stream, then the block-edge partials.
+int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common) {
+  const int n = (int)x->n_ids;
   if (n <= 0) return SFC_OK;
   const SegGeom g = seg_geom(c->D, n);
   const int nblk = (g.waves + 3) / 4;
@@ -158,7 +221,7 @@ int seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
   int rc;
   if ((rc = prof_begin(c, P_SEG_STREAM, c->st, &e1))) return rc;
   hipLaunchKernelGGL(k_seg_stream, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
-                     c->perm64, n, c->d4, g.G, g.L, (float4*)d_common, c->bp, c->bp_vid);
+                     x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, c->bp, c->bp_vid);
   if ((rc = prof_end(c, P_SEG_STREAM, c->st, &e1))) return rc;
   if ((rc = prof_begin(c, P_SEG_FINISH, c->st, &e2))) return rc;
   hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, c->bp,
@@ -166,7 +229,11 @@ int seg_launch(sfc_cache* c, const float* d_grad, float* d_common) {
   return prof_end(c, P_SEG_FINISH, c->st, &e2);
 }
 
-constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
+int sync_all(sfc_cache* c) {
+  HIPCHK(hipStreamSynchronize(c->st));
+  if (c->side != c->st) HIPCHK(hipStreamSynchronize(c->side));
+  return SFC_OK;
+}
 
 }  // namespace
 
@@ -203,8 +270,12 @@ void sfc_cache_destroy(sfc_cache* c) {
   for (int w = 0; w < P_N; ++w)
     for (EventPair& ep : c->pending[w]) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
   for (EventPair& ep : c->spare) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
-  if (c->ev_prepared) (void)hipEventDestroy(c->ev_prepared);
-  if (c->ev_fetched) (void)hipEventDestroy(c->ev_fetched);
+  if (c->ev_tmp) (void)hipEventDestroy(c->ev_tmp);
+  for (int k = 0; k < kMaxCtx; ++k) {
+    if (c->ctx[k].ev_prepared) (void)hipEventDestroy(c->ctx[k].ev_prepared);
+    if (c->ctx[k].ev_fetched) (void)hipEventDestroy(c->ctx[k].ev_fetched);
+  }
+  if (c->h_words) (void)hipHostFree(c->h_words);
   for (void* p : c->allocs) (void)hipFree(p);
   delete c;
 }
@@ -217,16 +288,16 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if (cfg->policy != SFC_POLICY_LRU_BATCH) return fail(SFC_EINVAL, "unknown policy");
   if (cfg->max_ids_per_batch < 1 || cfg->max_bags_per_batch < 1 || cfg->host_rows < 1)
     return fail(SFC_EINVAL, "max_ids_per_batch, max_bags_per_batch and host_rows must be >= 1");
-  if (cfg->capacity_rows + cfg->max_ids_per_batch >= (int64_t)1 << 31 ||
-      2 * (cfg->capacity_rows + cfg->max_ids_per_batch) >= (int64_t)1 << 32 ||
-      cfg->max_bags_per_batch >= (int64_t)1 << 31)
-    return fail(SFC_EINVAL, "capacity_rows + max_ids_per_batch must stay below 2^31");
+  if (cfg->lookahead < 0 || cfg->lookahead > 1) return fail(SFC_EINVAL, "lookahead must be 0 or 1");
+  const int64_t nctx = cfg->lookahead + 1;
+  if (cfg->capacity_rows + nctx * cfg->max_ids_per_batch >= (int64_t)1 << 31 ||
+      cfg->max_ids_per_batch >= (int64_t)1 << 30 || cfg->max_bags_per_batch >= (int64_t)1 << 31)
+    return fail(SFC_EINVAL, "capacity_rows + (lookahead + 1) * max_ids_per_batch must stay below 2^31");
   if (!cfg->h_weights || !cfg->h_acc) return fail(SFC_EINVAL, "null host table");
   if (((uintptr_t)cfg->h_weights | (uintptr_t)cfg->h_acc) & 15)
     return fail(SFC_EINVAL, "host table must be 16-byte aligned");
   if (cfg->host_row_stride && (cfg->host_row_stride < cfg->dim || cfg->host_row_stride % 4))
     return fail(SFC_EINVAL, "host_row_stride must be 0 or a multiple of 4 that is >= dim");
-  if (cfg->lookahead < 0 || cfg->lookahead > 1) return fail(SFC_EINVAL, "lookahead must be 0 or 1");
   if (cfg->max_steps < 0) return fail(SFC_EINVAL, "max_steps must be >= 0");
 
   sfc_cache* c = new (std::nothrow) sfc_cache;
@@ -234,6 +305,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   c->cfg = *cfg;
   c->C = cfg->capacity_rows; c->V = cfg->host_rows; c->D = cfg->dim; c->d4 = cfg->dim / 4;
   c->max_ids = cfg->max_ids_per_batch; c->max_bags = cfg->max_bags_per_batch;
+  c->nctx = (int)nctx;
   c->st = (hipStream_t)cfg->stream;
   c->side = cfg->side_stream ? (hipStream_t)cfg->side_stream : c->st;
   c->hist_len = (cfg->max_steps ? cfg->max_steps : (1 << 20)) + 2;
@@ -252,9 +324,13 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   }
   c->host.a = (float4*)dp;
   c->host.hs4 = (cfg->host_row_stride ? cfg->host_row_stride : cfg->dim) / 4;
+  if ((e = hipHostMalloc((void**)&c->h_words, 64 * sizeof(int), hipHostMallocMapped)) != hipSuccess) {
+    c->h_words = nullptr;
+    rc = fail(SFC_ENOMEM, "hipHostMalloc", e); goto bad;
+  }
 
   {
-    const int64_t rows = c->C + c->max_ids;
+    const int64_t rows = c->C + nctx * c->max_ids;
     const int64_t hu = 2 * c->max_ids;
     if ((rc = dalloc(c, &c->cw, rows * c->D))) goto bad;
     if ((rc = dalloc(c, &c->ca, rows * c->D))) goto bad;
@@ -270,23 +346,38 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->tile_miss, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_lt, c->C / kPosChunk + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_eq, c->C / kPosChunk + 2))) goto bad;
-    if ((rc = dalloc(c, &c->victim_slot, c->max_ids))) goto bad;
-    if ((rc = dalloc(c, &c->victim_id, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->cnt, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
-    if ((rc = dalloc(c, &c->perm64, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
-    if ((rc = dalloc(c, &c->pos_slot, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->age_mat, (int64_t)kResolveGrid * kAgeBins))) goto bad;
     {
-      const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;   // the wave count never exceeds that of max_ids
-      const int64_t nwmax = nw > 4104 ? nw : 4104;
+      const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;
+      const int64_t nwmax = nw > 4104 ? nw : 4104;     // the stream never has more wavefronts
       if ((rc = dalloc(c, &c->bp, 2 * nwmax * c->D))) goto bad;
       if ((rc = dalloc(c, &c->bp_vid, 2 * nwmax))) goto bad;
     }
-    if ((rc = dalloc(c, &c->ctr, 1))) goto bad;
     if ((rc = dalloc(c, &c->gsum, c->max_ids * c->D))) goto bad;
+    void* dwords = nullptr;
+    if ((e = hipHostGetDevicePointer(&dwords, c->h_words, 0)) != hipSuccess) {
+      rc = fail(SFC_EHIP, "hipHostGetDevicePointer", e); goto bad;
+    }
+    for (int k = 0; k < c->nctx; ++k) {
+      StepCtx* x = &c->ctx[k];
+      if ((rc = dalloc(c, &x->ctr, 1))) goto bad;
+      if ((rc = dalloc(c, &x->perm64, c->max_ids))) goto bad;
+      if ((rc = dalloc(c, &x->pos_slot, c->max_ids))) goto bad;
+      if ((rc = dalloc(c, &x->victim_slot, c->max_ids))) goto bad;
+      if ((rc = dalloc(c, &x->victim_id, c->max_ids))) goto bad;
+      x->boff = (int)(k * c->max_ids);
+      x->h_nbypass = c->h_words + 16 * k;
+      x->d_nbypass = (int*)dwords + 16 * k;
+      *x->h_nbypass = 0;
+      if ((e = hipEventCreateWithFlags(&x->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
+          (e = hipEventCreateWithFlags(&x->ev_fetched, hipEventDisableTiming)) != hipSuccess) {
+        rc = fail(SFC_EHIP, "hipEventCreate", e); goto bad;
+      }
+    }
 
     hipStream_t s = c->st;
     fill<int64_t>(s, c->slot_id, c->C, (int64_t)-1);
@@ -297,9 +388,11 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
     Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
-    if ((e = hipMemcpyAsync(c->ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess ||
-        (e = hipEventCreateWithFlags(&c->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
-        (e = hipEventCreateWithFlags(&c->ev_fetched, hipEventDisableTiming)) != hipSuccess ||
+    for (int k = 0; k < c->nctx; ++k)
+      if ((e = hipMemcpyAsync(c->ctx[k].ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess) {
+        rc = fail(SFC_EHIP, "cache initialisation", e); goto bad;
+      }
+    if ((e = hipEventCreateWithFlags(&c->ev_tmp, hipEventDisableTiming)) != hipSuccess ||
         (e = hipStreamSynchronize(s)) != hipSuccess || (e = hipGetLastError()) != hipSuccess) {
       rc = fail(SFC_EHIP, "cache initialisation", e); goto bad;
     }
@@ -320,34 +413,55 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   if (!d_offsets && n_bags != n_ids) return fail(SFC_EINVAL, "one-hot input needs n_bags == n_ids");
   if ((n_ids > 0 && !d_ids) || !d_unique_ids || !d_inverse || !d_slot || !d_miss_vids)
     return fail(SFC_EINVAL, "null buffer");
-  if (c->state == PREPARED)
+  if (c->last_prepared >= 0 && c->ctx[c->last_prepared].state == PREPARED)
     return fail(SFC_ESTATE, "sfc_prepare twice without sfc_fetch_misses: missed rows would never arrive");
   if (c->t + 1 >= c->hist_len - 1) return fail(SFC_ELIMIT, "max_steps reached");
+
+  // a free context; with every context busy, the oldest step whose rows were only read is dropped
+  StepCtx* x = nullptr;
+  for (int k = 0; k < c->nctx; ++k)
+    if (c->ctx[k].state == FREE) { x = &c->ctx[k]; break; }
+  if (!x) {
+    StepCtx* old = training_ctx(c);
+    if (!old) return fail(SFC_ESTATE, "no step context free");
+    if (old->state == FETCH_DEFERRED)
+      return fail(SFC_ESTATE, "the step in flight has not been looked up or updated yet");
+    x = old;
+  }
+  StepCtx* prev = c->last_prepared >= 0 ? &c->ctx[c->last_prepared] : x;
+  const bool pipelined = c->nctx > 1;
+  hipStream_t s = pipelined ? c->side : c->st;
+  if (pipelined) {
+    // the side stream must not overtake what the main stream has been given so far: the producer
+    // of d_ids, the last update that read this context's buffers, a fetch deferred to that stream
+    HIPCHK(hipEventRecord(c->ev_tmp, c->st));
+    HIPCHK(hipStreamWaitEvent(s, c->ev_tmp, 0));
+  }
   c->t += 1;
-  c->n_ids = n_ids; c->n_bags = n_bags; c->d_offsets = d_offsets;
-  c->d_unique = d_unique_ids; c->d_inverse = d_inverse; c->d_slot = d_slot; c->d_miss = d_miss_vids;
-  hipStream_t s = c->st;
+  x->t = c->t; x->state = PREPARED; x->updated = false; x->fetched_on_main = false;
+  x->n_ids = n_ids; x->n_bags = n_bags; x->d_offsets = d_offsets;
+  x->d_unique = d_unique_ids; x->d_inverse = d_inverse; x->d_slot = d_slot; x->d_miss = d_miss_vids;
+  *x->h_nbypass = -1;
+  c->last_prepared = (int)(x - c->ctx);
+
   EventPair ep{};
   int rc;
   if ((rc = prof_begin(c, P_PREPARE, s, &ep))) return rc;
-
   const int n = (int)n_ids;
   uint32_t hu = (uint32_t)(2 * n_ids);
   if (hu < 64) hu = 64;                       // the batch table is empty between steps: any size works
-  if (hu > 2 * c->max_ids) hu = (uint32_t)(2 * c->max_ids);
   const int nchunk = (n + kPosChunk - 1) / kPosChunk;
-  // per-step counters that the kernels accumulate into
-  hipLaunchKernelGGL(k_fill<int>, dim3(1), dim3(64), 0, s, &c->ctr->n_hit, (int64_t)2, 0);  // n_hit, n_invalid
+  hipLaunchKernelGGL(k_step_begin, dim3(1), dim3(64), 0, s, x->ctr, prev->ctr);
   if (n > 0) {
     hipLaunchKernelGGL(k_uniq_insert, dim3((n + kUniqChunk - 1) / kUniqChunk), dim3(256), 0, s,
-                       d_ids, n, c->V, c->utab, hu, c->hslot, c->ctr);
+                       d_ids, n, c->V, c->utab, hu, c->hslot, x->ctr);
     hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
                        c->blk_cnt);
   }
-  hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->ctr);
+  hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, x->ctr);
   hipLaunchKernelGGL(k_index_reinsert, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi,
-                     c->slot_id, c->ctr);
-  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, c->ctr);
+                     c->slot_id, x->ctr);
+  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, x->ctr);
   if (n > 0) {
     hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
                        c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt);
@@ -357,73 +471,77 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
       hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
                          d_offsets, (int)n_bags, n, c->pos2bag);
   }
-  const int gr = grid_for(n, kVidTile, kResolveGrid);
+  const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
-                     c->index, c->hi, c->stamp, c->hist, c->t, d_slot, c->tile_miss,
-                     c->cnt, c->tile_cnt, c->age_mat, c->ctr);
+                     c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt,
+                     c->tile_cnt, c->age_mat, x->ctr);
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_mat, gr,
-                     c->hist, c->t, c->cfg.lookahead, (int)c->C, c->hi, c->ctr);
+                     c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->d_nbypass, x->ctr);
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
-                     c->ctr);
-  hipLaunchKernelGGL(k_victim_scan, dim3(1), dim3(1024), 0, s, c->tile_lt, c->tile_eq, c->ctr);
+                     x->ctr);
+  hipLaunchKernelGGL(k_victim_scan, dim3(1), dim3(1024), 0, s, c->tile_lt, c->tile_eq, x->ctr);
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
-                     c->tile_eq, c->index, c->hi, c->victim_slot, c->victim_id, c->ctr);
+                     c->tile_eq, c->index, c->hi, x->victim_slot, x->victim_id, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->tile_cnt,
-                     c->cursor, c->tile_miss, c->victim_slot, d_slot, d_miss_vids, c->slot_id,
-                     c->stamp, c->index, c->hi, c->t, (int)c->C, c->ctr);
+                     c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, c->slot_id,
+                     c->stamp, c->index, c->hi, x->t, (int)c->C, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3(nchunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor,
-                       c->perm64, d_slot, c->pos_slot);
+                       x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
-  HIPCHK(hipEventRecord(c->ev_prepared, s));
-  c->state = PREPARED;
+  HIPCHK(hipEventRecord(x->ev_prepared, s));
   return SFC_OK;
 }
 
 int sfc_fetch_misses(sfc_cache* c) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  if (c->state != PREPARED) return fail(SFC_ESTATE, "sfc_fetch_misses needs a preceding sfc_prepare");
-  hipStream_t s = c->side;
-  if (s != c->st) HIPCHK(hipStreamWaitEvent(s, c->ev_prepared, 0));
-  EventPair ep{};
-  int rc;
-  if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
-  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(c->n_ids * 2 * c->d4, 256, 1024)), dim3(256), 0, s,
-                     c->d_miss, c->d_unique, c->d_slot, c->victim_id, (float4*)c->cw,
-                     (float4*)c->ca, c->host, c->d4, c->ctr);
-  HIPCHK(hipGetLastError());
-  if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
-  if (s != c->st) {
-    HIPCHK(hipEventRecord(c->ev_fetched, s));
-    HIPCHK(hipStreamWaitEvent(c->st, c->ev_fetched, 0));
+  StepCtx* x = c->last_prepared >= 0 ? &c->ctx[c->last_prepared] : nullptr;
+  if (!x || x->state != PREPARED) return fail(SFC_ESTATE, "sfc_fetch_misses needs a preceding sfc_prepare");
+  if (c->nctx > 1) {
+    // A row that bypassed the cache in the step still in flight reaches the Host table only with
+    // that step's update.  If that step may have had bypass rows (its count is not yet known to
+    // the host, or is nonzero) and its update has not been enqueued, this step's copies are
+    // deferred to the main stream, behind that update; otherwise they go to the side stream now.
+    StepCtx* o = training_ctx(c);
+    if (o && o != x && *o->h_nbypass != 0) {
+      x->state = FETCH_DEFERRED;
+      return SFC_OK;
+    }
   }
-  c->state = FETCHED;
-  return SFC_OK;
+  if (c->side != c->st) {
+    // everything the main stream has been given so far comes first: this step's prepare
+    // (lookahead 0), or the last update and a fetch that was deferred to that stream
+    HIPCHK(hipEventRecord(c->ev_tmp, c->st));
+    HIPCHK(hipStreamWaitEvent(c->side, c->ev_tmp, 0));
+  }
+  return launch_swap(c, x, c->side);
 }
 
 int sfc_lookup(sfc_cache* c, float* d_out) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  if (c->state != FETCHED) return fail(SFC_ESTATE, "sfc_lookup needs sfc_prepare and sfc_fetch_misses first");
-  if (c->n_bags > 0 && !d_out) return fail(SFC_EINVAL, "null output");
+  StepCtx* x = training_ctx(c);
+  if (!x) return fail(SFC_ESTATE, "sfc_lookup needs sfc_prepare and sfc_fetch_misses first");
+  if (x->n_bags > 0 && !d_out) return fail(SFC_EINVAL, "null output");
   if ((uintptr_t)d_out & 15) return fail(SFC_EINVAL, "output must be 16-byte aligned");
+  int rc;
+  if ((rc = rows_ready(c, x))) return rc;
   hipStream_t s = c->st;
   EventPair ep{};
-  int rc;
   if ((rc = prof_begin(c, P_LOOKUP, s, &ep))) return rc;
-  const int64_t total = c->n_bags * c->d4;
+  const int64_t total = x->n_bags * c->d4;
   if (total > 0) {
-    if (!c->d_offsets) {
+    if (!x->d_offsets) {
       const int d4 = c->d4, sh = (d4 & (d4 - 1)) == 0 ? __builtin_ctz(d4) : -1;
-      hipLaunchKernelGGL(k_lookup_onehot, dim3((unsigned)((c->n_bags + kLookupBags - 1) / kLookupBags)),
-                         dim3(256), 0, s, c->pos_slot, (const float4*)c->cw, (float4*)d_out,
-                         (int)c->n_bags, d4, sh);
+      hipLaunchKernelGGL(k_lookup_onehot, dim3((unsigned)((x->n_bags + kLookupBags - 1) / kLookupBags)),
+                         dim3(256), 0, s, x->pos_slot, (const float4*)c->cw, (float4*)d_out,
+                         (int)x->n_bags, d4, sh);
     } else {
       hipLaunchKernelGGL(k_lookup_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                         c->d_offsets, c->pos_slot, (const float4*)c->cw, (float4*)d_out, total,
+                         x->d_offsets, x->pos_slot, (const float4*)c->cw, (float4*)d_out, total,
                          c->d4);
     }
   }
@@ -433,47 +551,56 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
 
 int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  if (c->state == IDLE) return fail(SFC_ESTATE, "sfc_segment_sum needs a preceding sfc_prepare");
-  if ((c->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
+  StepCtx* x = training_ctx(c);
+  if (!x) return fail(SFC_ESTATE, "sfc_segment_sum needs sfc_prepare and sfc_fetch_misses first");
+  if ((x->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
-  int rc = seg_launch(c, d_grad, d_common_grad);
-  if (rc) return rc;
+  int rc;
+  if ((rc = rows_ready(c, x))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad))) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
 
 int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  if (c->state != FETCHED) return fail(SFC_ESTATE, "sfc_backward_update needs sfc_prepare and sfc_fetch_misses first");
-  if (c->n_bags > 0 && !d_grad) return fail(SFC_EINVAL, "null gradient");
+  StepCtx* x = training_ctx(c);
+  if (!x) return fail(SFC_ESTATE, "sfc_backward_update needs sfc_prepare and sfc_fetch_misses first");
+  if (x->n_bags > 0 && !d_grad) return fail(SFC_EINVAL, "null gradient");
   if ((uintptr_t)d_grad & 15) return fail(SFC_EINVAL, "gradient must be 16-byte aligned");
+  int rc;
+  if ((rc = rows_ready(c, x))) return rc;
   hipStream_t s = c->st;
   EventPair ep{}, e1{};
-  int rc;
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
-  if ((rc = seg_launch(c, d_grad, c->gsum))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, c->gsum))) return rc;
   if ((rc = prof_begin(c, P_ADAGRAD, s, &e1))) return rc;
-  hipLaunchKernelGGL(k_adagrad_rows, dim3(grid_for(c->n_ids * c->d4, 1024, kGridCap)), dim3(256), 0,
-                     s, (const float4*)c->gsum, c->d_slot, c->d_unique, (float4*)c->cw,
-                     (float4*)c->ca, c->host, (int)c->C, c->cfg.lr, c->cfg.eps, c->d4, c->ctr);
+  hipLaunchKernelGGL(k_adagrad_rows, dim3(grid_for(x->n_ids * c->d4, 1024, kGridCap)), dim3(256), 0,
+                     s, (const float4*)c->gsum, x->d_slot, x->d_unique, (float4*)c->cw,
+                     (float4*)c->ca, c->host, (int)c->C, x->boff, c->cfg.lr, c->cfg.eps, c->d4,
+                     x->ctr);
   if ((rc = prof_end(c, P_ADAGRAD, s, &e1))) return rc;
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_BACKWARD, s, &ep))) return rc;
-  c->state = IDLE;
-  return SFC_OK;
-}
-
-static int sync_all(sfc_cache* c) {
-  HIPCHK(hipStreamSynchronize(c->st));
-  if (c->side != c->st) HIPCHK(hipStreamSynchronize(c->side));
+  x->updated = true;
+  x->state = FREE;
+  // a fetch of the next step that had to wait for this update runs now, behind it
+  for (int k = 0; k < c->nctx; ++k)
+    if (c->ctx[k].state == FETCH_DEFERRED && (rc = launch_swap(c, &c->ctx[k], s))) return rc;
   return SFC_OK;
 }
 
 int sfc_flush(sfc_cache* c) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  if (c->state == PREPARED) return fail(SFC_ESTATE, "sfc_flush between sfc_prepare and sfc_fetch_misses");
+  for (int k = 0; k < c->nctx; ++k)
+    if (c->ctx[k].state == PREPARED || c->ctx[k].state == FETCH_DEFERRED)
+      return fail(SFC_ESTATE, "sfc_flush while a prepared step still waits for its rows");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  if (c->last_prepared < 0) return SFC_OK;
   hipLaunchKernelGGL(k_flush, dim3(grid_for(c->C * 2 * c->d4, 256, kGridCap)), dim3(256), 0, c->st,
-                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, c->host, c->d4, c->ctr);
+                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, c->host, c->d4,
+                     c->ctx[c->last_prepared].ctr);
   HIPCHK(hipGetLastError());
   return sync_all(c);
 }
@@ -482,8 +609,10 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out) {
   if (!c || !h_out) return fail(SFC_EINVAL, "null argument");
   int rc = sync_all(c);
   if (rc) return rc;
+  memset(h_out, 0, sizeof *h_out);
+  if (c->last_prepared < 0) return SFC_OK;
   Ctr h;
-  HIPCHK(hipMemcpy(&h, c->ctr, sizeof h, hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(&h, c->ctx[c->last_prepared].ctr, sizeof h, hipMemcpyDeviceToHost));
   if (h.err) return fail(SFC_EHIP, "cache index probe ran off its bound (index corrupt)");
   const int64_t rowbytes = 2 * (int64_t)sizeof(float) * c->D;
   h_out->n_unique = h.U; h_out->n_hit = h.n_hit; h_out->n_miss = h.M; h_out->n_evict = h.K;
@@ -506,9 +635,9 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
   return SFC_OK;
 }
 
-int sfc_profile_enable(sfc_cache* c, int32_t on) {
+int sfc_profile_enable(sfc_cache* c, int32_t level) {
   if (!c) return fail(SFC_EINVAL, "null cache");
-  c->prof = on < 0 ? 0 : (on > 2 ? 2 : on);
+  c->prof = level < 0 ? 0 : (level > 2 ? 2 : level);
   return SFC_OK;
 }
 

@@ -13,6 +13,18 @@ namespace sfc {
 constexpr int kPosChunk = 2048;   // positions (or slots) per block in the scan passes
 constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
 
+// First kernel of a prepare: the new step's counters inherit the cache-wide fields (watermark,
+// oldest stamp, tombstones, rebuild flag, error) from the previous step's and start their own
+// tallies at zero.  Steps in flight on the other stream keep reading their own copy.
+__global__ void k_step_begin(Ctr* cur, const Ctr* prev) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    Ctr c = *prev;
+    c.U = c.M = c.K = c.n_bypass = c.n_hit = c.n_invalid = 0;
+    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0;
+    *cur = c;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // VSI pass 1: insert every position's id into the batch table (open addressing, linear probing,
 // in HBM) and keep the smallest position per key; remember the table entry of each position.
@@ -299,13 +311,14 @@ __global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ off
 // payload = position (one-hot) or bag index (multi-hot).  cursor[v] starts at the exclusive scan
 // of cnt.  Same LDS treatment of the low virtual ids as above; an id that occurs once needs no
 // atomic at all.  The order inside a group is the order in which the atomics land.
-// Also writes pos_slot[p] = slot[inverse[p]] for the forward gather.
+// Also writes pos_slot[p] = row of slot[inverse[p]] for the forward gather (a bypass slot C + j
+// lives at row C + boff + j: each step in flight has its own bypass region).
 __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse,
                                                   const int* __restrict__ pos2bag, int n,
                                                   const int* __restrict__ cnt, int* cursor,
                                                   int64_t* __restrict__ perm64,
                                                   const int* __restrict__ slot,
-                                                  int* __restrict__ pos_slot) {
+                                                  int* __restrict__ pos_slot, int C, int boff) {
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
@@ -332,7 +345,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   for (int j = 0; j < 8; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     if (vv[j] < 0) continue;
-    pos_slot[p] = sv[j];                 // the forward gather reads slots per position
+    pos_slot[p] = sv[j] >= C ? sv[j] + boff : sv[j];   // row index for the forward gather
     if (vv[j] < kHotBins) rr[j] = atomicAdd(&lh[vv[j]], 1);
     else perm64[rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
   }
@@ -511,7 +524,7 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
 __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
                                                const int* __restrict__ age_mat, int age_rows,
                                                int* hist, int t, int lookahead, int C, uint32_t hi,
-                                               Ctr* ctr) {
+                                               int* host_nbypass, Ctr* ctr) {
   static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
   __shared__ int s_found;
@@ -591,6 +604,7 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     const int n_bypass = M - K - (f_new - f);
     hist[t] += M - n_bypass;
     ctr->M = M; ctr->K = K; ctr->n_bypass = n_bypass;
+    *host_nbypass = n_bypass;     // pinned Host word: lets the host skip a stream dependency when 0
     ctr->need = need; ctr->T = T; ctr->r = r;
     ctr->f_old = f; ctr->f = f_new;
     if (need > 0 && T > oldest) ctr->oldest = T;

@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
                                                     const int* __restrict__ slot,
                                                     const int64_t* __restrict__ victim_id,
                                                     float4* __restrict__ cw, float4* __restrict__ ca,
-                                                    HostRows h, int d4, const Ctr* ctr) {
+                                                    HostRows h, int d4, int C, int boff,
+                                                    const Ctr* ctr) {
   const int K = ctr->K;
   const int w2 = 2 * d4;
   const int64_t total = (int64_t)ctr->M * w2;
@@ -54,7 +55,9 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
     float4* hb = acc ? h.a : h.w;
     float4* cb = acc ? ca : cw;
     const int v = miss_vids[k];
-    const int64_t src = unique_ids[v] * h.hs4 + c, dst = (int64_t)slot[v] * d4 + c;
+    int row = slot[v];
+    if (row >= C) row += boff;              // bypass rows of this step's own region
+    const int64_t src = unique_ids[v] * h.hs4 + c, dst = (int64_t)row * d4 + c;
     const float4 nv = hb[src];
     if (k < K) hb[victim_id[k] * h.hs4 + c] = cb[dst];
     cb[dst] = nv;
@@ -436,7 +439,8 @@ __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__
                                                        const int64_t* __restrict__ unique_ids,
                                                        float4* __restrict__ cw,
                                                        float4* __restrict__ ca, HostRows h, int C,
-                                                       float lr, float eps, int d4, const Ctr* ctr) {
+                                                       int boff, float lr, float eps, int d4,
+                                                       const Ctr* ctr) {
   const int64_t total = (int64_t)ctr->U * d4;
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 4 * stride) {
@@ -449,7 +453,10 @@ __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__
       r[u] = -1;
       if (i < total) {
         sl[u] = slot[(int)(i / d4)];
-        if (sl[u] >= 0) { r[u] = (int64_t)sl[u] * d4 + (i % d4); g[u] = common[i]; w[u] = cw[r[u]]; a[u] = ca[r[u]]; }
+        if (sl[u] >= 0) {
+          r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + (i % d4);
+          g[u] = common[i]; w[u] = cw[r[u]]; a[u] = ca[r[u]];
+        }
       }
     }
 #pragma unroll

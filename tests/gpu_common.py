@@ -102,3 +102,60 @@ class Pair:
                 x, y = a[r0:r0 + chunk_rows], b[r0:r0 + chunk_rows]
                 if not np.array_equal(x, y):
                     assert_close(x, y, "%s after flush, rows %d.." % (name, r0))
+
+
+    def run_pipelined(self, batches, sync_every_call):
+        """Steps issued in pipelined order (needs lookahead = 1): prepare / fetch of step t+1 go
+        out between lookup and backward_update of step t.  The oracle runs the same steps one
+        after the other.  With sync_every_call the device is drained after each call and every
+        output of every step is compared; without it nothing waits until the end, so the side
+        stream really overlaps the main one, and lookup outputs, final cache state and flushed
+        tables are compared."""
+        c, o = self.cache, self.orc
+        dev = self.dev
+        sync = torch.cuda.synchronize if sync_every_call else (lambda: None)
+        T = len(batches)
+        d_in = []
+        for ids, grad, off in batches:
+            d_in.append((torch.from_numpy(np.asarray(ids, np.int64)).to(dev),
+                         torch.from_numpy(np.asarray(grad, np.float32)).to(dev),
+                         None if off is None else torch.from_numpy(np.asarray(off, np.int64)).to(dev)))
+        torch.cuda.synchronize()
+        expect = []
+        for ids, grad, off in batches:
+            pr = o.prepare(np.asarray(ids, np.int64), None if off is None else np.asarray(off, np.int64))
+            o.fetch_misses()
+            out = o.lookup()
+            o.backward_update(np.asarray(grad, np.float32))
+            expect.append((pr, out))
+        outs = []
+
+        def check_prepared(t, b):
+            if not sync_every_call:
+                return
+            pr = expect[t][0]
+            st = c.stats()
+            assert st == pr.stats, (t, st, pr.stats)
+            U, M, n = st["n_unique"], st["n_miss"], b.n_ids
+            assert np.array_equal(b.unique_ids[:U].cpu().numpy(), pr.unique_ids), "unique_ids step %d" % t
+            assert np.array_equal(b.inverse[:n].cpu().numpy(), pr.inverse), "inverse step %d" % t
+            assert np.array_equal(b.slot[:U].cpu().numpy(), pr.slot), "slot step %d" % t
+            assert np.array_equal(b.miss_vids[:M].cpu().numpy(), pr.miss_vids), "miss_vids step %d" % t
+
+        b = c.prepare(d_in[0][0], d_in[0][2]); sync(); check_prepared(0, b)
+        c.fetch_misses(); sync()
+        for t in range(T):
+            outs.append(c.lookup()); sync()
+            if t + 1 < T:
+                b = c.prepare(d_in[t + 1][0], d_in[t + 1][2]); sync(); check_prepared(t + 1, b)
+                c.fetch_misses(); sync()
+            c.backward_update(d_in[t][1]); sync()
+        torch.cuda.synchronize()
+        for t in range(T):
+            assert_close(outs[t].cpu().numpy(), expect[t][1], "lookup of step %d" % t)
+        if self.C:
+            sid, stamp = c.state()
+            osid, ostamp = o.state()
+            assert np.array_equal(sid, osid) and np.array_equal(stamp, ostamp), "final cache state"
+        self.finish()
+        return expect

@@ -194,3 +194,40 @@ def test_step_limit():
         p.cache.prepare(torch.arange(5, dtype=torch.int64, device="cuda:0"))
     assert e.value.code == sfc.SFC_ELIMIT
     p.close()
+
+
+def _batches(V, D, n, s, seed, steps):
+    return [(si.zipf_ids(n, s, V, seed, t).numpy(), si.grads(n, D, seed, t).numpy(), None)
+            for t in range(steps)]
+
+
+@pytest.mark.parametrize("sync_every_call", [True, False])
+def test_pipelined_steps_match_sequential_oracle(sync_every_call):
+    # lookahead 1: prepare / fetch of the next step overlap lookup / update of the current one;
+    # the cache is small enough to evict on every step and never has to bypass
+    V, D, n = 20000, 32, 6000
+    p = Pair(V, D, C=9000, max_ids=8192, lookahead=1)
+    p.run_pipelined(_batches(V, D, n, 1.05, 77, 12), sync_every_call)
+    p.close()
+
+
+@pytest.mark.parametrize("sync_every_call", [True, False])
+def test_pipelined_steps_with_bypass_rows(sync_every_call):
+    # the working set of two consecutive batches exceeds the cache: rows bypass it, and a row that
+    # bypassed in step t is missed again in step t+1 and must arrive with the update of step t
+    V, D, n = 3000, 16, 2500
+    p = Pair(V, D, C=500, max_ids=4096, lookahead=1)
+    expect = p.run_pipelined(_batches(V, D, n, 1.05, 78, 10), sync_every_call)
+    assert min(pr.stats["n_bypass"] for pr, _ in expect[1:]) > 0
+    p.close()
+
+
+def test_pipelined_multihot():
+    V, D, nb = 8000, 8, 700
+    p = Pair(V, D, C=5000, max_ids=nb * 20, max_bags=nb, lookahead=1)
+    bs = []
+    for t in range(6):
+        off = si.bag_offsets(nb, 1, 20, 79, t).numpy()
+        bs.append((si.zipf_ids(int(off[-1]), 1.1, V, 79, t).numpy(), si.grads(nb, D, 79, t).numpy(), off))
+    p.run_pipelined(bs, False)
+    p.close()
