@@ -42,8 +42,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
-    ap.add_argument("--lookahead", type=int, default=1, choices=[0, 1],
-                    help="1: prepare/fetch of step t+1 overlap lookup/update of step t (default)")
+    ap.add_argument("--lookahead", type=int, default=2, choices=[0, 1, 2],
+                    help="L > 0: prepare/fetch of step t+L overlap lookup/update of step t; with 2 "
+                         "the copies of step t+1 also overlap the prepare of step t+2 (default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -89,19 +90,26 @@ def main():
     # One step = prepare + fetch_misses + lookup + backward_update.  With lookahead 1 the prepare
     # and fetch issued in an iteration belong to the next step and overlap this step's lookup and
     # update; every iteration still issues exactly one of each call.
-    if args.lookahead:
+    for _ in range(args.lookahead):          # fill the pipeline
         b0 = next_batch()
         cache.prepare(b0[0], b0[1])
         cache.fetch_misses()
 
-    def run_steps(batches, k0=0):
+    def run_steps(batches, k0=0, overlap=True):
         for i, b in enumerate(batches):
             g = grads[(k0 + i) % 4]
-            if args.lookahead:
+            if args.lookahead and overlap:
                 cache.lookup(out)
                 cache.prepare(b[0], b[1])
                 cache.fetch_misses()
                 cache.backward_update(g)
+            elif args.lookahead:
+                # same calls, same kernels, but the next step's prepare is issued after this
+                # step's update, so the two streams never run at the same time
+                cache.lookup(out)
+                cache.backward_update(g)
+                cache.prepare(b[0], b[1])
+                cache.fetch_misses()
             else:
                 cache.prepare(b[0], b[1])
                 cache.fetch_misses()
@@ -126,14 +134,17 @@ def main():
     wall = time.perf_counter() - t_start
 
     # pass 2: K more steps with hipEvents around every step call (the next batches of the same
-    # sequence, so the cache keeps evolving as in training); device counters sampled on the way
+    # sequence, so the cache keeps evolving as in training); device counters sampled on the way.
+    # Kernel and call durations are taken with the two streams not overlapping, i.e. each kernel
+    # has the GPU to itself as in the lookahead-0 order; pass 4 below times the calls again in the
+    # overlapped order of the timed region.
     batches2 = [next_batch() for _ in range(K)]
     torch.cuda.synchronize()
     sfc.sfc_profile_enable(cache.h, 1)
     agg = dict(n_unique=0, n_hit=0, n_miss=0, n_evict=0, n_bypass=0, h2d_bytes=0, d2h_bytes=0)
     ns = 0
     for t in range(K):
-        run_steps([batches2[t]], t)
+        run_steps([batches2[t]], t, overlap=False)
         if t % max(1, K // 10) == 0:          # sample the device counters (each read synchronises)
             st = cache.stats()
             for k in agg:
@@ -144,10 +155,20 @@ def main():
     batches3 = [next_batch() for _ in range(K)]
     torch.cuda.synchronize()
     sfc.sfc_profile_enable(cache.h, 2)
-    run_steps(batches3)
+    run_steps(batches3, overlap=False)
     prof3 = sfc.sfc_profile_read(cache.h)
     for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows"):
         prof[k] = prof3[k]
+    overlapped_ms = None
+    if args.lookahead:
+        # pass 4: call durations in the overlapped order of the timed region
+        batches4 = [next_batch() for _ in range(K)]
+        torch.cuda.synchronize()
+        sfc.sfc_profile_enable(cache.h, 1)
+        run_steps(batches4)
+        p4 = sfc.sfc_profile_read(cache.h)
+        overlapped_ms = {k: (p4[k][0] / p4[k][1] if p4[k][1] else 0.0)
+                         for k in ("prepare", "fetch_misses", "lookup", "backward_update")}
     sfc.sfc_profile_enable(cache.h, 0)
     ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
     avg = {k: v / ns for k, v in agg.items()}
@@ -201,6 +222,7 @@ def main():
                                "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "call_ms": {k: ms[k] for k in ("prepare", "fetch_misses", "lookup", "backward_update")},
         "kernel_ms": {k: ms[k] for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows")},
+        "call_ms_overlapped": overlapped_ms,
         "host_link": {"h2d_bytes_per_step": avg["h2d_bytes"], "d2h_bytes_per_step": avg["d2h_bytes"],
                       "GB/s": ((avg["h2d_bytes"] + avg["d2h_bytes"]) / (link_ms * 1e-3) / 1e9
                                if link_ms else None)},
@@ -211,7 +233,7 @@ def main():
         # seeded batch sequence from a cold oracle cache, run in place on the host table after
         # the GPU run has been flushed into it (values differ from step 0, the work does not).
         from oracle import Oracle
-        if args.lookahead:                    # retire the step that is still in flight
+        for _ in range(args.lookahead):       # retire the steps that are still in flight
             cache.lookup(out)
             cache.backward_update(grads[0])
         cache.flush()

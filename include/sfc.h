@@ -3,7 +3,7 @@
  * (Virtual Sparse Id + MixCache + gather + gradient segment-sum + sparse
  * Adagrad), implemented with HIP kernels for gfx950 (MI355X).
  *
- * One training step is four calls, in this order (with lookahead = 1 the first two of step t+1 may
+ * One training step is four calls, in this order (with lookahead = L > 0 the first two of step t+L may
  * precede the last of step t; sfc_lookup, sfc_segment_sum and sfc_backward_update always act on
  * the oldest step that has been fetched and not yet updated) (Algorithm 1, lines 3-14,
  * with the multi-GPU lines 7, 10 and 13 and the dense model of line 12 left to
@@ -64,14 +64,18 @@ typedef struct {
                                  host link moves fastest. */
   float lr;                   /* Adagrad learning rate */
   float eps;                  /* Adagrad epsilon, added outside the square root */
-  int32_t lookahead;          /* 0: rows of the batch being prepared are protected from eviction;
-                                 calls of a step go prepare, fetch_misses, lookup, backward_update.
-                                 1: rows of the previous batch are protected as well, and
-                                 sfc_prepare / sfc_fetch_misses of step t+1 may be called before
-                                 sfc_backward_update of step t: they run on side_stream while the
-                                 main stream works on step t (the paper's pipeline of Host-Manager
-                                 and GPU-Worker).  The caller then alternates two sets of prepare
-                                 buffers. */
+  int32_t lookahead;          /* L = 0, 1 or 2: how many steps may be prepared ahead of the one being
+                                 trained.  Rows used by the batch being prepared and by the L
+                                 batches before it are protected from eviction.
+                                 0: calls of a step go prepare, fetch_misses, lookup,
+                                 backward_update, all in order.
+                                 L > 0 (needs side_stream != stream): sfc_prepare /
+                                 sfc_fetch_misses of step t+L may be called before
+                                 sfc_backward_update of step t; they run on other streams while the
+                                 main stream works on step t (the paper's pipeline of Data-Loader,
+                                 Host-Manager and GPU-Worker stages).  With L = 2 the Host copies of
+                                 step t+1 also overlap the prepare of step t+2.  The caller rotates
+                                 L + 1 sets of prepare buffers. */
   int32_t max_steps;          /* steps this cache may run (sizes the recency histogram); 0 = 1<<20 */
   void* stream;               /* hipStream_t for prepare / lookup / backward_update */
   void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */
@@ -116,7 +120,7 @@ void sfc_cache_destroy(sfc_cache* c);
  *  d_miss_vids   virtual ids that must be fetched from Host, ascending; n_miss entries.
  * Hit / miss / victim counts stay on the device (sfc_get_stats reads them).
  * Victims are chosen by batch-granular LRU: among resident rows not used by this batch (nor by
- * the previous one when lookahead = 1), those whose last use is oldest, ties by lower slot; the
+ * the `lookahead` batches before it), those whose last use is oldest, ties by lower slot; the
  * i-th miss takes the i-th slot of (free + victim slots) in ascending slot order.
  * Errors: SFC_EINVAL (null pointers, n_ids > max_ids_per_batch, n_bags > max_bags_per_batch,
  * one-hot with n_bags != n_ids), SFC_ELIMIT, SFC_EHIP.  Malformed offsets are not detected.

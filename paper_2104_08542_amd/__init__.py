@@ -253,9 +253,9 @@ class Cache:
     """One sfc_cache with its output buffers; methods mirror the C calls of a step.
 
     lookahead = 0: prepare, fetch_misses, lookup, backward_update in that order.
-    lookahead = 1: prepare / fetch_misses of step t+1 may be issued before backward_update of
-    step t (they run on the side stream meanwhile); lookup and backward_update always act on the
-    oldest step that has not been updated.  Two sets of output buffers alternate.
+    lookahead = L (1 or 2): prepare / fetch_misses of step t+L may be issued before backward_update
+    of step t (they run on other streams meanwhile); lookup and backward_update always act on the
+    oldest step that has not been updated.  lookahead + 1 sets of output buffers rotate.
     """
 
     def __init__(self, table: HostTable, capacity_rows: int, max_ids: int, max_bags: Optional[int] = None,

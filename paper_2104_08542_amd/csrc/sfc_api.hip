@@ -43,7 +43,7 @@ int fail(int code, const char* what, hipError_t e = hipSuccess) {
   } while (0)
 
 // life of a step context
-enum State { FREE = 0, PREPARED = 1, FETCH_DEFERRED = 2, FETCHED = 3 };
+enum State { FREE = 0, PREPARED = 1, FETCHED = 2 };
 enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEG_STREAM = 4, P_SEG_FINISH = 5,
        P_ADAGRAD = 6, P_N = 7 };
 
@@ -62,15 +62,19 @@ struct StepCtx {
   int* victim_slot = nullptr;         // [max_ids]
   int64_t* victim_id = nullptr;       // [max_ids]
   int boff = 0;                       // bypass slot C + j lives at row C + boff + j
-  volatile int* h_nbypass = nullptr;  // pinned Host word written by the plan kernel (-1 = not yet)
-  int* d_nbypass = nullptr;           // its device address
   hipEvent_t ev_prepared = nullptr;   // the step's prepare kernels have run
-  hipEvent_t ev_fetched = nullptr;    // the step's rows are in place
-  bool fetched_on_main = false;
+  hipEvent_t ev_fetched = nullptr;    // the side-stream launch of the step's Host copies has run
   bool updated = false;               // backward_update has been enqueued for this step
+  // pipelined mode: the second launch of the Host copies, due on the main stream behind the
+  // update of step main_after (see k_swap_rows); older1 / older2 = counters of the older steps
+  // that were still in flight when the fetch was issued
+  bool main_pending = false;
+  int main_after = 0;
+  const Ctr *older1 = nullptr, *older2 = nullptr;
+  int chain = 0;
 };
 
-constexpr int kMaxCtx = 2;
+constexpr int kMaxCtx = 3;
 
 }  // namespace
 
@@ -78,7 +82,9 @@ struct sfc_cache {
   sfc_config cfg{};
   int64_t C = 0, V = 0, max_ids = 0, max_bags = 0;
   int D = 0, d4 = 0, nctx = 1;
-  hipStream_t st = nullptr, side = nullptr;
+  hipStream_t st = nullptr, side = nullptr;     // main stream; stream of the Host copies
+  hipStream_t prep = nullptr;                   // stream of the prepare kernels
+  bool own_prep = false;                        // prep was created here (lookahead 2)
   hipEvent_t ev_tmp = nullptr;                  // cross-stream ordering inside one call
   // device memory
   float *cw = nullptr, *ca = nullptr;           // [(C + nctx * max_ids), D]
@@ -99,7 +105,6 @@ struct sfc_cache {
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
   HostRows host{};                              // device view of the Host table
-  int* h_words = nullptr;                       // pinned Host words (bypass counts)
   std::vector<void*> allocs;
   // steps
   StepCtx ctx[kMaxCtx];
@@ -178,36 +183,37 @@ StepCtx* training_ctx(sfc_cache* c) {
   StepCtx* best = nullptr;
   for (int k = 0; k < c->nctx; ++k) {
     StepCtx* x = &c->ctx[k];
-    if ((x->state == FETCHED || x->state == FETCH_DEFERRED) && !x->updated && (!best || x->t < best->t))
+    if (x->state == FETCHED && !x->updated && (!best || x->t < best->t))
       best = x;
   }
   return best;
 }
 
-// Host<->cache copies of one step, on stream s.
-int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s) {
+// One launch of the Host<->cache copies of a step on stream s (see k_swap_rows for the two
+// launches of pipelined mode).
+int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
   EventPair ep{};
   int rc;
   // the copies read the step's counters, miss list and victim list: its prepare comes first
-  // (on the same stream that is automatic; a fetch deferred to the main stream must wait)
-  HIPCHK(hipStreamWaitEvent(s, x->ev_prepared, 0));
-  if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
+  if (s != c->prep) HIPCHK(hipStreamWaitEvent(s, x->ev_prepared, 0));
+  const bool timed = !main_variant;
+  if (timed && (rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
   hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, 1024)), dim3(256), 0, s,
                      x->d_miss, x->d_unique, x->d_slot, x->victim_id, (float4*)c->cw,
-                     (float4*)c->ca, c->host, c->d4, (int)c->C, x->boff, x->ctr);
+                     (float4*)c->ca, c->host, c->d4, (int)c->C, x->boff, x->ctr, x->older1,
+                     x->older2, x->chain, main_variant);
   HIPCHK(hipGetLastError());
-  if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
-  HIPCHK(hipEventRecord(x->ev_fetched, s));
-  x->fetched_on_main = s == c->st;
-  x->state = FETCHED;
+  if (timed && (rc = prof_end(c, P_FETCH, s, &ep))) return rc;
+  if (main_variant) x->main_pending = false;
+  else HIPCHK(hipEventRecord(x->ev_fetched, s));
   return SFC_OK;
 }
 
-// Before main-stream work that reads the step's rows: run a deferred fetch, or wait for the side
-// stream's one.
+// Before main-stream work that reads the step's rows: both launches of its copies come first.
 int rows_ready(sfc_cache* c, StepCtx* x) {
-  if (x->state == FETCH_DEFERRED) return launch_swap(c, x, c->st);
-  if (!x->fetched_on_main) HIPCHK(hipStreamWaitEvent(c->st, x->ev_fetched, 0));
+  int rc;
+  if (x->main_pending && (rc = launch_swap(c, x, c->st, 1))) return rc;
+  if (c->side != c->st) HIPCHK(hipStreamWaitEvent(c->st, x->ev_fetched, 0));
   return SFC_OK;
 }
 
@@ -232,6 +238,7 @@ int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common) {
 int sync_all(sfc_cache* c) {
   HIPCHK(hipStreamSynchronize(c->st));
   if (c->side != c->st) HIPCHK(hipStreamSynchronize(c->side));
+  if (c->prep != c->st && c->prep != c->side) HIPCHK(hipStreamSynchronize(c->prep));
   return SFC_OK;
 }
 
@@ -267,6 +274,7 @@ void sfc_cache_destroy(sfc_cache* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->st);
   if (c->side != c->st) (void)hipStreamSynchronize(c->side);
+  if (c->own_prep && c->prep) (void)hipStreamSynchronize(c->prep);
   for (int w = 0; w < P_N; ++w)
     for (EventPair& ep : c->pending[w]) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
   for (EventPair& ep : c->spare) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
@@ -275,7 +283,7 @@ void sfc_cache_destroy(sfc_cache* c) {
     if (c->ctx[k].ev_prepared) (void)hipEventDestroy(c->ctx[k].ev_prepared);
     if (c->ctx[k].ev_fetched) (void)hipEventDestroy(c->ctx[k].ev_fetched);
   }
-  if (c->h_words) (void)hipHostFree(c->h_words);
+  if (c->own_prep && c->prep) (void)hipStreamDestroy(c->prep);
   for (void* p : c->allocs) (void)hipFree(p);
   delete c;
 }
@@ -288,7 +296,9 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if (cfg->policy != SFC_POLICY_LRU_BATCH) return fail(SFC_EINVAL, "unknown policy");
   if (cfg->max_ids_per_batch < 1 || cfg->max_bags_per_batch < 1 || cfg->host_rows < 1)
     return fail(SFC_EINVAL, "max_ids_per_batch, max_bags_per_batch and host_rows must be >= 1");
-  if (cfg->lookahead < 0 || cfg->lookahead > 1) return fail(SFC_EINVAL, "lookahead must be 0 or 1");
+  if (cfg->lookahead < 0 || cfg->lookahead > 2) return fail(SFC_EINVAL, "lookahead must be 0, 1 or 2");
+  if (cfg->lookahead > 0 && (!cfg->side_stream || cfg->side_stream == cfg->stream))
+    return fail(SFC_EINVAL, "lookahead > 0 needs a side_stream different from stream");
   const int64_t nctx = cfg->lookahead + 1;
   if (cfg->capacity_rows + nctx * cfg->max_ids_per_batch >= (int64_t)1 << 31 ||
       cfg->max_ids_per_batch >= (int64_t)1 << 30 || cfg->max_bags_per_batch >= (int64_t)1 << 31)
@@ -324,9 +334,15 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   }
   c->host.a = (float4*)dp;
   c->host.hs4 = (cfg->host_row_stride ? cfg->host_row_stride : cfg->dim) / 4;
-  if ((e = hipHostMalloc((void**)&c->h_words, 64 * sizeof(int), hipHostMallocMapped)) != hipSuccess) {
-    c->h_words = nullptr;
-    rc = fail(SFC_ENOMEM, "hipHostMalloc", e); goto bad;
+  // lookahead 0: prepare on the main stream; 1: on the side stream, ahead of that step's copies;
+  // 2: on a stream of its own, so that the copies of step t+1 overlap the prepare of step t+2
+  c->prep = cfg->lookahead == 0 ? c->st : c->side;
+  if (cfg->lookahead == 2) {
+    if ((e = hipStreamCreateWithFlags(&c->prep, hipStreamNonBlocking)) != hipSuccess) {
+      c->prep = nullptr;
+      rc = fail(SFC_EHIP, "hipStreamCreate", e); goto bad;
+    }
+    c->own_prep = true;
   }
 
   {
@@ -358,10 +374,6 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       if ((rc = dalloc(c, &c->bp_vid, 2 * nwmax))) goto bad;
     }
     if ((rc = dalloc(c, &c->gsum, c->max_ids * c->D))) goto bad;
-    void* dwords = nullptr;
-    if ((e = hipHostGetDevicePointer(&dwords, c->h_words, 0)) != hipSuccess) {
-      rc = fail(SFC_EHIP, "hipHostGetDevicePointer", e); goto bad;
-    }
     for (int k = 0; k < c->nctx; ++k) {
       StepCtx* x = &c->ctx[k];
       if ((rc = dalloc(c, &x->ctr, 1))) goto bad;
@@ -370,9 +382,6 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       if ((rc = dalloc(c, &x->victim_slot, c->max_ids))) goto bad;
       if ((rc = dalloc(c, &x->victim_id, c->max_ids))) goto bad;
       x->boff = (int)(k * c->max_ids);
-      x->h_nbypass = c->h_words + 16 * k;
-      x->d_nbypass = (int*)dwords + 16 * k;
-      *x->h_nbypass = 0;
       if ((e = hipEventCreateWithFlags(&x->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
           (e = hipEventCreateWithFlags(&x->ev_fetched, hipEventDisableTiming)) != hipSuccess) {
         rc = fail(SFC_EHIP, "hipEventCreate", e); goto bad;
@@ -422,26 +431,24 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   for (int k = 0; k < c->nctx; ++k)
     if (c->ctx[k].state == FREE) { x = &c->ctx[k]; break; }
   if (!x) {
-    StepCtx* old = training_ctx(c);
-    if (!old) return fail(SFC_ESTATE, "no step context free");
-    if (old->state == FETCH_DEFERRED)
-      return fail(SFC_ESTATE, "the step in flight has not been looked up or updated yet");
-    x = old;
+    x = training_ctx(c);
+    if (!x) return fail(SFC_ESTATE, "no step context free");
+    if (x->main_pending) return fail(SFC_ESTATE, "the oldest step in flight has not been looked up or updated yet");
   }
   StepCtx* prev = c->last_prepared >= 0 ? &c->ctx[c->last_prepared] : x;
-  const bool pipelined = c->nctx > 1;
-  hipStream_t s = pipelined ? c->side : c->st;
-  if (pipelined) {
-    // the side stream must not overtake what the main stream has been given so far: the producer
-    // of d_ids, the last update that read this context's buffers, a fetch deferred to that stream
+  hipStream_t s = c->prep;
+  if (s != c->st) {
+    // the prepare stream must not overtake what the main stream has been given so far: the
+    // producer of d_ids and the last update that read this context's buffers
     HIPCHK(hipEventRecord(c->ev_tmp, c->st));
     HIPCHK(hipStreamWaitEvent(s, c->ev_tmp, 0));
+    // a context taken over from a step that was never updated: its copies may still be reading its lists
+    if (x->state == FETCHED && s != c->side) HIPCHK(hipStreamWaitEvent(s, x->ev_fetched, 0));
   }
   c->t += 1;
-  x->t = c->t; x->state = PREPARED; x->updated = false; x->fetched_on_main = false;
+  x->t = c->t; x->state = PREPARED; x->updated = false; x->main_pending = false;
   x->n_ids = n_ids; x->n_bags = n_bags; x->d_offsets = d_offsets;
   x->d_unique = d_unique_ids; x->d_inverse = d_inverse; x->d_slot = d_slot; x->d_miss = d_miss_vids;
-  *x->h_nbypass = -1;
   c->last_prepared = (int)(x - c->ctx);
 
   EventPair ep{};
@@ -476,7 +483,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt,
                      c->tile_cnt, c->age_mat, x->ctr);
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_mat, gr,
-                     c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->d_nbypass, x->ctr);
+                     c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
                      x->ctr);
@@ -501,24 +508,28 @@ int sfc_fetch_misses(sfc_cache* c) {
   if (!c) return fail(SFC_EINVAL, "null cache");
   StepCtx* x = c->last_prepared >= 0 ? &c->ctx[c->last_prepared] : nullptr;
   if (!x || x->state != PREPARED) return fail(SFC_ESTATE, "sfc_fetch_misses needs a preceding sfc_prepare");
-  if (c->nctx > 1) {
-    // A row that bypassed the cache in the step still in flight reaches the Host table only with
-    // that step's update.  If that step may have had bypass rows (its count is not yet known to
-    // the host, or is nonzero) and its update has not been enqueued, this step's copies are
-    // deferred to the main stream, behind that update; otherwise they go to the side stream now.
-    StepCtx* o = training_ctx(c);
-    if (o && o != x && *o->h_nbypass != 0) {
-      x->state = FETCH_DEFERRED;
-      return SFC_OK;
-    }
+  // older steps whose update has not been enqueued yet: their bypass rows are not in the Host
+  // table yet (k_swap_rows decides on the device which of its two launches does the work)
+  x->older1 = x->older2 = nullptr;
+  x->chain = 0; x->main_pending = false; x->main_after = 0;
+  for (int k = 0; k < c->nctx; ++k) {
+    StepCtx* o = &c->ctx[k];
+    if (o == x || o->state != FETCHED || o->updated) continue;
+    if (o->t == x->t - 1) { x->older1 = o->ctr; x->chain = o->main_pending ? 1 : 0; }
+    else if (o->t == x->t - 2) x->older2 = o->ctr;
+    if (o->t > x->main_after) x->main_after = o->t;
   }
   if (c->side != c->st) {
     // everything the main stream has been given so far comes first: this step's prepare
-    // (lookahead 0), or the last update and a fetch that was deferred to that stream
+    // (lookahead 0), older updates and their second launches
     HIPCHK(hipEventRecord(c->ev_tmp, c->st));
     HIPCHK(hipStreamWaitEvent(c->side, c->ev_tmp, 0));
   }
-  return launch_swap(c, x, c->side);
+  int rc = launch_swap(c, x, c->side, 0);
+  if (rc) return rc;
+  x->main_pending = x->older1 || x->older2;
+  x->state = FETCHED;
+  return SFC_OK;
 }
 
 int sfc_lookup(sfc_cache* c, float* d_out) {
@@ -584,16 +595,23 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if ((rc = prof_end(c, P_BACKWARD, s, &ep))) return rc;
   x->updated = true;
   x->state = FREE;
-  // a fetch of the next step that had to wait for this update runs now, behind it
-  for (int k = 0; k < c->nctx; ++k)
-    if (c->ctx[k].state == FETCH_DEFERRED && (rc = launch_swap(c, &c->ctx[k], s))) return rc;
+  // second launches of the copies of newer steps that had to stay behind this update, oldest first
+  for (int pass = 0; pass < c->nctx; ++pass) {
+    StepCtx* y = nullptr;
+    for (int k = 0; k < c->nctx; ++k) {
+      StepCtx* z = &c->ctx[k];
+      if (z->state == FETCHED && z->main_pending && z->main_after <= x->t && (!y || z->t < y->t)) y = z;
+    }
+    if (!y) break;
+    if ((rc = launch_swap(c, y, s, 1))) return rc;
+  }
   return SFC_OK;
 }
 
 int sfc_flush(sfc_cache* c) {
   if (!c) return fail(SFC_EINVAL, "null cache");
   for (int k = 0; k < c->nctx; ++k)
-    if (c->ctx[k].state == PREPARED || c->ctx[k].state == FETCH_DEFERRED)
+    if (c->ctx[k].state == PREPARED || (c->ctx[k].state == FETCHED && c->ctx[k].main_pending))
       return fail(SFC_ESTATE, "sfc_flush while a prepared step still waits for its rows");
   int rc = sync_all(c);
   if (rc) return rc;

@@ -30,7 +30,7 @@ struct Ctr {
   int tomb;       // deleted entries in the cache index
   int rebuild;    // set when the index must be rebuilt before the next resolve
   int err;        // nonzero: a probe loop ran off its bound
-  int pad;
+  int fetch_on_main;  // pipelined mode: this step's Host copies ran behind the older steps' updates
 };
 
 // Entry of the per-step batch table: key and the smallest position that carries it, one 16-byte

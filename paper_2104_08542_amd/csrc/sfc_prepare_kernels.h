@@ -20,7 +20,7 @@ __global__ void k_step_begin(Ctr* cur, const Ctr* prev) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     Ctr c = *prev;
     c.U = c.M = c.K = c.n_bypass = c.n_hit = c.n_invalid = 0;
-    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0;
+    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
     *cur = c;
   }
 }
@@ -524,7 +524,7 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
 __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
                                                const int* __restrict__ age_mat, int age_rows,
                                                int* hist, int t, int lookahead, int C, uint32_t hi,
-                                               int* host_nbypass, Ctr* ctr) {
+                                               Ctr* ctr) {
   static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
   __shared__ int s_found;
@@ -604,7 +604,6 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     const int n_bypass = M - K - (f_new - f);
     hist[t] += M - n_bypass;
     ctr->M = M; ctr->K = K; ctr->n_bypass = n_bypass;
-    *host_nbypass = n_bypass;     // pinned Host word: lets the host skip a stream dependency when 0
     ctr->need = need; ctr->T = T; ctr->r = r;
     ctr->f_old = f; ctr->f = f_new;
     if (need > 0 && T > oldest) ctr->oldest = T;

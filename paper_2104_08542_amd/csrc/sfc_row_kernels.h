@@ -30,6 +30,14 @@ __device__ __forceinline__ void st_stream(float4* p, float4 v) {
 // assignment), so one lane group does both directions for that slot: it loads the victim's row
 // from HBM and the missed row from Host, then stores each on the other side.  Reads and writes
 // cross the link at the same time instead of one after the other.
+//
+// Pipelined steps: a row that bypassed the cache in an older step still in flight reaches the
+// Host table only with that step's update, so this step's copies must then run behind it.  The
+// host cannot know whether that happened without waiting, so it launches the kernel twice: once
+// on the side stream right away and once on the main stream behind the older steps' updates; the
+// device counters decide which of the two launches does the work (on_main below), the other one
+// returns at once.  `chain` extends the rule to "the previous step's copies ran on the main
+// stream and that launch was not yet enqueued when this one was issued".
 // ---------------------------------------------------------------------------------------------
 struct HostRows {
   float4* w;      // device view of h_weights
@@ -43,7 +51,13 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
                                                     const int64_t* __restrict__ victim_id,
                                                     float4* __restrict__ cw, float4* __restrict__ ca,
                                                     HostRows h, int d4, int C, int boff,
-                                                    const Ctr* ctr) {
+                                                    Ctr* ctr, const Ctr* older1,
+                                                    const Ctr* older2, int chain,
+                                                    int main_variant) {
+  const bool on_main = (older1 && older1->n_bypass != 0) || (older2 && older2->n_bypass != 0) ||
+                       (chain && older1 && older1->fetch_on_main != 0);
+  if (blockIdx.x == 0 && threadIdx.x == 0) ctr->fetch_on_main = on_main;   // same value from both launches
+  if (on_main != (main_variant != 0)) return;
   const int K = ctr->K;
   const int w2 = 2 * d4;
   const int64_t total = (int64_t)ctr->M * w2;

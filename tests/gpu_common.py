@@ -105,7 +105,7 @@ class Pair:
 
 
     def run_pipelined(self, batches, sync_every_call):
-        """Steps issued in pipelined order (needs lookahead = 1): prepare / fetch of step t+1 go
+        """Steps issued in pipelined order (lookahead L >= 1): prepare / fetch of step t+L go
         out between lookup and backward_update of step t.  The oracle runs the same steps one
         after the other.  With sync_every_call the device is drained after each call and every
         output of every step is compared; without it nothing waits until the end, so the side
@@ -142,12 +142,14 @@ class Pair:
             assert np.array_equal(b.slot[:U].cpu().numpy(), pr.slot), "slot step %d" % t
             assert np.array_equal(b.miss_vids[:M].cpu().numpy(), pr.miss_vids), "miss_vids step %d" % t
 
-        b = c.prepare(d_in[0][0], d_in[0][2]); sync(); check_prepared(0, b)
-        c.fetch_misses(); sync()
+        L = max(1, c.lookahead)
+        for t in range(min(L, T)):                  # fill the pipeline
+            b = c.prepare(d_in[t][0], d_in[t][2]); sync(); check_prepared(t, b)
+            c.fetch_misses(); sync()
         for t in range(T):
             outs.append(c.lookup()); sync()
-            if t + 1 < T:
-                b = c.prepare(d_in[t + 1][0], d_in[t + 1][2]); sync(); check_prepared(t + 1, b)
+            if t + L < T:
+                b = c.prepare(d_in[t + L][0], d_in[t + L][2]); sync(); check_prepared(t + L, b)
                 c.fetch_misses(); sync()
             c.backward_update(d_in[t][1]); sync()
         torch.cuda.synchronize()

@@ -201,30 +201,48 @@ def _batches(V, D, n, s, seed, steps):
             for t in range(steps)]
 
 
+@pytest.mark.parametrize("lookahead", [1, 2])
 @pytest.mark.parametrize("sync_every_call", [True, False])
-def test_pipelined_steps_match_sequential_oracle(sync_every_call):
-    # lookahead 1: prepare / fetch of the next step overlap lookup / update of the current one;
-    # the cache is small enough to evict on every step and never has to bypass
+def test_pipelined_steps_match_sequential_oracle(sync_every_call, lookahead):
+    # prepare / fetch of later steps overlap lookup / update of the current one; the cache is
+    # small enough to evict on every step and large enough never to bypass
     V, D, n = 20000, 32, 6000
-    p = Pair(V, D, C=9000, max_ids=8192, lookahead=1)
+    p = Pair(V, D, C=12000, max_ids=8192, lookahead=lookahead)
     p.run_pipelined(_batches(V, D, n, 1.05, 77, 12), sync_every_call)
     p.close()
 
 
+@pytest.mark.parametrize("lookahead", [1, 2])
 @pytest.mark.parametrize("sync_every_call", [True, False])
-def test_pipelined_steps_with_bypass_rows(sync_every_call):
+def test_pipelined_steps_with_bypass_rows(sync_every_call, lookahead):
     # the working set of two consecutive batches exceeds the cache: rows bypass it, and a row that
     # bypassed in step t is missed again in step t+1 and must arrive with the update of step t
     V, D, n = 3000, 16, 2500
-    p = Pair(V, D, C=500, max_ids=4096, lookahead=1)
+    p = Pair(V, D, C=500, max_ids=4096, lookahead=lookahead)
     expect = p.run_pipelined(_batches(V, D, n, 1.05, 78, 10), sync_every_call)
     assert min(pr.stats["n_bypass"] for pr, _ in expect[1:]) > 0
     p.close()
 
 
-def test_pipelined_multihot():
+def test_pipelined_mixed_bypass_and_none():
+    # steps with and without bypass rows alternate, so the Host copies switch between the two
+    # streams from step to step
+    V, D = 6000, 8
+    p = Pair(V, D, C=1000, max_ids=4096, lookahead=2)
+    bs = []
+    for t in range(16):
+        n = 3500 if t % 5 == 0 else 300
+        bs.append((si.zipf_ids(n, 1.02, V, 80, t).numpy(), si.grads(n, D, 80, t).numpy(), None))
+    expect = p.run_pipelined(bs, False)
+    nb = [pr.stats["n_bypass"] for pr, _ in expect]
+    assert max(nb) > 0 and min(nb) == 0
+    p.close()
+
+
+@pytest.mark.parametrize("lookahead", [1, 2])
+def test_pipelined_multihot(lookahead):
     V, D, nb = 8000, 8, 700
-    p = Pair(V, D, C=5000, max_ids=nb * 20, max_bags=nb, lookahead=1)
+    p = Pair(V, D, C=5000, max_ids=nb * 20, max_bags=nb, lookahead=lookahead)
     bs = []
     for t in range(6):
         off = si.bag_offsets(nb, 1, 20, 79, t).numpy()
