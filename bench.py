@@ -110,6 +110,8 @@ def main():
                 cache.backward_update(g)
                 cache.prepare(b[0], b[1])
                 cache.fetch_misses()
+                if args.lookahead > 1:
+                    cache.stream.wait_stream(cache.side)   # lookup(t+1) would not wait for fetch(t+2)
             else:
                 cache.prepare(b[0], b[1])
                 cache.fetch_misses()
@@ -230,14 +232,17 @@ def main():
 
     if not args.no_cpu_baseline:
         # The oracle as it stands, single-threaded, on the same workload: first steps of the same
-        # seeded batch sequence from a cold oracle cache, run in place on the host table after
-        # the GPU run has been flushed into it (values differ from step 0, the work does not).
+        # seeded batch sequence from a cold oracle cache, on a dense copy of the host table taken
+        # after the GPU run has been flushed into it (values differ from step 0, the work does not).
         from oracle import Oracle
         for _ in range(args.lookahead):       # retire the steps that are still in flight
             cache.lookup(out)
             cache.backward_update(grads[0])
         cache.flush()
-        orc = Oracle(C, D, table.w, table.acc, lr=w.lr, eps=w.eps)
+        t1 = time.time()
+        ow, oa = np.ascontiguousarray(table.w), np.ascontiguousarray(table.acc)
+        log("dense copy of the host table for the oracle in %.1fs" % (time.time() - t1))
+        orc = Oracle(C, D, ow, oa, lr=w.lr, eps=w.eps)
         done_ids, steps_done, cpu_t = 0, 0, 0.0
         while cpu_t < args.cpu_seconds and steps_done < 50:
             ids, off = w.batch_ids(steps_done, dev)

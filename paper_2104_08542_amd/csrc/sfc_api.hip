@@ -189,6 +189,10 @@ StepCtx* training_ctx(sfc_cache* c) {
   return best;
 }
 
+// The copies are bound by the host link: 32 blocks x 256 lanes x 16 bytes in flight saturate it
+// (measured), and a wider grid only slows the kernels that run beside it on the other streams.
+constexpr int kSwapBlocks = 32;
+
 // One launch of the Host<->cache copies of a step on stream s (see k_swap_rows for the two
 // launches of pipelined mode).
 int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
@@ -198,7 +202,7 @@ int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
   if (s != c->prep) HIPCHK(hipStreamWaitEvent(s, x->ev_prepared, 0));
   const bool timed = !main_variant;
   if (timed && (rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
-  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, 1024)), dim3(256), 0, s,
+  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, kSwapBlocks)), dim3(256), 0, s,
                      x->d_miss, x->d_unique, x->d_slot, x->victim_id, (float4*)c->cw,
                      (float4*)c->ca, c->host, c->d4, (int)c->C, x->boff, x->ctr, x->older1,
                      x->older2, x->chain, main_variant);
