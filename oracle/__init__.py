@@ -43,7 +43,7 @@ def _load():
         lib = ctypes.CDLL(build())
         vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
         lib.orc_create.restype = vp
-        lib.orc_create.argtypes = [i64, i32, i64, vp, vp, f32, f32, i32]
+        lib.orc_create.argtypes = [i64, i32, i64, vp, vp, f32, f32, i32, i32, ctypes.c_double, ctypes.c_double]
         lib.orc_destroy.argtypes = [vp]
         lib.orc_prepare.restype = ctypes.c_int
         lib.orc_prepare.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, ctypes.POINTER(_Stats)]
@@ -60,6 +60,14 @@ def _ptr(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
+OPTIMIZERS = ("adagrad", "adam", "rowwise_adagrad")
+
+
+def state_floats(optimizer, dim):
+    """Floats of optimizer state that travel with one row."""
+    return {"adagrad": dim, "adam": 2 * dim, "rowwise_adagrad": 1}[optimizer]
+
+
 @dataclass
 class Prepared:
     unique_ids: np.ndarray    # [U] int64, first-appearance order (global_id); -1 = null entry
@@ -74,15 +82,20 @@ class Prepared:
 class Oracle:
     """One cache + host table pair, stepped with prepare/fetch/lookup/backward_update."""
 
-    def __init__(self, capacity_rows, dim, host_w, host_acc, lr=0.01, eps=1e-8, lookahead=0):
+    def __init__(self, capacity_rows, dim, host_w, host_acc, lr=0.01, eps=1e-8, lookahead=0,
+                 optimizer="adagrad", betas=(0.9, 0.999)):
+        """host_acc is the optimizer state [V, S]: S = dim (adagrad: accumulators), 2*dim (adam:
+        first moments then second moments) or 1 (rowwise_adagrad)."""
+        self.S = state_floats(optimizer, dim)
         assert host_w.dtype == np.float32 and host_acc.dtype == np.float32
         assert host_w.flags.c_contiguous and host_acc.flags.c_contiguous
-        assert host_w.shape == host_acc.shape and host_w.shape[1] == dim
+        assert host_w.shape[1] == dim and host_acc.shape == (host_w.shape[0], self.S)
         self.lib = _load()
         self.C, self.D, self.V = int(capacity_rows), int(dim), int(host_w.shape[0])
         self.host_w, self.host_acc = host_w, host_acc
         self.h = self.lib.orc_create(self.C, self.D, self.V, _ptr(host_w), _ptr(host_acc),
-                                     lr, eps, lookahead)
+                                     lr, eps, lookahead, OPTIMIZERS.index(optimizer),
+                                     betas[0], betas[1])
         self.n_bags = 0
         self.n_unique = 0
 
@@ -139,7 +152,7 @@ class Oracle:
         slot_id = np.empty(self.C, np.int64)
         stamp = np.empty(self.C, np.int32)
         w = np.empty((self.C, self.D), np.float32) if rows else None
-        a = np.empty((self.C, self.D), np.float32) if rows else None
+        a = np.empty((self.C, self.S), np.float32) if rows else None
         self.lib.orc_get_state(self.h, _ptr(slot_id), _ptr(stamp), _ptr(w), _ptr(a))
         return (slot_id, stamp, w, a) if rows else (slot_id, stamp)
 

@@ -37,6 +37,19 @@
 //     The optimizer is element-wise Adagrad as the benchmark definition fixes
 //     it: acc += g*g ; w -= lr*g/(sqrt(acc)+eps), in fp32, with the summed
 //     gradient accumulated in double and rounded to fp32 once.
+//   * Other optimizers (Experiment settings: the paper trains with Adam, whose
+//     two moment rows travel with each parameter row, so that the training
+//     state is three times the embedding size).  S floats of optimizer state
+//     follow every row through cache and Host:
+//       - Adam (S = 2D, first moments then second moments), the textbook
+//         update with the step number t of the batch in the bias correction:
+//           m = b1*m + (1-b1)*g ; v = b2*v + (1-b2)*g*g
+//           w -= lr * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)
+//         The paper does not say what happens to rows outside the batch; the
+//         reading here is the lazy one: they and their moments stay untouched.
+//       - row-wise Adagrad (S = 1; not in the paper, the cheap variant of the
+//         benchmark's Adagrad): one accumulator per row,
+//           acc += mean_j(g_j^2) ; w_j -= lr*g_j/(sqrt(acc)+eps).
 //   * Ids outside [0, V) (paper silent): all of them collapse to one null
 //     entry with id -1; it owns no row, reads as zeros and drops its gradient.
 //
@@ -60,10 +73,13 @@ struct Oracle {
   int64_t C = 0, V = 0;
   int D = 0;
   float lr = 0, eps = 0;
+  double beta1 = 0, beta2 = 0;   // Adam's decay rates; every constant derived from them is rounded to fp32 once
   int lookahead = 0;
+  int opt = 0;                // 0 Adagrad, 1 Adam, 2 row-wise Adagrad
+  int S = 0;                  // floats of optimizer state per row: D, 2D, 1
   float* host_w = nullptr;    // [V, D] caller-owned, updated in place
-  float* host_acc = nullptr;  // [V, D]
-  std::vector<float> cw, ca;  // [(C + bypass) , D] cache rows and accumulators
+  float* host_acc = nullptr;  // [V, S]
+  std::vector<float> cw, ca;  // [(C + bypass), D] cache rows and [(C + bypass), S] optimizer state
   std::vector<int64_t> slot_id;  // [C] resident id or -1
   std::vector<int32_t> stamp;    // [C] last step that used the slot, 0 = never
   std::unordered_map<int64_t, int32_t> where;  // id -> slot
@@ -79,10 +95,9 @@ struct Oracle {
 };
 
 void ensure_rows(Oracle* o, int64_t rows) {
-  size_t need = (size_t)rows * o->D;
-  if (o->cw.size() < need) {
-    o->cw.resize(need, 0.f);
-    o->ca.resize(need, 0.f);
+  if (o->cw.size() < (size_t)rows * o->D) {
+    o->cw.resize((size_t)rows * o->D, 0.f);
+    o->ca.resize((size_t)rows * o->S, 0.f);
   }
 }
 
@@ -91,9 +106,12 @@ void ensure_rows(Oracle* o, int64_t rows) {
 extern "C" {
 
 void* orc_create(int64_t C, int32_t D, int64_t V, float* host_w, float* host_acc, float lr,
-                 float eps, int32_t lookahead) {
+                 float eps, int32_t lookahead, int32_t optimizer, double beta1, double beta2) {
+  if (optimizer < 0 || optimizer > 2) return nullptr;
   Oracle* o = new Oracle;
   o->C = C; o->D = D; o->V = V; o->lr = lr; o->eps = eps; o->lookahead = lookahead;
+  o->opt = optimizer; o->beta1 = beta1; o->beta2 = beta2;
+  o->S = optimizer == 1 ? 2 * D : optimizer == 2 ? 1 : D;
   o->host_w = host_w; o->host_acc = host_acc;
   o->slot_id.assign((size_t)C, -1);
   o->stamp.assign((size_t)C, 0);
@@ -189,7 +207,7 @@ int orc_prepare(void* p, const int64_t* ids, int64_t n_ids, const int64_t* offse
   o->n_bypass = nb;
   o->st.n_bypass = nb;
   ensure_rows(o, o->C + nb);
-  const int64_t rowbytes = 2 * (int64_t)sizeof(float) * o->D;   // weights + accumulator
+  const int64_t rowbytes = (int64_t)sizeof(float) * (o->D + o->S);   // weights + optimizer state
   o->st.h2d_bytes = M * rowbytes;
   o->st.d2h_bytes = (o->st.n_evict + nb) * rowbytes;
 
@@ -206,18 +224,18 @@ int orc_prepare(void* p, const int64_t* ids, int64_t n_ids, const int64_t* offse
 // 5. Pull victims to Host, then push missed rows into their slots.
 void orc_fetch_misses(void* p) {
   Oracle* o = (Oracle*)p;
-  const int D = o->D;
+  const int D = o->D, S = o->S;
   for (size_t i = 0; i < o->ev_slots.size(); ++i) {
     int64_t id = o->ev_ids[i]; int32_t s = o->ev_slots[i];
     std::memcpy(o->host_w + id * D, &o->cw[(size_t)s * D], sizeof(float) * D);
-    std::memcpy(o->host_acc + id * D, &o->ca[(size_t)s * D], sizeof(float) * D);
+    std::memcpy(o->host_acc + id * S, &o->ca[(size_t)s * S], sizeof(float) * S);
     o->where.erase(id);
     o->slot_id[s] = -1;
   }
   for (int32_t v : o->miss) {
     int64_t id = o->uniq[v]; int32_t s = o->slot_of_vid[v];
     std::memcpy(&o->cw[(size_t)s * D], o->host_w + id * D, sizeof(float) * D);
-    std::memcpy(&o->ca[(size_t)s * D], o->host_acc + id * D, sizeof(float) * D);
+    std::memcpy(&o->ca[(size_t)s * S], o->host_acc + id * S, sizeof(float) * S);
     if (s < o->C) {
       o->where[id] = s;
       o->slot_id[s] = id;
@@ -245,11 +263,16 @@ void orc_lookup(void* p, float* out) {
   }
 }
 
-// 7.-9. segment-sum of grad by virtual id, Adagrad on each unique row, bypass rows to Host.
-// common_grad (optional, [U, D]) receives the summed gradients.
+// 7.-9. segment-sum of grad by virtual id, one optimizer update on each unique row, bypass rows
+// to Host.  common_grad (optional, [U, D]) receives the summed gradients.
 void orc_backward_update(void* p, const float* grad, float* common_grad) {
   Oracle* o = (Oracle*)p;
-  const int D = o->D;
+  const int D = o->D, S = o->S;
+  // Adam's bias corrections for this step's number
+  const float b1 = (float)o->beta1, b2 = (float)o->beta2;
+  const float c1 = (float)(1.0 - o->beta1), c2 = (float)(1.0 - o->beta2);
+  const float bc1 = (float)(1.0 - std::pow(o->beta1, (double)o->t));
+  const float bc2 = (float)(1.0 - std::pow(o->beta2, (double)o->t));
   const int64_t U = (int64_t)o->uniq.size();
   std::vector<double> G((size_t)U * D, 0.0);
   for (int64_t b = 0; b < o->n_bags; ++b) {
@@ -266,12 +289,37 @@ void orc_backward_update(void* p, const float* grad, float* common_grad) {
     int32_t s = o->slot_of_vid[v];
     if (s < 0) continue;
     float* w = &o->cw[(size_t)s * D];
-    float* a = &o->ca[(size_t)s * D];
-    for (int j = 0; j < D; ++j) {
-      float g = (float)G[(size_t)v * D + j];
-      float acc = a[j] + g * g;
-      a[j] = acc;
-      w[j] = w[j] - o->lr * g / (std::sqrt(acc) + o->eps);
+    float* a = &o->ca[(size_t)s * S];
+    if (o->opt == 0) {
+      for (int j = 0; j < D; ++j) {
+        float g = (float)G[(size_t)v * D + j];
+        float acc = a[j] + g * g;
+        a[j] = acc;
+        w[j] = w[j] - o->lr * g / (std::sqrt(acc) + o->eps);
+      }
+    } else if (o->opt == 1) {
+      float* m = a;
+      float* sq = a + D;
+      for (int j = 0; j < D; ++j) {
+        float g = (float)G[(size_t)v * D + j];
+        m[j] = b1 * m[j] + c1 * g;
+        sq[j] = b2 * sq[j] + c2 * (g * g);
+        float mhat = m[j] / bc1;
+        float vhat = sq[j] / bc2;
+        w[j] = w[j] - o->lr * mhat / (std::sqrt(vhat) + o->eps);
+      }
+    } else {
+      double ss = 0.0;
+      for (int j = 0; j < D; ++j) {
+        float g = (float)G[(size_t)v * D + j];
+        ss += (double)g * (double)g;
+      }
+      float acc = a[0] + (float)(ss / D);
+      a[0] = acc;
+      for (int j = 0; j < D; ++j) {
+        float g = (float)G[(size_t)v * D + j];
+        w[j] = w[j] - o->lr * g / (std::sqrt(acc) + o->eps);
+      }
     }
   }
   for (int32_t v : o->miss) {
@@ -279,19 +327,19 @@ void orc_backward_update(void* p, const float* grad, float* common_grad) {
     if (s < o->C) continue;
     int64_t id = o->uniq[v];
     std::memcpy(o->host_w + id * D, &o->cw[(size_t)s * D], sizeof(float) * D);
-    std::memcpy(o->host_acc + id * D, &o->ca[(size_t)s * D], sizeof(float) * D);
+    std::memcpy(o->host_acc + id * S, &o->ca[(size_t)s * S], sizeof(float) * S);
   }
 }
 
 // 10. Every resident row and accumulator to Host (the cache stays resident).
 void orc_flush(void* p) {
   Oracle* o = (Oracle*)p;
-  const int D = o->D;
+  const int D = o->D, S = o->S;
   for (int64_t s = 0; s < o->C; ++s) {
     int64_t id = o->slot_id[s];
     if (id < 0) continue;
     std::memcpy(o->host_w + id * D, &o->cw[(size_t)s * D], sizeof(float) * D);
-    std::memcpy(o->host_acc + id * D, &o->ca[(size_t)s * D], sizeof(float) * D);
+    std::memcpy(o->host_acc + id * S, &o->ca[(size_t)s * S], sizeof(float) * S);
   }
 }
 
@@ -300,9 +348,8 @@ void orc_get_state(void* p, int64_t* slot_id, int32_t* stamp, float* rows, float
   Oracle* o = (Oracle*)p;
   if (slot_id) std::copy(o->slot_id.begin(), o->slot_id.end(), slot_id);
   if (stamp) std::copy(o->stamp.begin(), o->stamp.end(), stamp);
-  size_t n = (size_t)o->C * o->D;
-  if (rows) std::copy(o->cw.begin(), o->cw.begin() + n, rows);
-  if (acc) std::copy(o->ca.begin(), o->ca.begin() + n, acc);
+  if (rows) std::copy(o->cw.begin(), o->cw.begin() + (size_t)o->C * o->D, rows);
+  if (acc) std::copy(o->ca.begin(), o->ca.begin() + (size_t)o->C * o->S, acc);
 }
 
 }  // extern "C"
