@@ -47,6 +47,17 @@ extern "C" {
 
 #define SFC_POLICY_LRU_BATCH 0
 
+/* Optimizers and the floats of state S that travel with every row (cache <-> Host):
+ *   ADAGRAD          S = D    element-wise accumulator
+ *   ADAM             S = 2D   first moments [D], then second moments [D] (Experiment settings: the
+ *                             paper's optimizer; its state makes the training parameters three
+ *                             times the embedding size)
+ *   ROWWISE_ADAGRAD  S = 4    one accumulator per row in the first float; the other three floats
+ *                             pad the state to one 16-byte chunk and are carried unchanged */
+#define SFC_OPT_ADAGRAD 0
+#define SFC_OPT_ADAM 1
+#define SFC_OPT_ROWWISE_ADAGRAD 2
+
 typedef struct sfc_cache sfc_cache; /* opaque */
 
 typedef struct {
@@ -57,13 +68,13 @@ typedef struct {
   int64_t max_bags_per_batch; /* upper bound on n_bags of any step */
   int64_t host_rows;          /* V: rows of the Host table; valid ids are [0, V) */
   float* h_weights;           /* [V, D] Host table, pinned and device-mapped (see sfc_host_alloc) */
-  float* h_acc;               /* [V, D] Adagrad accumulator of every row, same kind of memory */
-  int64_t host_row_stride;    /* floats between consecutive rows of h_weights (and of h_acc); 0 = D.
-                                 With h_acc = h_weights + D and stride 2D each row's weights and
-                                 accumulator are one contiguous 8*D-byte block, the layout the
-                                 host link moves fastest. */
-  float lr;                   /* Adagrad learning rate */
-  float eps;                  /* Adagrad epsilon, added outside the square root */
+  float* h_acc;               /* [V, S] optimizer state of every row, same kind of memory */
+  int64_t host_row_stride;    /* floats between consecutive rows of h_weights; 0 = D.
+                                 With h_acc = h_weights + D and both strides D + S each row's
+                                 weights and state are one contiguous block, the layout the host
+                                 link moves fastest. */
+  float lr;                   /* learning rate */
+  float eps;                  /* epsilon, added outside the square root */
   int32_t lookahead;          /* L = 0, 1 or 2: how many steps may be prepared ahead of the one being
                                  trained.  Rows used by the batch being prepared and by the L
                                  batches before it are protected from eviction.
@@ -79,6 +90,10 @@ typedef struct {
   int32_t max_steps;          /* steps this cache may run (sizes the recency histogram); 0 = 1<<20 */
   void* stream;               /* hipStream_t for prepare / lookup / backward_update */
   void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */
+  int32_t optimizer;          /* SFC_OPT_* */
+  int32_t reserved;           /* 0 */
+  int64_t host_state_stride;  /* floats between consecutive rows of h_acc; 0 = S */
+  double beta1, beta2;        /* Adam's decay rates (ignored otherwise) */
 } sfc_config;
 
 typedef struct {
@@ -88,7 +103,7 @@ typedef struct {
   int64_t n_evict;    /* resident rows written back to Host to make room */
   int64_t n_bypass;   /* misses that found no slot and live in a transient row for this step */
   int64_t n_invalid;  /* positions whose id was outside [0, V) */
-  int64_t h2d_bytes;  /* Host->cache bytes of this step (rows + accumulators) */
+  int64_t h2d_bytes;  /* Host->cache bytes of this step (rows + optimizer state) */
   int64_t d2h_bytes;  /* cache->Host bytes of this step (victims + bypass rows) */
 } sfc_stats;
 
@@ -154,8 +169,13 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad);
 
 /*
  * Step 4 (GPU-Worker / Backward; Algorithm 1 line 14): segment-sum d_grad [n_bags, D] per
- * virtual id as above and apply one Adagrad update per unique row in the cache:
- *     acc += g*g ;  w -= lr * g / (sqrt(acc) + eps)        (fp32, element-wise)
+ * virtual id as above and apply one optimizer update per unique row in the cache (fp32):
+ *   ADAGRAD          acc += g*g ;  w -= lr * g / (sqrt(acc) + eps)             (element-wise)
+ *   ADAM             m = b1*m + (1-b1)*g ;  v = b2*v + (1-b2)*g*g ;
+ *                    w -= lr * (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps)
+ *                    with t = the number of this step's batch (the first sfc_prepare is 1); rows
+ *                    outside the batch and their moments are left as they are
+ *   ROWWISE_ADAGRAD  acc += mean_j(g_j^2) ;  w_j -= lr * g_j / (sqrt(acc) + eps)
  * Bypass rows are written back to the Host table by the same pass.  Ends the step.
  */
 int sfc_backward_update(sfc_cache* c, const float* d_grad);
@@ -170,7 +190,7 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out);
  * Snapshot of the cache for inspection; waits for the streams.  Any pointer may be NULL.
  *  h_slot_id [C] int64  resident id per slot, -1 = free
  *  h_stamp   [C] int32  step number of the last batch that used the slot, 0 = never
- *  h_rows    [C, D]     cached weights        h_acc [C, D] cached accumulators
+ *  h_rows    [C, D]     cached weights        h_acc [C, S] cached optimizer state
  */
 int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h_rows, float* h_acc);
 

@@ -44,6 +44,8 @@ class sfc_config(ctypes.Structure):
         ("host_rows", ctypes.c_int64), ("h_weights", ctypes.c_void_p), ("h_acc", ctypes.c_void_p),
         ("host_row_stride", ctypes.c_int64), ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("lookahead", ctypes.c_int32),
         ("max_steps", ctypes.c_int32), ("stream", ctypes.c_void_p), ("side_stream", ctypes.c_void_p),
+        ("optimizer", ctypes.c_int32), ("reserved", ctypes.c_int32), ("host_state_stride", ctypes.c_int64),
+        ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
     ]
 
 
@@ -160,12 +162,12 @@ def sfc_get_stats(h) -> dict:
     return {k: int(getattr(st, k)) for k, _ in sfc_stats._fields_}
 
 
-def sfc_cache_state(h, capacity_rows, dim, rows=False):
-    """(slot_id[C] int64, stamp[C] int32[, rows[C,D], acc[C,D]]) as numpy arrays."""
+def sfc_cache_state(h, capacity_rows, dim, rows=False, state_dim=None):
+    """(slot_id[C] int64, stamp[C] int32[, rows[C,D], state[C,S]]) as numpy arrays."""
     sid = np.empty(capacity_rows, np.int64)
     stp = np.empty(capacity_rows, np.int32)
     w = np.empty((capacity_rows, dim), np.float32) if rows else None
-    a = np.empty((capacity_rows, dim), np.float32) if rows else None
+    a = np.empty((capacity_rows, state_dim or dim), np.float32) if rows else None
     p = lambda x: None if x is None else x.ctypes.data_as(ctypes.c_void_p)
     _check(_lib.sfc_cache_state(ctypes.c_void_p(h), p(sid), p(stp), p(w), p(a)))
     return (sid, stp, w, a) if rows else (sid, stp)
@@ -190,35 +192,47 @@ def sfc_profile_read(h) -> dict:
 
 # ------------------------------------------------------------------ conveniences
 
-class HostTable:
-    """[V, D] fp32 weights and accumulators in pinned, device-mapped host memory.
+OPTIMIZERS = ("adagrad", "adam", "rowwise_adagrad")      # index = SFC_OPT_*
 
-    interleaved=True (default) stores row i as [weights_i | acc_i] in one allocation, so a row's
+
+def state_floats(optimizer: str, dim: int) -> int:
+    """S: floats of optimizer state that travel with one row."""
+    return {"adagrad": dim, "adam": 2 * dim, "rowwise_adagrad": 4}[optimizer]
+
+
+class HostTable:
+    """[V, D] fp32 weights and [V, S] optimizer state in pinned, device-mapped host memory
+    (S = state_floats(optimizer, D)).
+
+    interleaved=True (default) stores row i as [weights_i | state_i] in one allocation, so a row's
     weights and optimizer state are one contiguous block for the host link; `w` and `acc` are then
     strided numpy views.  interleaved=False uses two separate contiguous arrays.
     """
 
-    def __init__(self, rows: int, dim: int, interleaved: bool = True):
+    def __init__(self, rows: int, dim: int, interleaved: bool = True, optimizer: str = "adagrad"):
         self.rows, self.dim, self.interleaved = int(rows), int(dim), bool(interleaved)
-        n = self.rows * self.dim
+        self.optimizer = optimizer
+        S = self.state_dim = state_floats(optimizer, self.dim)
         if self.interleaved:
-            self._base = sfc_host_alloc(2 * n * 4)
-            self._pw, self._pa, self.stride = self._base, self._base + 4 * self.dim, 2 * self.dim
-            both = np.ctypeslib.as_array((ctypes.c_float * (2 * n)).from_address(self._base)
-                                         ).reshape(self.rows, 2, self.dim)
-            self.w, self.acc = both[:, 0, :], both[:, 1, :]
+            tot = self.rows * (self.dim + S)
+            self._base = sfc_host_alloc(tot * 4)
+            self._pw, self._pa = self._base, self._base + 4 * self.dim
+            self.stride = self.state_stride = self.dim + S
+            both = np.ctypeslib.as_array((ctypes.c_float * tot).from_address(self._base)
+                                         ).reshape(self.rows, self.dim + S)
+            self.w, self.acc = both[:, :self.dim], both[:, self.dim:]
             self._bases = [self._base]
         else:
-            self._pw = sfc_host_alloc(n * 4)
+            self._pw = sfc_host_alloc(self.rows * self.dim * 4)
             try:
-                self._pa = sfc_host_alloc(n * 4)
+                self._pa = sfc_host_alloc(self.rows * S * 4)
             except SfcError:
                 sfc_host_free(self._pw)
                 raise
-            self.stride = self.dim
-            mk = lambda p: np.ctypeslib.as_array((ctypes.c_float * n).from_address(p)
-                                                 ).reshape(self.rows, self.dim)
-            self.w, self.acc = mk(self._pw), mk(self._pa)
+            self.stride, self.state_stride = self.dim, S
+            mk = lambda p, k: np.ctypeslib.as_array((ctypes.c_float * (self.rows * k)).from_address(p)
+                                                    ).reshape(self.rows, k)
+            self.w, self.acc = mk(self._pw, self.dim), mk(self._pa, S)
             self._bases = [self._pw, self._pa]
         self.w_t, self.acc_t = torch.from_numpy(self.w), torch.from_numpy(self.acc)
 
@@ -259,7 +273,8 @@ class Cache:
     """
 
     def __init__(self, table: HostTable, capacity_rows: int, max_ids: int, max_bags: Optional[int] = None,
-                 lr=0.01, eps=1e-8, lookahead=0, max_steps=0, device="cuda:0", side_stream=True):
+                 lr=0.01, eps=1e-8, lookahead=0, max_steps=0, device="cuda:0", side_stream=True,
+                 betas=(0.9, 0.999)):
         self.table, self.C, self.D = table, int(capacity_rows), table.dim
         self.device = torch.device(device)
         self.max_ids = int(max_ids)
@@ -270,7 +285,9 @@ class Cache:
             self.side = torch.cuda.Stream() if (side_stream or lookahead) else self.stream
             cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH, self.max_ids, self.max_bags,
                              table.rows, table._pw, table._pa, table.stride, lr, eps, lookahead,
-                             max_steps, self.stream.cuda_stream, self.side.cuda_stream)
+                             max_steps, self.stream.cuda_stream, self.side.cuda_stream,
+                             OPTIMIZERS.index(table.optimizer), 0, table.state_stride,
+                             betas[0], betas[1])
             self.h = sfc_cache_create(cfg)
             self.bufs = [StepBuffers(max(self.max_ids, 1), self.device) for _ in range(self.lookahead + 1)]
         self._next = 0
@@ -341,7 +358,7 @@ class Cache:
         return sfc_get_stats(self.h)
 
     def state(self, rows=False):
-        return sfc_cache_state(self.h, self.C, self.D, rows)
+        return sfc_cache_state(self.h, self.C, self.D, rows, self.table.state_dim)
 
     def step(self, ids, grad, offsets=None, out=None):
         self.prepare(ids, offsets)

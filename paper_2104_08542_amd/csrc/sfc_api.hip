@@ -12,6 +12,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -87,7 +88,8 @@ struct sfc_cache {
   bool own_prep = false;                        // prep was created here (lookahead 2)
   hipEvent_t ev_tmp = nullptr;                  // cross-stream ordering inside one call
   // device memory
-  float *cw = nullptr, *ca = nullptr;           // [(C + nctx * max_ids), D]
+  float *cw = nullptr, *ca = nullptr;           // rows [(C + nctx * max_ids), D] and their optimizer state [.., S]
+  int S = 0, s4 = 0;                            // floats / 16-byte chunks of optimizer state per row
   int64_t* slot_id = nullptr;                   // [C]
   int* stamp = nullptr;                         // [C]
   IdxEntry* index = nullptr; uint32_t hi = 0;   // cache index
@@ -204,7 +206,7 @@ int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
   if (timed && (rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
   hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, kSwapBlocks)), dim3(256), 0, s,
                      x->d_miss, x->d_unique, x->d_slot, x->victim_id, (float4*)c->cw,
-                     (float4*)c->ca, c->host, c->d4, (int)c->C, x->boff, x->ctr, x->older1,
+                     (float4*)c->ca, c->host, c->d4, c->s4, (int)c->C, x->boff, x->ctr, x->older1,
                      x->older2, x->chain, main_variant);
   HIPCHK(hipGetLastError());
   if (timed && (rc = prof_end(c, P_FETCH, s, &ep))) return rc;
@@ -313,11 +315,21 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if (cfg->host_row_stride && (cfg->host_row_stride < cfg->dim || cfg->host_row_stride % 4))
     return fail(SFC_EINVAL, "host_row_stride must be 0 or a multiple of 4 that is >= dim");
   if (cfg->max_steps < 0) return fail(SFC_EINVAL, "max_steps must be >= 0");
+  if (cfg->optimizer < SFC_OPT_ADAGRAD || cfg->optimizer > SFC_OPT_ROWWISE_ADAGRAD)
+    return fail(SFC_EINVAL, "unknown optimizer");
+  const int S = cfg->optimizer == SFC_OPT_ADAM ? 2 * cfg->dim
+              : cfg->optimizer == SFC_OPT_ROWWISE_ADAGRAD ? 4 : cfg->dim;
+  if (cfg->host_state_stride && (cfg->host_state_stride < S || cfg->host_state_stride % 4))
+    return fail(SFC_EINVAL, "host_state_stride must be 0 or a multiple of 4 that is >= the state size");
+  if (cfg->optimizer == SFC_OPT_ADAM &&
+      !(cfg->beta1 >= 0.0 && cfg->beta1 < 1.0 && cfg->beta2 >= 0.0 && cfg->beta2 < 1.0))
+    return fail(SFC_EINVAL, "Adam needs 0 <= beta1, beta2 < 1");
 
   sfc_cache* c = new (std::nothrow) sfc_cache;
   if (!c) return fail(SFC_ENOMEM, "host allocation failed");
   c->cfg = *cfg;
   c->C = cfg->capacity_rows; c->V = cfg->host_rows; c->D = cfg->dim; c->d4 = cfg->dim / 4;
+  c->S = S; c->s4 = S / 4;
   c->max_ids = cfg->max_ids_per_batch; c->max_bags = cfg->max_bags_per_batch;
   c->nctx = (int)nctx;
   c->st = (hipStream_t)cfg->stream;
@@ -338,6 +350,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   }
   c->host.a = (float4*)dp;
   c->host.hs4 = (cfg->host_row_stride ? cfg->host_row_stride : cfg->dim) / 4;
+  c->host.has4 = (cfg->host_state_stride ? cfg->host_state_stride : S) / 4;
   // lookahead 0: prepare on the main stream; 1: on the side stream, ahead of that step's copies;
   // 2: on a stream of its own, so that the copies of step t+1 overlap the prepare of step t+2
   c->prep = cfg->lookahead == 0 ? c->st : c->side;
@@ -353,7 +366,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     const int64_t rows = c->C + nctx * c->max_ids;
     const int64_t hu = 2 * c->max_ids;
     if ((rc = dalloc(c, &c->cw, rows * c->D))) goto bad;
-    if ((rc = dalloc(c, &c->ca, rows * c->D))) goto bad;
+    if ((rc = dalloc(c, &c->ca, rows * c->S))) goto bad;
     if ((rc = dalloc(c, &c->slot_id, c->C))) goto bad;
     if ((rc = dalloc(c, &c->stamp, c->C))) goto bad;
     if ((rc = dalloc(c, &c->index, (int64_t)c->hi))) goto bad;
@@ -590,10 +603,28 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
   if ((rc = seg_launch(c, x, d_grad, c->gsum))) return rc;
   if ((rc = prof_begin(c, P_ADAGRAD, s, &e1))) return rc;
-  hipLaunchKernelGGL(k_adagrad_rows, dim3(grid_for(x->n_ids * c->d4, 1024, kGridCap)), dim3(256), 0,
-                     s, (const float4*)c->gsum, x->d_slot, x->d_unique, (float4*)c->cw,
-                     (float4*)c->ca, c->host, (int)c->C, x->boff, c->cfg.lr, c->cfg.eps, c->d4,
-                     x->ctr);
+  const dim3 ug(grid_for(x->n_ids * c->d4, 1024, kGridCap));
+  if (c->cfg.optimizer == SFC_OPT_ADAGRAD) {
+    hipLaunchKernelGGL(k_adagrad_rows, ug, dim3(256), 0, s, (const float4*)c->gsum, x->d_slot,
+                       x->d_unique, (float4*)c->cw, (float4*)c->ca, c->host, (int)c->C, x->boff,
+                       c->cfg.lr, c->cfg.eps, c->d4, x->ctr);
+  } else if (c->cfg.optimizer == SFC_OPT_ADAM) {
+    // every constant derived from the decay rates is computed in double and rounded to fp32 once
+    AdamArgs k;
+    k.b1 = (float)c->cfg.beta1; k.c1 = (float)(1.0 - c->cfg.beta1);
+    k.b2 = (float)c->cfg.beta2; k.c2 = (float)(1.0 - c->cfg.beta2);
+    k.bc1 = (float)(1.0 - pow(c->cfg.beta1, (double)x->t));
+    k.bc2 = (float)(1.0 - pow(c->cfg.beta2, (double)x->t));
+    k.lr = c->cfg.lr; k.eps = c->cfg.eps;
+    hipLaunchKernelGGL(k_adam_rows, ug, dim3(256), 0, s, (const float4*)c->gsum, x->d_slot,
+                       x->d_unique, (float4*)c->cw, (float4*)c->ca, c->host, (int)c->C, x->boff, k,
+                       c->d4, x->ctr);
+  } else {
+    const int pow2 = (c->d4 & (c->d4 - 1)) == 0;
+    hipLaunchKernelGGL(k_rowwise_adagrad_rows, ug, dim3(256), 0, s, (const float4*)c->gsum,
+                       x->d_slot, x->d_unique, (float4*)c->cw, (float4*)c->ca, c->host, (int)c->C,
+                       x->boff, c->cfg.lr, c->cfg.eps, c->d4, pow2, x->ctr);
+  }
   if ((rc = prof_end(c, P_ADAGRAD, s, &e1))) return rc;
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_BACKWARD, s, &ep))) return rc;
@@ -621,7 +652,7 @@ int sfc_flush(sfc_cache* c) {
   if (rc) return rc;
   if (c->last_prepared < 0) return SFC_OK;
   hipLaunchKernelGGL(k_flush, dim3(grid_for(c->C * 2 * c->d4, 256, kGridCap)), dim3(256), 0, c->st,
-                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, c->host, c->d4,
+                     c->slot_id, (const float4*)c->cw, (const float4*)c->ca, c->host, c->d4, c->s4,
                      c->ctx[c->last_prepared].ctr);
   HIPCHK(hipGetLastError());
   return sync_all(c);
@@ -636,7 +667,7 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out) {
   Ctr h;
   HIPCHK(hipMemcpy(&h, c->ctx[c->last_prepared].ctr, sizeof h, hipMemcpyDeviceToHost));
   if (h.err) return fail(SFC_EHIP, "cache index probe ran off its bound (index corrupt)");
-  const int64_t rowbytes = 2 * (int64_t)sizeof(float) * c->D;
+  const int64_t rowbytes = (int64_t)sizeof(float) * (c->D + c->S);
   h_out->n_unique = h.U; h_out->n_hit = h.n_hit; h_out->n_miss = h.M; h_out->n_evict = h.K;
   h_out->n_bypass = h.n_bypass; h_out->n_invalid = h.n_invalid;
   h_out->h2d_bytes = h.M * rowbytes;
@@ -653,7 +684,7 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
   if (h_slot_id) HIPCHK(hipMemcpy(h_slot_id, c->slot_id, (size_t)c->C * sizeof(int64_t), hipMemcpyDeviceToHost));
   if (h_stamp) HIPCHK(hipMemcpy(h_stamp, c->stamp, (size_t)c->C * sizeof(int32_t), hipMemcpyDeviceToHost));
   if (h_rows) HIPCHK(hipMemcpy(h_rows, c->cw, rows, hipMemcpyDeviceToHost));
-  if (h_acc) HIPCHK(hipMemcpy(h_acc, c->ca, rows, hipMemcpyDeviceToHost));
+  if (h_acc) HIPCHK(hipMemcpy(h_acc, c->ca, (size_t)c->C * c->S * sizeof(float), hipMemcpyDeviceToHost));
   return SFC_OK;
 }
 

@@ -41,8 +41,9 @@ __device__ __forceinline__ void st_stream(float4* p, float4 v) {
 // ---------------------------------------------------------------------------------------------
 struct HostRows {
   float4* w;      // device view of h_weights
-  float4* a;      // device view of h_acc
-  int64_t hs4;    // row stride in float4
+  float4* a;      // device view of h_acc (the optimizer state, s4 chunks per row)
+  int64_t hs4;    // row stride of w in float4
+  int64_t has4;   // row stride of a in float4
 };
 
 __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_vids,
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
                                                     const int* __restrict__ slot,
                                                     const int64_t* __restrict__ victim_id,
                                                     float4* __restrict__ cw, float4* __restrict__ ca,
-                                                    HostRows h, int d4, int C, int boff,
+                                                    HostRows h, int d4, int s4, int C, int boff,
                                                     Ctr* ctr, const Ctr* older1,
                                                     const Ctr* older2, int chain,
                                                     int main_variant) {
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
   if (blockIdx.x == 0 && threadIdx.x == 0) ctr->fetch_on_main = on_main;   // same value from both launches
   if (on_main != (main_variant != 0)) return;
   const int K = ctr->K;
-  const int w2 = 2 * d4;
+  const int w2 = d4 + s4;                   // chunks of a row and of its optimizer state
   const int64_t total = (int64_t)ctr->M * w2;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int k = (int)(i / w2);
@@ -68,12 +69,14 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
     if (acc) c -= d4;
     float4* hb = acc ? h.a : h.w;
     float4* cb = acc ? ca : cw;
+    const int64_t hst = acc ? h.has4 : h.hs4;
+    const int cst = acc ? s4 : d4;
     const int v = miss_vids[k];
     int row = slot[v];
     if (row >= C) row += boff;              // bypass rows of this step's own region
-    const int64_t src = unique_ids[v] * h.hs4 + c, dst = (int64_t)row * d4 + c;
+    const int64_t src = unique_ids[v] * hst + c, dst = (int64_t)row * cst + c;
     const float4 nv = hb[src];
-    if (k < K) hb[victim_id[k] * h.hs4 + c] = cb[dst];
+    if (k < K) hb[victim_id[k] * hst + c] = cb[dst];
     cb[dst] = nv;
   }
 }
@@ -81,8 +84,8 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
 __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_id,
                                                 const float4* __restrict__ cw,
                                                 const float4* __restrict__ ca, HostRows h, int d4,
-                                                const Ctr* ctr) {
-  const int w2 = 2 * d4;
+                                                int s4, const Ctr* ctr) {
+  const int w2 = d4 + s4;
   const int64_t total = (int64_t)ctr->f * w2;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int64_t s = i / w2;
@@ -91,7 +94,8 @@ __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_
     if (acc) c -= d4;
     const int64_t id = slot_id[s];
     if (id < 0) continue;
-    (acc ? h.a : h.w)[id * h.hs4 + c] = (acc ? ca : cw)[s * d4 + c];
+    if (acc) h.a[id * h.has4 + c] = ca[s * s4 + c];
+    else h.w[id * h.hs4 + c] = cw[s * d4 + c];
   }
 }
 
@@ -481,9 +485,150 @@ __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__
         if (sl[u] >= C) {
           const int64_t i = i0 + u * stride;
           const int64_t hr = unique_ids[(int)(i / d4)] * h.hs4 + (i % d4);
-          h.w[hr] = w[u]; h.a[hr] = a[u];
+          h.w[hr] = w[u];
+          h.a[unique_ids[(int)(i / d4)] * h.has4 + (i % d4)] = a[u];
         }
       }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Adam (Experiment settings: the paper's optimizer), lazily on the rows of the batch, with the
+// batch number t in the bias corrections bc = 1 - beta^t (computed by the host in double):
+//   m = b1*m + c1*g ; v = b2*v + c2*g*g ; w -= lr * (m/bc1) / (sqrt(v/bc2) + eps)
+// The state of a row is 2*d4 chunks: first moments, then second moments.
+// ---------------------------------------------------------------------------------------------
+struct AdamArgs {
+  float b1, c1, b2, c2;   // beta1, 1-beta1, beta2, 1-beta2
+  float bc1, bc2, lr, eps;
+};
+__device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, const AdamArgs& k) {
+  m = k.b1 * m + k.c1 * g;
+  v = k.b2 * v + k.c2 * (g * g);
+  const float mhat = m / k.bc1, vhat = v / k.bc2;
+  w = w - k.lr * mhat / (sqrtf(vhat) + k.eps);
+}
+
+__global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ common,
+                                                    const int* __restrict__ slot,
+                                                    const int64_t* __restrict__ unique_ids,
+                                                    float4* __restrict__ cw,
+                                                    float4* __restrict__ cs, HostRows h, int C,
+                                                    int boff, AdamArgs k, int d4,
+                                                    const Ctr* ctr) {
+  const int64_t total = (int64_t)ctr->U * d4;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 2 * stride) {
+    float4 g[2], w[2], m[2], v[2];
+    int64_t rw[2], rs[2];
+    int sl[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int64_t i = i0 + u * stride;
+      rw[u] = -1;
+      if (i < total) {
+        sl[u] = slot[(int)(i / d4)];
+        if (sl[u] >= 0) {
+          const int64_t row = sl[u] >= C ? sl[u] + boff : sl[u];
+          rw[u] = row * d4 + (i % d4);
+          rs[u] = row * 2 * d4 + (i % d4);
+          g[u] = common[i]; w[u] = cw[rw[u]]; m[u] = cs[rs[u]]; v[u] = cs[rs[u] + d4];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (rw[u] >= 0) {
+        adam1(w[u].x, m[u].x, v[u].x, g[u].x, k);
+        adam1(w[u].y, m[u].y, v[u].y, g[u].y, k);
+        adam1(w[u].z, m[u].z, v[u].z, g[u].z, k);
+        adam1(w[u].w, m[u].w, v[u].w, g[u].w, k);
+        cw[rw[u]] = w[u]; cs[rs[u]] = m[u]; cs[rs[u] + d4] = v[u];
+        if (sl[u] >= C) {
+          const int64_t i = i0 + u * stride;
+          const int64_t id = unique_ids[(int)(i / d4)];
+          const int c = (int)(i % d4);
+          h.w[id * h.hs4 + c] = w[u];
+          h.a[id * h.has4 + c] = m[u];
+          h.a[id * h.has4 + d4 + c] = v[u];
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row-wise Adagrad: one accumulator per row (first float of a one-chunk state),
+//   acc += mean_j(g_j^2) ; w_j -= lr * g_j / (sqrt(acc) + eps).
+// One thread per 16-byte chunk of a row as above; the d4 lanes of a row add their squares with
+// shuffles when d4 is a power of two (a row then never straddles a wavefront).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_rowwise_adagrad_rows(const float4* __restrict__ common,
+                                                               const int* __restrict__ slot,
+                                                               const int64_t* __restrict__ unique_ids,
+                                                               float4* __restrict__ cw,
+                                                               float4* __restrict__ cs, HostRows h,
+                                                               int C, int boff, float lr, float eps,
+                                                               int d4, int pow2, const Ctr* ctr) {
+  const int64_t total = (int64_t)ctr->U * d4;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const float inv_d = 1.0f / (float)(4 * d4);
+  if (!pow2) {
+    // any other width: one thread per row (the lanes of a row could straddle two wavefronts, and
+    // the accumulator must be read by all of them before one writes it)
+    for (int64_t vrow = (int64_t)blockIdx.x * 256 + threadIdx.x; vrow < ctr->U; vrow += stride) {
+      const int sl = slot[vrow];
+      if (sl < 0) continue;
+      float ss = 0.f;
+      for (int j = 0; j < d4; ++j) {
+        const float4 q = common[vrow * d4 + j];
+        ss += q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
+      }
+      const int64_t row = sl >= C ? sl + boff : sl;
+      float4 st = cs[row];
+      st.x = st.x + ss * inv_d;
+      const float den = sqrtf(st.x) + eps;
+      const int64_t id = unique_ids[vrow];
+      for (int j = 0; j < d4; ++j) {
+        const float4 g = common[vrow * d4 + j];
+        float4 w = cw[row * d4 + j];
+        w.x = w.x - lr * g.x / den; w.y = w.y - lr * g.y / den;
+        w.z = w.z - lr * g.z / den; w.w = w.w - lr * g.w / den;
+        cw[row * d4 + j] = w;
+        if (sl >= C) h.w[id * h.hs4 + j] = w;
+      }
+      cs[row] = st;
+      if (sl >= C) h.a[id * h.has4] = st;
+    }
+    return;
+  }
+  // every lane of a wavefront runs the same number of iterations: the shuffles stay convergent
+  const int64_t rounds = (total + stride - 1) / stride;
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (int64_t it = 0; it < rounds; ++it, i += stride) {
+    const bool live = i < total;
+    const int vrow = live ? (int)(i / d4) : 0;
+    const int c = live ? (int)(i % d4) : 0;
+    const int sl = live ? slot[vrow] : -1;
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) g = common[i];
+    float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
+    for (int d = 1; d < d4; d <<= 1) ss += __shfl_xor(ss, d, kWave);
+    if (sl < 0) continue;
+    const int64_t row = sl >= C ? sl + boff : sl;
+    float4 st = cs[row];
+    float4 w = cw[row * d4 + c];
+    const float acc = st.x + ss * inv_d;
+    const float den = sqrtf(acc) + eps;
+    w.x = w.x - lr * g.x / den; w.y = w.y - lr * g.y / den;
+    w.z = w.z - lr * g.z / den; w.w = w.w - lr * g.w / den;
+    cw[row * d4 + c] = w;
+    st.x = acc;
+    if (c == 0) cs[row] = st;
+    if (sl >= C) {
+      const int64_t id = unique_ids[vrow];
+      h.w[id * h.hs4 + c] = w;
+      if (c == 0) h.a[id * h.has4] = st;
+    }
   }
 }
 
