@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--lookahead", type=int, default=2, choices=[0, 1, 2],
                     help="L > 0: prepare/fetch of step t+L overlap lookup/update of step t; with 2 "
                          "the copies of step t+1 also overlap the prepare of step t+2 (default)")
+    ap.add_argument("--optimizer", default="adagrad", choices=["adagrad", "adam", "rowwise_adagrad"],
+                    help="adagrad is the benchmark's; adam is the paper's (state 2x the row)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -68,13 +70,14 @@ def main():
     R = 4 * D
 
     t0 = time.time()
-    table = sfc.HostTable(V, D)
+    S = sfc.state_floats(args.optimizer, D)
+    table = sfc.HostTable(V, D, optimizer=args.optimizer)
     chunk = max(1, (1 << 26) // D)
     for r0 in range(0, V, chunk):
         r1 = min(V, r0 + chunk)
         table.w_t[r0:r1].copy_(si.table_rows(w.seed, r0, r1, D, dev))
-    table.acc_t.fill_(w.init_acc)
-    log("host table [%d, %d] x2 pinned and filled in %.1fs" % (V, D, time.time() - t0))
+    table.acc_t.fill_(0.0 if args.optimizer == "adam" else w.init_acc)
+    log("host table [%d, %d + %d] pinned and filled in %.1fs" % (V, D, S, time.time() - t0))
 
     cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lr=w.lr, eps=w.eps, lookahead=args.lookahead,
                       device="cuda:0")
@@ -181,11 +184,12 @@ def main():
     # algorithmic bytes per launch (rows counted once per unique id)
     extra = 0 if w.one_hot else 8 * bags
     b_lookup = 4 * N + 4 * U + U * R + bags * R + extra
-    b_update = bags * R + 4 * N + 4 * U + 4 * U * R + extra          # sfc_backward_update as a whole
+    RS = R + 4 * S                                                    # a row and its optimizer state
+    b_update = bags * R + 4 * N + 4 * U + 2 * U * RS + extra         # sfc_backward_update as a whole
     kernels = {
         "k_lookup": (b_lookup, ms["lookup"]),
         "k_seg_stream": (bags * R + 4 * N + U * R + extra, ms["k_seg_stream"]),   # grad + grouping in, common out
-        "k_adagrad_rows": (4 * U + U * R + 4 * U * R, ms["k_adagrad_rows"]),
+        "k_%s_rows" % args.optimizer: (4 * U + U * R + 2 * U * RS, ms["k_adagrad_rows"]),
     }
     dom = max(kernels, key=lambda k: kernels[k][1])
     ach = kernels[dom][0] / (kernels[dom][1] * 1e-3) / 1e9
@@ -203,10 +207,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {
-            "workload": "%s: batch %d x %d fields%s, ids %s over %.0e rows, dim %d fp32, cache %d rows LRU, Adagrad"
+            "workload": "%s: batch %d x %d fields%s, ids %s over %.0e rows, dim %d fp32, cache %d rows LRU, %s"
                         % (w.name, w.batch, w.fields,
                            "" if w.one_hot else " (bags of %d-%d ids)" % (w.bag_lo, w.bag_hi),
-                           "uniform" if w.zipf_s is None else "Zipf(s=%.2f)" % w.zipf_s, V, D, C),
+                           "uniform" if w.zipf_s is None else "Zipf(s=%.2f)" % w.zipf_s, V, D, C,
+                           {"adagrad": "Adagrad", "adam": "Adam", "rowwise_adagrad": "row-wise Adagrad"}[args.optimizer]),
             "ids_per_step": N, "unique_per_step": U,
             "hit_rate": avg["n_hit"] / max(1.0, avg["n_hit"] + avg["n_miss"]),
             "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
@@ -223,7 +228,8 @@ def main():
                                "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
                                "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "call_ms": {k: ms[k] for k in ("prepare", "fetch_misses", "lookup", "backward_update")},
-        "kernel_ms": {k: ms[k] for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows")},
+        "kernel_ms": {"k_seg_stream": ms["k_seg_stream"], "k_seg_finish": ms["k_seg_finish"],
+                      "k_%s_rows" % args.optimizer: ms["k_adagrad_rows"]},
         "call_ms_overlapped": overlapped_ms,
         "host_link": {"h2d_bytes_per_step": avg["h2d_bytes"], "d2h_bytes_per_step": avg["d2h_bytes"],
                       "GB/s": ((avg["h2d_bytes"] + avg["d2h_bytes"]) / (link_ms * 1e-3) / 1e9
@@ -234,15 +240,16 @@ def main():
         # The oracle as it stands, single-threaded, on the same workload: first steps of the same
         # seeded batch sequence from a cold oracle cache, on a dense copy of the host table taken
         # after the GPU run has been flushed into it (values differ from step 0, the work does not).
-        from oracle import Oracle
+        from oracle import Oracle, state_floats as oracle_state_floats
         for _ in range(args.lookahead):       # retire the steps that are still in flight
             cache.lookup(out)
             cache.backward_update(grads[0])
         cache.flush()
         t1 = time.time()
-        ow, oa = np.ascontiguousarray(table.w), np.ascontiguousarray(table.acc)
+        ow = np.ascontiguousarray(table.w)
+        oa = np.ascontiguousarray(table.acc[:, :oracle_state_floats(args.optimizer, D)])
         log("dense copy of the host table for the oracle in %.1fs" % (time.time() - t1))
-        orc = Oracle(C, D, ow, oa, lr=w.lr, eps=w.eps)
+        orc = Oracle(C, D, ow, oa, lr=w.lr, eps=w.eps, optimizer=args.optimizer)
         done_ids, steps_done, cpu_t = 0, 0, 0.0
         while cpu_t < args.cpu_seconds and steps_done < 50:
             ids, off = w.batch_ids(steps_done, dev)
