@@ -43,7 +43,7 @@ def _load():
         lib = ctypes.CDLL(build())
         vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
         lib.orc_create.restype = vp
-        lib.orc_create.argtypes = [i64, i32, i64, vp, vp, f32, f32, i32, i32, ctypes.c_double, ctypes.c_double]
+        lib.orc_create.argtypes = [i64, i32, i64, vp, vp, f32, f32, i32, i32, ctypes.c_double, ctypes.c_double, i32]
         lib.orc_destroy.argtypes = [vp]
         lib.orc_prepare.restype = ctypes.c_int
         lib.orc_prepare.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, ctypes.POINTER(_Stats)]
@@ -61,6 +61,7 @@ def _ptr(a):
 
 
 OPTIMIZERS = ("adagrad", "adam", "rowwise_adagrad")
+STRATEGIES = ("cache", "prefetch")     # capacity 0 with "cache" is the ablation's Host strategy
 
 
 def state_floats(optimizer, dim):
@@ -83,7 +84,7 @@ class Oracle:
     """One cache + host table pair, stepped with prepare/fetch/lookup/backward_update."""
 
     def __init__(self, capacity_rows, dim, host_w, host_acc, lr=0.01, eps=1e-8, lookahead=0,
-                 optimizer="adagrad", betas=(0.9, 0.999)):
+                 optimizer="adagrad", betas=(0.9, 0.999), strategy="cache"):
         """host_acc is the optimizer state [V, S]: S = dim (adagrad: accumulators), 2*dim (adam:
         first moments then second moments) or 1 (rowwise_adagrad)."""
         self.S = state_floats(optimizer, dim)
@@ -95,7 +96,8 @@ class Oracle:
         self.host_w, self.host_acc = host_w, host_acc
         self.h = self.lib.orc_create(self.C, self.D, self.V, _ptr(host_w), _ptr(host_acc),
                                      lr, eps, lookahead, OPTIMIZERS.index(optimizer),
-                                     betas[0], betas[1])
+                                     betas[0], betas[1], STRATEGIES.index(strategy))
+        assert self.h, "oracle: bad optimizer / strategy (prefetch needs capacity 0)"
         self.n_bags = 0
         self.n_unique = 0
 

@@ -50,6 +50,15 @@
 //       - row-wise Adagrad (S = 1; not in the paper, the cheap variant of the
 //         benchmark's Adagrad): one accumulator per row,
 //           acc += mean_j(g_j^2) ; w_j -= lr*g_j/(sqrt(acc)+eps).
+//   * The "Prefetch" strategy of the MixCache ablation (RQ3): no cache; the
+//     rows of the next batch are copied from Host before the current batch is
+//     trained, with no guarantee of consistency.  Made definite here as "stale
+//     by exactly one step": the copy for batch t sees the Host table with the
+//     write-backs of batches <= t-2; the rows trained by batch t-1 reach Host
+//     only after that copy.  A row in two consecutive batches is therefore
+//     trained from its old value and the earlier update is overwritten.  (The
+//     "Host" strategy is capacity 0 without this: every copy sees every
+//     earlier write-back.)
 //   * Ids outside [0, V) (paper silent): all of them collapse to one null
 //     entry with id -1; it owns no row, reads as zeros and drops its gradient.
 //
@@ -75,6 +84,9 @@ struct Oracle {
   float lr = 0, eps = 0;
   double beta1 = 0, beta2 = 0;   // Adam's decay rates; every constant derived from them is rounded to fp32 once
   int lookahead = 0;
+  int strategy = 0;           // 0 MixCache (capacity 0 = Host strategy), 1 Prefetch (stale by one step)
+  std::vector<int64_t> pend_ids;       // Prefetch: rows trained by the last batch, not yet in Host
+  std::vector<float> pend_w, pend_a;
   int opt = 0;                // 0 Adagrad, 1 Adam, 2 row-wise Adagrad
   int S = 0;                  // floats of optimizer state per row: D, 2D, 1
   float* host_w = nullptr;    // [V, D] caller-owned, updated in place
@@ -94,6 +106,17 @@ struct Oracle {
   Stats st{};
 };
 
+// Prefetch: the rows of the previous batch reach Host.
+void apply_pending(Oracle* o) {
+  const int D = o->D, S = o->S;
+  for (size_t i = 0; i < o->pend_ids.size(); ++i) {
+    int64_t id = o->pend_ids[i];
+    std::memcpy(o->host_w + id * D, &o->pend_w[i * D], sizeof(float) * D);
+    std::memcpy(o->host_acc + id * S, &o->pend_a[i * S], sizeof(float) * S);
+  }
+  o->pend_ids.clear(); o->pend_w.clear(); o->pend_a.clear();
+}
+
 void ensure_rows(Oracle* o, int64_t rows) {
   if (o->cw.size() < (size_t)rows * o->D) {
     o->cw.resize((size_t)rows * o->D, 0.f);
@@ -106,11 +129,13 @@ void ensure_rows(Oracle* o, int64_t rows) {
 extern "C" {
 
 void* orc_create(int64_t C, int32_t D, int64_t V, float* host_w, float* host_acc, float lr,
-                 float eps, int32_t lookahead, int32_t optimizer, double beta1, double beta2) {
-  if (optimizer < 0 || optimizer > 2) return nullptr;
+                 float eps, int32_t lookahead, int32_t optimizer, double beta1, double beta2,
+                 int32_t strategy) {
+  if (optimizer < 0 || optimizer > 2 || strategy < 0 || strategy > 1) return nullptr;
+  if (strategy == 1 && C != 0) return nullptr;       // Prefetch keeps nothing resident
   Oracle* o = new Oracle;
   o->C = C; o->D = D; o->V = V; o->lr = lr; o->eps = eps; o->lookahead = lookahead;
-  o->opt = optimizer; o->beta1 = beta1; o->beta2 = beta2;
+  o->opt = optimizer; o->beta1 = beta1; o->beta2 = beta2; o->strategy = strategy;
   o->S = optimizer == 1 ? 2 * D : optimizer == 2 ? 1 : D;
   o->host_w = host_w; o->host_acc = host_acc;
   o->slot_id.assign((size_t)C, -1);
@@ -242,6 +267,7 @@ void orc_fetch_misses(void* p) {
       o->stamp[s] = (int32_t)o->t;
     }
   }
+  if (o->strategy == 1) apply_pending(o);    // only now do the previous batch's rows reach Host
 }
 
 // 6. out[b,:] = sum over the bag's positions of the cached row of that position's id.
@@ -326,6 +352,12 @@ void orc_backward_update(void* p, const float* grad, float* common_grad) {
     int32_t s = o->slot_of_vid[v];
     if (s < o->C) continue;
     int64_t id = o->uniq[v];
+    if (o->strategy == 1) {
+      o->pend_ids.push_back(id);
+      o->pend_w.insert(o->pend_w.end(), &o->cw[(size_t)s * D], &o->cw[(size_t)s * D] + D);
+      o->pend_a.insert(o->pend_a.end(), &o->ca[(size_t)s * S], &o->ca[(size_t)s * S] + S);
+      continue;
+    }
     std::memcpy(o->host_w + id * D, &o->cw[(size_t)s * D], sizeof(float) * D);
     std::memcpy(o->host_acc + id * S, &o->ca[(size_t)s * S], sizeof(float) * S);
   }
@@ -335,6 +367,7 @@ void orc_backward_update(void* p, const float* grad, float* common_grad) {
 void orc_flush(void* p) {
   Oracle* o = (Oracle*)p;
   const int D = o->D, S = o->S;
+  apply_pending(o);
   for (int64_t s = 0; s < o->C; ++s) {
     int64_t id = o->slot_id[s];
     if (id < 0) continue;
