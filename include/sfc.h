@@ -46,6 +46,14 @@ extern "C" {
 #define SFC_ELIMIT (-5)  /* more steps than max_steps */
 
 #define SFC_POLICY_LRU_BATCH 0
+/* The "Prefetch" strategy of the paper's MixCache ablation (RQ3), for comparison runs: nothing is
+ * kept resident (capacity_rows must be 0, lookahead must be 1) and the rows of step t+1 are copied
+ * from Host while step t is looked up, without waiting for step t's update: a row of both batches
+ * is trained from its stale value and step t's update of it is overwritten.  Made deterministic:
+ * sfc_backward_update of step t waits for the copies of step t+1 when they were issued before it,
+ * so step t+1 misses exactly the update of step t.  (The ablation's "Host" strategy is
+ * SFC_POLICY_LRU_BATCH with capacity_rows = 0.) */
+#define SFC_POLICY_PREFETCH 1
 
 /* Optimizers and the floats of state S that travel with every row (cache <-> Host):
  *   ADAGRAD          S = D    element-wise accumulator
@@ -63,7 +71,7 @@ typedef struct sfc_cache sfc_cache; /* opaque */
 typedef struct {
   int64_t capacity_rows;      /* C >= 0: row slots of the cache buffer (0 = every row bypasses) */
   int32_t dim;                /* D: floats per row, multiple of 4, <= 256 */
-  int32_t policy;             /* SFC_POLICY_LRU_BATCH */
+  int32_t policy;             /* SFC_POLICY_LRU_BATCH or SFC_POLICY_PREFETCH */
   int64_t max_ids_per_batch;  /* upper bound on n_ids of any step; sizes scratch and bypass rows */
   int64_t max_bags_per_batch; /* upper bound on n_bags of any step */
   int64_t host_rows;          /* V: rows of the Host table; valid ids are [0, V) */

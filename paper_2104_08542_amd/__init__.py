@@ -22,6 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libsfc.so")
 
 SFC_OK, SFC_EINVAL, SFC_ESTATE, SFC_EHIP, SFC_ENOMEM, SFC_ELIMIT = 0, -1, -2, -3, -4, -5
 SFC_POLICY_LRU_BATCH = 0
+SFC_POLICY_PREFETCH = 1
 
 EXPORTS = [
     "sfc_host_alloc", "sfc_host_free", "sfc_cache_create", "sfc_cache_destroy", "sfc_prepare",
@@ -274,7 +275,7 @@ class Cache:
 
     def __init__(self, table: HostTable, capacity_rows: int, max_ids: int, max_bags: Optional[int] = None,
                  lr=0.01, eps=1e-8, lookahead=0, max_steps=0, device="cuda:0", side_stream=True,
-                 betas=(0.9, 0.999)):
+                 betas=(0.9, 0.999), policy=None):
         self.table, self.C, self.D = table, int(capacity_rows), table.dim
         self.device = torch.device(device)
         self.max_ids = int(max_ids)
@@ -283,7 +284,7 @@ class Cache:
         with torch.cuda.device(self.device):
             self.stream = torch.cuda.current_stream()
             self.side = torch.cuda.Stream() if (side_stream or lookahead) else self.stream
-            cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH, self.max_ids, self.max_bags,
+            cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH if policy is None else policy, self.max_ids, self.max_bags,
                              table.rows, table._pw, table._pa, table.stride, lr, eps, lookahead,
                              max_steps, self.stream.cuda_stream, self.side.cuda_stream,
                              OPTIMIZERS.index(table.optimizer), 0, table.state_stride,

@@ -299,7 +299,10 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   *out = nullptr;
   if (cfg->capacity_rows < 0 || cfg->dim <= 0 || cfg->dim % 4 || cfg->dim > 256)
     return fail(SFC_EINVAL, "capacity_rows must be >= 0 and dim a multiple of 4 in [4, 256]");
-  if (cfg->policy != SFC_POLICY_LRU_BATCH) return fail(SFC_EINVAL, "unknown policy");
+  if (cfg->policy != SFC_POLICY_LRU_BATCH && cfg->policy != SFC_POLICY_PREFETCH)
+    return fail(SFC_EINVAL, "unknown policy");
+  if (cfg->policy == SFC_POLICY_PREFETCH && (cfg->capacity_rows != 0 || cfg->lookahead != 1))
+    return fail(SFC_EINVAL, "the Prefetch strategy needs capacity_rows = 0 and lookahead = 1");
   if (cfg->max_ids_per_batch < 1 || cfg->max_bags_per_batch < 1 || cfg->host_rows < 1)
     return fail(SFC_EINVAL, "max_ids_per_batch, max_bags_per_batch and host_rows must be >= 1");
   if (cfg->lookahead < 0 || cfg->lookahead > 2) return fail(SFC_EINVAL, "lookahead must be 0, 1 or 2");
@@ -529,7 +532,7 @@ int sfc_fetch_misses(sfc_cache* c) {
   // table yet (k_swap_rows decides on the device which of its two launches does the work)
   x->older1 = x->older2 = nullptr;
   x->chain = 0; x->main_pending = false; x->main_after = 0;
-  for (int k = 0; k < c->nctx; ++k) {
+  for (int k = 0; k < c->nctx && c->cfg.policy != SFC_POLICY_PREFETCH; ++k) {
     StepCtx* o = &c->ctx[k];
     if (o == x || o->state != FETCHED || o->updated) continue;
     if (o->t == x->t - 1) { x->older1 = o->ctr; x->chain = o->main_pending ? 1 : 0; }
@@ -602,6 +605,14 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   EventPair ep{}, e1{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
   if ((rc = seg_launch(c, x, d_grad, c->gsum))) return rc;
+  if (c->cfg.policy == SFC_POLICY_PREFETCH) {
+    // the copies of a newer step issued so far read the Host table before this update writes it
+    for (int k = 0; k < c->nctx; ++k) {
+      StepCtx* y = &c->ctx[k];
+      if (y != x && y->state == FETCHED && !y->updated && y->t > x->t)
+        HIPCHK(hipStreamWaitEvent(s, y->ev_fetched, 0));
+    }
+  }
   if ((rc = prof_begin(c, P_ADAGRAD, s, &e1))) return rc;
   const dim3 ug(grid_for(x->n_ids * c->d4, 1024, kGridCap));
   if (c->cfg.optimizer == SFC_OPT_ADAGRAD) {

@@ -74,3 +74,4 @@ def test_adam_capacity_zero_and_full_residency():
         p.close()
     assert_close(tabs[0][0], tabs[1][0], "weights, C = 0 vs C = V")
     assert_close(tabs[0][1], tabs[1][1], "moments, C = 0 vs C = V")
+
