@@ -47,6 +47,11 @@ def main():
                          "the copies of step t+1 also overlap the prepare of step t+2 (default)")
     ap.add_argument("--optimizer", default="adagrad", choices=["adagrad", "adam", "rowwise_adagrad"],
                     help="adagrad is the benchmark's; adam is the paper's (state 2x the row)")
+    ap.add_argument("--strategy", default="cache", choices=["cache", "host", "prefetch"],
+                    help="the MixCache ablation's strategies: cache (MixCache, default), host (no cache, "
+                         "nothing fetched ahead: capacity 0, lookahead 0), prefetch (no cache, next "
+                         "batch's rows copied before the current update, stale by one step)")
+    ap.add_argument("--cache-rows", type=int, default=None, help="override the workload's cache size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -67,6 +72,13 @@ def main():
     w = si.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
     D, V, C = w.dim, w.vocab, w.cache_rows
+    if args.cache_rows is not None:
+        C = args.cache_rows
+    policy = None
+    if args.strategy != "cache":
+        C = 0
+        args.lookahead = 0 if args.strategy == "host" else 1
+        policy = sfc.SFC_POLICY_PREFETCH if args.strategy == "prefetch" else None
     R = 4 * D
 
     t0 = time.time()
@@ -80,7 +92,7 @@ def main():
     log("host table [%d, %d + %d] pinned and filled in %.1fs" % (V, D, S, time.time() - t0))
 
     cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lr=w.lr, eps=w.eps, lookahead=args.lookahead,
-                      device="cuda:0")
+                      device="cuda:0", policy=policy)
     out = torch.empty(w.n_bags, D, dtype=torch.float32, device=dev)
     grads = [w.batch_grads(i, dev) for i in range(4)]
     step_no = [0]          # next batch of the seeded sequence
@@ -216,6 +228,9 @@ def main():
             "hit_rate": avg["n_hit"] / max(1.0, avg["n_hit"] + avg["n_miss"]),
             "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
             "bypass_per_step": avg["n_bypass"], "lookahead": args.lookahead,
+            "strategy": args.strategy,
+            "host_to_gpu_rows_per_unique": avg["n_miss"] / max(1.0, U),
+            "gpu_to_host_rows_per_unique": (avg["n_evict"] + avg["n_bypass"]) / max(1.0, U),
         },
         "roofline": {
             "bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -249,7 +264,8 @@ def main():
         ow = np.ascontiguousarray(table.w)
         oa = np.ascontiguousarray(table.acc[:, :oracle_state_floats(args.optimizer, D)])
         log("dense copy of the host table for the oracle in %.1fs" % (time.time() - t1))
-        orc = Oracle(C, D, ow, oa, lr=w.lr, eps=w.eps, optimizer=args.optimizer)
+        orc = Oracle(C, D, ow, oa, lr=w.lr, eps=w.eps, optimizer=args.optimizer,
+                     strategy="prefetch" if args.strategy == "prefetch" else "cache")
         done_ids, steps_done, cpu_t = 0, 0, 0.0
         while cpu_t < args.cpu_seconds and steps_done < 50:
             ids, off = w.batch_ids(steps_done, dev)

@@ -48,7 +48,10 @@ enum State { FREE = 0, PREPARED = 1, FETCHED = 2 };
 enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEG_STREAM = 4, P_SEG_FINISH = 5,
        P_ADAGRAD = 6, P_N = 7 };
 
-struct EventPair { hipEvent_t a, b; };
+struct EventPair {
+  hipEvent_t a, b;
+  bool extra = false;   // adds to the time of its call but is not a call of its own
+};
 
 struct StepCtx {
   int state = FREE;
@@ -103,7 +106,7 @@ struct sfc_cache {
   int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
-  int* age_mat = nullptr;                       // [kResolveGrid, kAgeBins] hits by age per block
+  int* age_hist = nullptr;                      // [kAgeBins] hits of the step by age, zero between steps
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
   HostRows host{};                              // device view of the Host table
@@ -153,6 +156,7 @@ int prof_begin(sfc_cache* c, int which, hipStream_t s, EventPair* ep) {
   if (!prof_on(c, which)) return SFC_OK;
   if (!c->spare.empty()) { *ep = c->spare.back(); c->spare.pop_back(); }
   else { HIPCHK(hipEventCreate(&ep->a)); HIPCHK(hipEventCreate(&ep->b)); }
+  ep->extra = false;
   HIPCHK(hipEventRecord(ep->a, s));
   return SFC_OK;
 }
@@ -169,7 +173,7 @@ int prof_collect(sfc_cache* c) {
       HIPCHK(hipEventSynchronize(ep.b));
       HIPCHK(hipEventElapsedTime(&ms, ep.a, ep.b));
       c->ms_sum[w] += ms;
-      c->calls[w] += 1;
+      if (!ep.extra) c->calls[w] += 1;
       c->spare.push_back(ep);
     }
     c->pending[w].clear();
@@ -202,14 +206,14 @@ int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
   int rc;
   // the copies read the step's counters, miss list and victim list: its prepare comes first
   if (s != c->prep) HIPCHK(hipStreamWaitEvent(s, x->ev_prepared, 0));
-  const bool timed = !main_variant;
-  if (timed && (rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
+  if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
+  ep.extra = main_variant != 0;          // the second launch of a step: same call
   hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, kSwapBlocks)), dim3(256), 0, s,
                      x->d_miss, x->d_unique, x->d_slot, x->victim_id, (float4*)c->cw,
                      (float4*)c->ca, c->host, c->d4, c->s4, (int)c->C, x->boff, x->ctr, x->older1,
                      x->older2, x->chain, main_variant);
   HIPCHK(hipGetLastError());
-  if (timed && (rc = prof_end(c, P_FETCH, s, &ep))) return rc;
+  if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
   if (main_variant) x->main_pending = false;
   else HIPCHK(hipEventRecord(x->ev_fetched, s));
   return SFC_OK;
@@ -386,7 +390,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
-    if ((rc = dalloc(c, &c->age_mat, (int64_t)kResolveGrid * kAgeBins))) goto bad;
+    if ((rc = dalloc(c, &c->age_hist, (int64_t)kAgeBins))) goto bad;
     {
       const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;
       const int64_t nwmax = nw > 4104 ? nw : 4104;     // the stream never has more wavefronts
@@ -414,6 +418,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     IdxEntry empty; empty.key = kEmpty; empty.slot = -1; empty.pad = 0;
     fill<IdxEntry>(s, c->index, (int64_t)c->hi, empty);
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
+    fill<int>(s, c->age_hist, (int64_t)kAgeBins, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
     Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
@@ -501,8 +506,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt,
-                     c->tile_cnt, c->age_mat, x->ctr);
-  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_mat, gr,
+                     c->tile_cnt, c->age_hist, x->ctr);
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
                      c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,

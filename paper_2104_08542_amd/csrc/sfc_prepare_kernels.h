@@ -434,13 +434,13 @@ __global__ __launch_bounds__(256) void k_index_reinsert(IdxEntry* index, uint32_
 // Resolve: each unique id against the index.  Hits get their slot and the current stamp.  The
 // recency histogram hist[stamp] = #slots with that stamp must stay exact; stamps of hits cluster
 // on the last few steps, i.e. on a few words of hist, so each block tallies its hits by age
-// (t - old stamp) in LDS and stores the tally as one row of age_mat; the plan kernel adds the
-// rows up.  Only ages beyond the LDS range use an atomic on hist.  Bin 0 of a row counts the
-// block's hits.  Also returns the batch-table entries of this step to the empty state, so that
+// (t - old stamp) in LDS and adds its nonzero bins to age_hist, which the plan kernel applies
+// to hist and returns to zero.  Only ages beyond the LDS range use an atomic on hist.  Bin 0
+// counts the hits.  Also returns the batch-table entries of this step to the empty state, so that
 // table never needs a per-step clear, and sums cnt per tile for the segment offsets.
 // ---------------------------------------------------------------------------------------------
 constexpr int kAgeBins = 1024;
-constexpr int kResolveGrid = 256;   // rows of age_mat
+constexpr int kResolveGrid = 256;
 
 __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
                                                   const int* __restrict__ vid_hslot, UEntry* utab,
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
                                                   int* __restrict__ tile_miss,
                                                   const int* __restrict__ cnt,
                                                   int* __restrict__ tile_cnt,
-                                                  int* __restrict__ age_mat, Ctr* ctr) {
+                                                  int* __restrict__ age_hist, Ctr* ctr) {
   __shared__ int smem[20];
   __shared__ int lage[kAgeBins];
   for (int i = threadIdx.x; i < kAgeBins; i += 256) lage[i] = 0;
@@ -513,7 +513,8 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < kAgeBins; i += 256) age_mat[blockIdx.x * kAgeBins + i] = lage[i];
+  for (int i = threadIdx.x; i < kAgeBins; i += 256)
+    if (lage[i]) atomicAdd(&age_hist[i], lage[i]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -522,8 +523,7 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
 // evictable slots (stamp < limit, oldest first) passes need; r of the slots stamped T go too.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
-                                               const int* __restrict__ age_mat, int age_rows,
-                                               int* hist, int t, int lookahead, int C, uint32_t hi,
+                                               int* __restrict__ age_hist, int* hist, int t, int lookahead, int C, uint32_t hi,
                                                Ctr* ctr) {
   static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
@@ -536,9 +536,8 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
   // hits by age: thread a owns age a.  hist[t] gains the hits, hist[t - a] loses its share.
   {
     const int a = (int)threadIdx.x;
-    int sum = 0;
-#pragma unroll 8
-    for (int g = 0; g < age_rows; ++g) sum += age_mat[g * kAgeBins + a];
+    const int sum = age_hist[a];
+    age_hist[a] = 0;
     if (a == 0) { hist[t] += sum; ctr->n_hit = sum; }
     else if (sum) hist[t - a] -= sum;
   }
@@ -626,14 +625,21 @@ __global__ __launch_bounds__(256) void k_victim_count(const int* __restrict__ st
   for (int tile = blockIdx.x; tile * kPosChunk < f; tile += gridDim.x) {
     const int base = tile * kPosChunk + (int)threadIdx.x * 8;
     int lt = 0, eq = 0;
+    if (base + 8 <= f) {
+      const int4 a = *reinterpret_cast<const int4*>(stamp + base);
+      const int4 b = *reinterpret_cast<const int4*>(stamp + base + 4);
+      const int v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int s = base + j;
-      if (s < f) { const int st = stamp[s]; lt += st < T; eq += st == T; }
+      for (int j = 0; j < 8; ++j) { lt += v[j] < T; eq += v[j] == T; }
+    } else {
+      for (int j = 0; j < 8; ++j) {
+        const int s = base + j;
+        if (s < f) { const int st = stamp[s]; lt += st < T; eq += st == T; }
+      }
     }
-    lt = block_sum(lt, smem);
-    eq = block_sum(eq, smem);
-    if (threadIdx.x == 0) { tile_lt[tile] = lt; tile_eq[tile] = eq; }
+    // both counts in one block reduction: a tile has 2048 slots, so each fits in 16 bits
+    const int both = block_sum((lt << 16) | eq, smem);
+    if (threadIdx.x == 0) { tile_lt[tile] = both >> 16; tile_eq[tile] = both & 0xffff; }
   }
 }
 
@@ -670,18 +676,25 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
     const int base = tile * kPosChunk + (int)threadIdx.x * 8;
     unsigned mlt = 0, meq = 0;
     int lt = 0, eq = 0;
+    int v[8];
+    if (base + 8 <= f) {
+      const int4 a = *reinterpret_cast<const int4*>(stamp + base);
+      const int4 b = *reinterpret_cast<const int4*>(stamp + base + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = base + j < f ? stamp[base + j] : kIntMax;   // never a victim
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int s = base + j;
-      if (s < f) {
-        const int st = stamp[s];
-        if (st < T) { mlt |= 1u << j; ++lt; }
-        if (st == T) { meq |= 1u << j; ++eq; }
-      }
+      if (v[j] < T) { mlt |= 1u << j; ++lt; }
+      if (v[j] == T) { meq |= 1u << j; ++eq; }
     }
+    // one scan for both counts: a tile has 2048 slots, so each prefix fits in 16 bits
     int tot;
-    int lt_before = block_excl_scan(lt, tot, smem) + tile_lt[tile];
-    int eq_before = block_excl_scan(eq, tot, smem) + tile_eq[tile];
+    const int both = block_excl_scan((lt << 16) | eq, tot, smem);
+    int lt_before = (both >> 16) + tile_lt[tile];
+    int eq_before = (both & 0xffff) + tile_eq[tile];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bool is_lt = mlt & (1u << j), is_eq = meq & (1u << j);
