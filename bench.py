@@ -51,6 +51,8 @@ def main():
                     help="the MixCache ablation's strategies: cache (MixCache, default), host (no cache, "
                          "nothing fetched ahead: capacity 0, lookahead 0), prefetch (no cache, next "
                          "batch's rows copied before the current update, stale by one step)")
+    ap.add_argument("--align-floats", type=int, default=32,
+                    help="pad each Host row block [weights | state] to a multiple of this many floats")
     ap.add_argument("--cache-rows", type=int, default=None, help="override the workload's cache size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -83,7 +85,7 @@ def main():
 
     t0 = time.time()
     S = sfc.state_floats(args.optimizer, D)
-    table = sfc.HostTable(V, D, optimizer=args.optimizer)
+    table = sfc.HostTable(V, D, optimizer=args.optimizer, align_floats=args.align_floats)
     chunk = max(1, (1 << 26) // D)
     for r0 in range(0, V, chunk):
         r1 = min(V, r0 + chunk)

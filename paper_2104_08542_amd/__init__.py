@@ -210,18 +210,21 @@ class HostTable:
     strided numpy views.  interleaved=False uses two separate contiguous arrays.
     """
 
-    def __init__(self, rows: int, dim: int, interleaved: bool = True, optimizer: str = "adagrad"):
+    def __init__(self, rows: int, dim: int, interleaved: bool = True, optimizer: str = "adagrad",
+                 align_floats: int = 1):
         self.rows, self.dim, self.interleaved = int(rows), int(dim), bool(interleaved)
         self.optimizer = optimizer
         S = self.state_dim = state_floats(optimizer, self.dim)
         if self.interleaved:
-            tot = self.rows * (self.dim + S)
+            # align_floats > 1 pads each [weights | state] block to a multiple of that many floats
+            st = -(-(self.dim + S) // align_floats) * align_floats
+            tot = self.rows * st
             self._base = sfc_host_alloc(tot * 4)
             self._pw, self._pa = self._base, self._base + 4 * self.dim
-            self.stride = self.state_stride = self.dim + S
+            self.stride = self.state_stride = st
             both = np.ctypeslib.as_array((ctypes.c_float * tot).from_address(self._base)
-                                         ).reshape(self.rows, self.dim + S)
-            self.w, self.acc = both[:, :self.dim], both[:, self.dim:]
+                                         ).reshape(self.rows, st)
+            self.w, self.acc = both[:, :self.dim], both[:, self.dim:self.dim + S]
             self._bases = [self._base]
         else:
             self._pw = sfc_host_alloc(self.rows * self.dim * 4)
