@@ -5,6 +5,7 @@ The oracle runs in lock step on its own copy of the Host table, so every output 
 compared element by element, as in the small tests.  Four batches of uniform ids fill the 8e6
 slots (a Zipf batch brings only ~2.4e5 new ids), then Zipf batches run against the full cache, so
 eviction, tombstones in the index and long hot groups are all exercised at full size.
+The last five steps run pipelined at lookahead 2, the order and streams bench.py times.
 Needs about 60 GB of host memory; skipped when the box has less.
 """
 import sys
@@ -30,25 +31,35 @@ def test_target_configuration_full_size():
     if psutil.virtual_memory().available < need:
         pytest.skip("needs %.0f GB of free host memory" % (need / 1e9))
     t0 = time.time()
-    p = Pair(w.vocab, w.dim, w.cache_rows, w.max_ids, seed=w.seed)
+    p = Pair(w.vocab, w.dim, w.cache_rows, w.max_ids, seed=w.seed, lookahead=2)
     _say("tables ready after %.0fs" % (time.time() - t0))
     n = w.max_ids
     evicted = bypassed = 0
-    for t in range(7):
+    # calls in order first: every output of every call compared
+    for t in range(5):
         if t < 4:
             ids = si.uniform_ids(n, w.vocab, w.seed, t).numpy()       # ~2.5e6 new ids per step
         else:
             ids = w.batch_ids(t)[0].numpy()
         grad = w.batch_grads(t).numpy()
-        pr = p.step(ids, grad, check_state=(t in (3, 6)), check_rows=False)
+        pr = p.step(ids, grad, check_state=(t in (3, 4)), check_rows=False)
         evicted += pr.stats["n_evict"]
         bypassed += pr.stats["n_bypass"]
         _say("step %d: U=%d hit=%d miss=%d evict=%d, %.0fs" % (
             t, pr.stats["n_unique"], pr.stats["n_hit"], pr.stats["n_miss"], pr.stats["n_evict"],
             time.time() - t0))
+    # then as bench.py issues them: prepare / copies two steps ahead on their own streams, nothing
+    # waits; lookup outputs, final cache state and flushed tables are compared
+    bs = [(w.batch_ids(t)[0].numpy(), w.batch_grads(t).numpy(), None) for t in range(5, 10)]
+    expect = p.run_pipelined(bs, False)
+    for pr, _ in expect:
+        evicted += pr.stats["n_evict"]
+        bypassed += pr.stats["n_bypass"]
+    _say("5 pipelined steps and flushed tables compared after %.0fs" % (time.time() - t0))
     assert evicted > 1_000_000 and bypassed == 0
     # properties that hold at any size, on the last step's outputs
     c = p.cache
+    ids = bs[-1][0]
     U = c.stats()["n_unique"]
     uniq = c.unique_ids[:U].cpu().numpy()
     inv = c.inverse[:n].cpu().numpy()
@@ -59,8 +70,6 @@ def test_target_configuration_full_size():
     assert np.array_equal(sid[slot], uniq)                 # every id of the batch is resident
     res = sid[sid >= 0]
     assert res.size == np.unique(res).size == w.cache_rows  # full cache, no id twice
-    p.finish()
-    _say("flushed tables compared after %.0fs" % (time.time() - t0))
     p.close()
 
 
