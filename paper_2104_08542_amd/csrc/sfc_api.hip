@@ -106,6 +106,7 @@ struct sfc_cache {
   int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
+  int* n_invalid = nullptr;                     // out-of-range positions of the step being prepared
   int* age_hist = nullptr;                      // [kAgeBins] hits of the step by age, zero between steps
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
@@ -391,6 +392,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->age_hist, (int64_t)kAgeBins))) goto bad;
+    if ((rc = dalloc(c, &c->n_invalid, 1))) goto bad;
     {
       const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;
       const int64_t nwmax = nw > 4104 ? nw : 4104;     // the stream never has more wavefronts
@@ -419,6 +421,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<IdxEntry>(s, c->index, (int64_t)c->hi, empty);
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
     fill<int>(s, c->age_hist, (int64_t)kAgeBins, 0);
+    fill<int>(s, c->n_invalid, 1, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
     Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
@@ -483,20 +486,18 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   uint32_t hu = (uint32_t)(2 * n_ids);
   if (hu < 64) hu = 64;                       // the batch table is empty between steps: any size works
   const int nchunk = (n + kPosChunk - 1) / kPosChunk;
-  hipLaunchKernelGGL(k_step_begin, dim3(1), dim3(64), 0, s, x->ctr, prev->ctr);
   if (n > 0) {
     hipLaunchKernelGGL(k_uniq_insert, dim3((n + kUniqChunk - 1) / kUniqChunk), dim3(256), 0, s,
-                       d_ids, n, c->V, c->utab, hu, c->hslot, x->ctr);
+                       d_ids, n, c->V, c->utab, hu, c->hslot, c->n_invalid);
     hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
-                       c->blk_cnt);
+                       c->blk_cnt, c->index, c->hi, prev->ctr);
   }
-  hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, x->ctr);
-  hipLaunchKernelGGL(k_index_reinsert, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi,
-                     c->slot_id, x->ctr);
-  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, x->ctr);
+  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, x->ctr, prev->ctr,
+                     c->n_invalid);
   if (n > 0) {
     hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
-                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt);
+                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt, c->index, c->hi,
+                       c->slot_id, x->ctr);
     hipLaunchKernelGGL(k_uniq_inverse, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uvid, n,
                        d_inverse, c->cnt);
     if (d_offsets)
@@ -512,7 +513,6 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
                      x->ctr);
-  hipLaunchKernelGGL(k_victim_scan, dim3(1), dim3(1024), 0, s, c->tile_lt, c->tile_eq, x->ctr);
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
                      c->tile_eq, c->index, c->hi, x->victim_slot, x->victim_id, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);

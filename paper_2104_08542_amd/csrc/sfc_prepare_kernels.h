@@ -13,18 +13,6 @@ namespace sfc {
 constexpr int kPosChunk = 2048;   // positions (or slots) per block in the scan passes
 constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
 
-// First kernel of a prepare: the new step's counters inherit the cache-wide fields (watermark,
-// oldest stamp, tombstones, rebuild flag, error) from the previous step's and start their own
-// tallies at zero.  Steps in flight on the other stream keep reading their own copy.
-__global__ void k_step_begin(Ctr* cur, const Ctr* prev) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    Ctr c = *prev;
-    c.U = c.M = c.K = c.n_bypass = c.n_hit = c.n_invalid = 0;
-    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
-    *cur = c;
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 // VSI pass 1: insert every position's id into the batch table (open addressing, linear probing,
 // in HBM) and keep the smallest position per key; remember the table entry of each position.
@@ -50,7 +38,8 @@ __device__ __forceinline__ T coherent_load(const T* p) {
 
 __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__ ids, int n,
                                                       int64_t V, UEntry* utab, uint32_t hu,
-                                                      int* __restrict__ hslot, Ctr* ctr) {
+                                                      int* __restrict__ hslot,
+                                                      int* __restrict__ n_invalid) {
   __shared__ int64_t lkey[kLdsTab];
   __shared__ int lval[kLdsTab];               // smallest position of the key in this block; later its HBM entry
   __shared__ unsigned short lst[kUniqChunk];  // occupied LDS entries, compacted
@@ -90,7 +79,7 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
       ls[j] = (int)l;
     }
     const uint64_t b = __ballot(invalid);
-    if (b && lane_id() == 0) atomicAdd(&ctr->n_invalid, __popcll(b));
+    if (b && lane_id() == 0) atomicAdd(n_invalid, __popcll(b));
   }
   __syncthreads();
   // compact the occupied entries (16 consecutive entries per thread)
@@ -183,10 +172,37 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
 }
 
 // VSI pass 2: per chunk of positions, how many are the first appearance of their id.
+// Rebuild of the cache index, second half (the first half empties it): every resident id goes
+// back in.  Grid-stride over the occupied slots [0, f).
+__device__ __forceinline__ void index_reinsert(IdxEntry* index, uint32_t hi,
+                                               const int64_t* __restrict__ slot_id, int f) {
+  for (int s = blockIdx.x * 256 + threadIdx.x; s < f; s += gridDim.x * 256) {
+    const int64_t id = slot_id[s];
+    if (id < 0) continue;
+    uint32_t h = bucket_of(id, hi);
+    for (uint32_t probes = 0; probes < hi; ++probes) {
+      if (index[h].key == kEmpty &&
+          (int64_t)atomicCAS((unsigned long long*)&index[h].key, (unsigned long long)kEmpty,
+                             (unsigned long long)id) == kEmpty) {
+        index[h].slot = s;
+        break;
+      }
+      h = h + 1 == hi ? 0 : h + 1;
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslot,
                                                      const UEntry* __restrict__ utab, int n,
-                                                     int* __restrict__ blk_cnt) {
+                                                     int* __restrict__ blk_cnt, IdxEntry* index,
+                                                     uint32_t hi, const Ctr* prev) {
   __shared__ int smem[20];
+  // cache index due for a rebuild (the previous step's plan asked for it): empty it here, the
+  // assign pass re-inserts the resident ids
+  if (prev->rebuild) {
+    IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
+  }
   const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
   int c = 0;
 #pragma unroll
@@ -201,9 +217,13 @@ __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslo
   if (threadIdx.x == 0) blk_cnt[blockIdx.x] = tot;
 }
 
-// Single-block exclusive scan of data[0..n) in place; total to *total_out.  Also the place where
-// per-step flags are reset (it runs once per prepare, after the optional index rebuild).
-__global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* ctr) {
+// One block, after the count pass: scans the per-chunk counts, and starts the step's counters:
+// they inherit the cache-wide fields (watermark, oldest stamp, tombstones, rebuild flag, error)
+// from the previous step's and start their own tallies at zero.  Steps in flight on the other
+// streams keep reading their own copy.  n_invalid is the insert pass's tally of out-of-range
+// positions, returned to zero here.
+__global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* cur, const Ctr* prev,
+                                                      int* n_invalid) {
   __shared__ int smem[20];
   int carry = 0;
   for (int b = 0; b < n; b += 1024) {
@@ -215,20 +235,27 @@ __global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* ctr
     carry += tot;
   }
   if (threadIdx.x == 0) {
-    ctr->U = carry;
-    if (ctr->rebuild) { ctr->rebuild = 0; ctr->tomb = 0; }
+    Ctr c = *prev;
+    c.U = carry;
+    c.M = c.K = c.n_bypass = c.n_hit = 0;
+    c.n_invalid = *n_invalid;
+    *n_invalid = 0;
+    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
+    *cur = c;
   }
 }
-
-// VSI pass 3: first appearances get consecutive virtual ids in position order.
 __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hslot,
                                                       const UEntry* __restrict__ utab, int n,
                                                       const int* __restrict__ blk_off,
                                                       int64_t* __restrict__ unique_ids,
                                                       int* __restrict__ uvid,
                                                       int* __restrict__ vid_hslot,
-                                                      int* __restrict__ cnt) {
+                                                      int* __restrict__ cnt, IdxEntry* index,
+                                                      uint32_t hi,
+                                                      const int64_t* __restrict__ slot_id,
+                                                      const Ctr* ctr) {
   __shared__ int smem[20];
+  if (ctr->rebuild) index_reinsert(index, hi, slot_id, ctr->f);
   const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
   int hs[8];
   unsigned flags = 0;
@@ -401,33 +428,6 @@ __device__ __forceinline__ void index_insert(IdxEntry* index, uint32_t hi, int64
     h = h + 1 == hi ? 0 : h + 1;
   }
   ctr->err = 2;
-}
-
-// Optional rebuild (runs every step, returns at once unless the plan kernel asked for it).
-__global__ __launch_bounds__(256) void k_index_clear(IdxEntry* index, uint32_t hi, const Ctr* ctr) {
-  if (!ctr->rebuild) return;
-  IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
-  for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
-}
-__global__ __launch_bounds__(256) void k_index_reinsert(IdxEntry* index, uint32_t hi,
-                                                         const int64_t* __restrict__ slot_id,
-                                                         Ctr* ctr) {
-  if (!ctr->rebuild) return;
-  const int f = ctr->f;
-  for (int s = blockIdx.x * 256 + threadIdx.x; s < f; s += gridDim.x * 256) {
-    const int64_t id = slot_id[s];
-    if (id < 0) continue;
-    uint32_t h = bucket_of(id, hi);
-    for (uint32_t probes = 0; probes < hi; ++probes) {
-      if (index[h].key == kEmpty &&
-          (int64_t)atomicCAS((unsigned long long*)&index[h].key, (unsigned long long)kEmpty,
-                             (unsigned long long)id) == kEmpty) {
-        index[h].slot = s;
-        break;
-      }
-      h = h + 1 == hi ? 0 : h + 1;
-    }
-  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -606,6 +606,8 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     ctr->need = need; ctr->T = T; ctr->r = r;
     ctr->f_old = f; ctr->f = f_new;
     if (need > 0 && T > oldest) ctr->oldest = T;
+    // a rebuild asked for by the previous step has run in this step's count / assign passes
+    if (ctr->rebuild && U > 0) { ctr->rebuild = 0; ctr->tomb = 0; }
     // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
     // quarter of the index would be deleted entries
     if ((unsigned)(ctr->tomb + K) > hi / 4) ctr->rebuild = 1;
@@ -643,25 +645,6 @@ __global__ __launch_bounds__(256) void k_victim_count(const int* __restrict__ st
   }
 }
 
-__global__ __launch_bounds__(1024) void k_victim_scan(int* tile_lt, int* tile_eq, const Ctr* ctr) {
-  __shared__ int smem[20];
-  if (ctr->K == 0) return;
-  const int ntiles = (ctr->f_old + kPosChunk - 1) / kPosChunk;
-  int c_lt = 0, c_eq = 0;
-  for (int b = 0; b < ntiles; b += 1024) {
-    const int i = b + (int)threadIdx.x;
-    int tot;
-    const int x = i < ntiles ? tile_lt[i] : 0;
-    const int e = block_excl_scan(x, tot, smem);
-    if (i < ntiles) tile_lt[i] = c_lt + e;
-    c_lt += tot;
-    const int y = i < ntiles ? tile_eq[i] : 0;
-    const int e2 = block_excl_scan(y, tot, smem);
-    if (i < ntiles) tile_eq[i] = c_eq + e2;
-    c_eq += tot;
-  }
-}
-
 __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ stamp,
                                                        const int64_t* __restrict__ slot_id,
                                                        const int* __restrict__ tile_lt,
@@ -672,7 +655,17 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
   __shared__ int smem[20];
   if (ctr->K == 0) return;
   const int f = ctr->f_old, T = ctr->T, r = ctr->r, K = ctr->K;
+  // victims in the tiles before this block's current one: summed from the per-tile counts, and
+  // carried on from tile to tile (each block reads every count at most once)
+  int pre_lt = 0, pre_eq = 0, summed = 0;
   for (int tile = blockIdx.x; tile * kPosChunk < f; tile += gridDim.x) {
+    {
+      int a = 0, b = 0;
+      for (int i = summed + (int)threadIdx.x; i < tile; i += 256) { a += tile_lt[i]; b += tile_eq[i]; }
+      pre_lt += block_sum(a, smem);
+      pre_eq += block_sum(b, smem);
+      summed = tile;
+    }
     const int base = tile * kPosChunk + (int)threadIdx.x * 8;
     unsigned mlt = 0, meq = 0;
     int lt = 0, eq = 0;
@@ -693,8 +686,8 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
     // one scan for both counts: a tile has 2048 slots, so each prefix fits in 16 bits
     int tot;
     const int both = block_excl_scan((lt << 16) | eq, tot, smem);
-    int lt_before = (both >> 16) + tile_lt[tile];
-    int eq_before = (both & 0xffff) + tile_eq[tile];
+    int lt_before = (both >> 16) + pre_lt;
+    int eq_before = (both & 0xffff) + pre_eq;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bool is_lt = mlt & (1u << j), is_eq = meq & (1u << j);
