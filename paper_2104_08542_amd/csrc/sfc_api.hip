@@ -4,10 +4,12 @@
 // documents as synchronising.
 //
 // A step in flight is a StepCtx: the caller's buffers, the step's device counters, its grouping
-// of positions, its victim list and its bypass region.  lookahead = 0 has one context and runs the
-// prepare on the main stream; lookahead = 1 has two, runs prepare and fetch of step t+1 on the side
-// stream while lookup / backward_update of step t run on the main stream (the paper's pipeline of
-// Host-Manager and GPU-Worker stages).
+// of positions, its victim list and its bypass region.  lookahead = L has L + 1 contexts.
+// L = 0 runs the prepare on the main stream; L = 1 runs prepare and Host copies of step t+1 on
+// the side stream while lookup / backward_update of step t run on the main stream; L = 2 gives
+// the prepare a stream of its own, so that prepare(t+2), the copies of t+1 and lookup / update
+// of t overlap (the paper's pipeline of Data-Loader, Host-Manager and GPU-Worker stages).
+// Streams are ordered by events only; the host never waits.
 #include "../../include/sfc.h"
 
 #include <hip/hip_runtime.h>

@@ -1,5 +1,5 @@
 // Row-moving kernels: Host<->cache copies, the forward gather, the gradient segment-sum and
-// the Adagrad update.  A row is D fp32 = D/4 chunks of 16 bytes; consecutive lanes take
+// the optimizer updates (Adagrad, Adam, row-wise Adagrad).  A row is D fp32 = D/4 chunks of 16 bytes; consecutive lanes take
 // consecutive chunks, so a wavefront moves 1 KiB of contiguous output per instruction and a
 // 128-byte row (D = 32) is one request of 8 lanes.
 #pragma once
@@ -21,11 +21,11 @@ __device__ __forceinline__ void st_stream(float4* p, float4 v) {
 
 // ---------------------------------------------------------------------------------------------
 // Host link (Algorithm 1 lines 5-6).  The Host table is pinned, device-mapped memory; the kernels
-// read / write it directly, 16 bytes per lane.  A row moves as 2*D/4 chunks: its weights, then its
-// accumulator; hs4 is the Host row stride in 16-byte units.  When the caller interleaves the two
-// Host arrays (h_acc = h_weights + D, stride 2D) the 2*D/4 lanes of a row touch one contiguous
-// 8*D-byte block of Host memory, which the link moves measurably faster than two 4*D-byte blocks
-// (55 vs 41 GB/s Host->device for D = 32).
+// read / write it directly, 16 bytes per lane.  A row moves as (D + S)/4 chunks: its weights, then
+// its S floats of optimizer state; hs4 / has4 are the Host row strides in 16-byte units.  When the
+// caller interleaves the two Host arrays (h_acc = h_weights + D, both strides D + S) the lanes of
+// a row touch one contiguous 4*(D+S)-byte block of Host memory, which the link moves measurably
+// faster than two separate blocks (55 vs 41 GB/s Host->device for D = S = 32).
 // The k-th miss takes the slot of the k-th victim (both lists are in ascending order of the
 // assignment), so one lane group does both directions for that slot: it loads the victim's row
 // from HBM and the missed row from Host, then stores each on the other side.  Reads and writes
