@@ -137,8 +137,12 @@ def main():
 
     # warm-up: fills the cache and reaches the steady-state hit rate
     t0 = time.time()
+    hit_curve = {}
     for t in range(W):
         run_steps([next_batch()], t)
+        if t % max(1, W // 10) == 0 or t == W - 1:     # hit rate on the way to the plateau (untimed)
+            st = cache.stats()                          # of the most recently prepared batch
+            hit_curve[step_no[0]] = round(st["n_hit"] / max(1, st["n_hit"] + st["n_miss"]), 4)
     torch.cuda.synchronize()
     log("warm-up %d steps in %.1fs" % (W, time.time() - t0))
 
@@ -231,6 +235,7 @@ def main():
             "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
             "bypass_per_step": avg["n_bypass"], "lookahead": args.lookahead,
             "strategy": args.strategy,
+            "hit_rate_by_batch": hit_curve,
             "host_to_gpu_rows_per_unique": avg["n_miss"] / max(1.0, U),
             "gpu_to_host_rows_per_unique": (avg["n_evict"] + avg["n_bypass"]) / max(1.0, U),
         },
