@@ -345,7 +345,13 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   c->st = (hipStream_t)cfg->stream;
   c->side = cfg->side_stream ? (hipStream_t)cfg->side_stream : c->st;
   c->hist_len = (cfg->max_steps ? cfg->max_steps : (1 << 20)) + 2;
-  c->hi = (uint32_t)(2 * (c->C + c->max_ids));
+  {
+    // four entries per possible resident id keep probe sequences short (HBM is plentiful); two
+    // where four would not fit a 32-bit entry number
+    int64_t h = 4 * (c->C + c->max_ids);
+    if (h > (int64_t)0xF0000000LL) h = 2 * (c->C + c->max_ids);
+    c->hi = (uint32_t)h;
+  }
   if (c->hi < 64) c->hi = 64;
 
   int rc = SFC_OK;

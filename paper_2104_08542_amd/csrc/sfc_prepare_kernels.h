@@ -609,8 +609,8 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     // a rebuild asked for by the previous step has run in this step's count / assign passes
     if (ctr->rebuild && U > 0) { ctr->rebuild = 0; ctr->tomb = 0; }
     // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
-    // quarter of the index would be deleted entries
-    if ((unsigned)(ctr->tomb + K) > hi / 4) ctr->rebuild = 1;
+    // eighth of the index would be deleted entries
+    if ((unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
   }
 }
 
