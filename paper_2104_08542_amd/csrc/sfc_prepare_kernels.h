@@ -411,7 +411,9 @@ __device__ __forceinline__ int index_find(const IdxEntry* __restrict__ index, ui
 }
 
 // id is known to be absent.  Takes the first empty or deleted entry of its probe sequence.
-__device__ __forceinline__ void index_insert(IdxEntry* index, uint32_t hi, int64_t id, int slot,
+// Returns true if that was a deleted entry: the caller takes it off the tombstone count (once per
+// wavefront: thousands of same-address atomics per step would serialise at the memory side).
+__device__ __forceinline__ bool index_insert(IdxEntry* index, uint32_t hi, int64_t id, int slot,
                                              Ctr* ctr) {
   uint32_t h = bucket_of(id, hi);
   for (uint32_t probes = 0; probes < hi; ++probes) {
@@ -421,13 +423,13 @@ __device__ __forceinline__ void index_insert(IdxEntry* index, uint32_t hi, int64
                                              (unsigned long long)k, (unsigned long long)id);
       if (old == k) {
         index[h].slot = slot;
-        if (k == kTomb) atomicSub(&ctr->tomb, 1);
-        return;
+        return k == kTomb;
       }
     }
     h = h + 1 == hi ? 0 : h + 1;
   }
   ctr->err = 2;
+  return false;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -739,6 +741,7 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
     const int off = block_excl_scan(v < U ? cnt[v] : 0, tot, smem) + tile_coff[tile];
     if (v < U) cursor[v] = off;
     const int i = block_excl_scan(miss ? 1 : 0, tot, smem) + tile_moff[tile];
+    bool reused = false;
     if (miss) {
       miss_vids[i] = v;
       int s;
@@ -750,9 +753,11 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
         const int64_t id = unique_ids[v];
         slot_id[s] = id;
         stamp[s] = t;
-        index_insert(index, hi, id, s, ctr);
+        reused = index_insert(index, hi, id, s, ctr);
       }
     }
+    const uint64_t m = __ballot(reused);
+    if (m && lane_id() == 0) atomicSub(&ctr->tomb, __popcll(m));
   }
 }
 
