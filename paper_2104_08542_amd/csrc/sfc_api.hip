@@ -108,6 +108,7 @@ struct sfc_cache {
   int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
+  int* tile_reuse = nullptr;                    // [max_ids / kVidTile + 1] deleted index entries reused per tile
   int* n_invalid = nullptr;                     // out-of-range positions of the step being prepared
   int* age_hist = nullptr;                      // [kAgeBins] hits of the step by age, zero between steps
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
@@ -399,6 +400,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
+    if ((rc = dalloc(c, &c->tile_reuse, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->age_hist, (int64_t)kAgeBins))) goto bad;
     if ((rc = dalloc(c, &c->n_invalid, 1))) goto bad;
     {
@@ -430,6 +432,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
     fill<int>(s, c->age_hist, (int64_t)kAgeBins, 0);
     fill<int>(s, c->n_invalid, 1, 0);
+    fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
     Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
@@ -517,6 +520,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt,
                      c->tile_cnt, c->age_hist, x->ctr);
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
+                     c->tile_reuse, (int)(c->max_ids / kVidTile + 1),
                      c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
@@ -526,7 +530,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int gv = grid_for(n, kVidTile, kGridCap);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->tile_cnt,
                      c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, c->slot_id,
-                     c->stamp, c->index, c->hi, x->t, (int)c->C, x->ctr);
+                     c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3(nchunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor,

@@ -396,37 +396,71 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
 // ---------------------------------------------------------------------------------------------
 // Cache index helpers (open addressing, linear probing, tombstones).
 // ---------------------------------------------------------------------------------------------
+// A probe sequence is walked eight entries (128 bytes) at a time, all eight loads in flight
+// together: the longest cluster among the tens of thousands of probes of a step sets the duration
+// of the kernel, and a dependent load per entry made that tail tens of microseconds long.
+constexpr int kProbeBatch = 8;
+
+__device__ __forceinline__ int64_t idx_key(const int4& raw) {
+  return ((int64_t)(uint32_t)raw.y << 32) | (uint32_t)raw.x;
+}
+__device__ __forceinline__ void idx_load_batch(const IdxEntry* index, uint32_t hi, uint32_t h,
+                                               int4 (&raw)[kProbeBatch]) {
+#pragma unroll
+  for (int j = 0; j < kProbeBatch; ++j) {
+    uint32_t hj = h + j;
+    if (hj >= hi) hj -= hi;                  // hi >= 64: wraps at most once
+    raw[j] = *reinterpret_cast<const int4*>(&index[hj]);
+  }
+}
+
 __device__ __forceinline__ int index_find(const IdxEntry* __restrict__ index, uint32_t hi,
                                           int64_t id, uint32_t* where, Ctr* ctr) {
   uint32_t h = bucket_of(id, hi);
-  for (uint32_t probes = 0; probes < hi; ++probes) {
-    const int4 raw = *reinterpret_cast<const int4*>(&index[h]);
-    const int64_t k = ((int64_t)(uint32_t)raw.y << 32) | (uint32_t)raw.x;
-    if (k == id) { if (where) *where = h; return raw.z; }
-    if (k == kEmpty) return -1;
-    h = h + 1 == hi ? 0 : h + 1;
+  for (uint32_t probes = 0; probes < hi; probes += kProbeBatch) {
+    int4 raw[kProbeBatch];
+    idx_load_batch(index, hi, h, raw);
+#pragma unroll
+    for (int j = 0; j < kProbeBatch; ++j) {
+      const int64_t k = idx_key(raw[j]);
+      if (k == id) {
+        if (where) { uint32_t hj = h + j; *where = hj >= hi ? hj - hi : hj; }
+        return raw[j].z;
+      }
+      if (k == kEmpty) return -1;
+    }
+    h += kProbeBatch;
+    if (h >= hi) h -= hi;
   }
   ctr->err = 1;
   return -1;
 }
 
 // id is known to be absent.  Takes the first empty or deleted entry of its probe sequence.
-// Returns true if that was a deleted entry: the caller takes it off the tombstone count (once per
-// wavefront: thousands of same-address atomics per step would serialise at the memory side).
+// Returns true if that was a deleted entry: the caller takes it off the tombstone count.
 __device__ __forceinline__ bool index_insert(IdxEntry* index, uint32_t hi, int64_t id, int slot,
                                              Ctr* ctr) {
   uint32_t h = bucket_of(id, hi);
-  for (uint32_t probes = 0; probes < hi; ++probes) {
-    const int64_t k = index[h].key;
-    if (k == kEmpty || k == kTomb) {
-      const int64_t old = (int64_t)atomicCAS((unsigned long long*)&index[h].key,
-                                             (unsigned long long)k, (unsigned long long)id);
-      if (old == k) {
-        index[h].slot = slot;
-        return k == kTomb;
+  for (uint32_t probes = 0; probes < hi; probes += kProbeBatch) {
+    int4 raw[kProbeBatch];
+    idx_load_batch(index, hi, h, raw);
+#pragma unroll
+    for (int j = 0; j < kProbeBatch; ++j) {
+      const int64_t k = idx_key(raw[j]);
+      if (k == kEmpty || k == kTomb) {
+        uint32_t hj = h + j;
+        if (hj >= hi) hj -= hi;
+        // an entry seen free may have been taken by another insert since: then walk on
+        const int64_t old = (int64_t)atomicCAS((unsigned long long*)&index[hj].key,
+                                               (unsigned long long)k, (unsigned long long)id);
+        if (old == k) {
+          index[hj].slot = slot;
+          return k == kTomb;
+        }
       }
     }
-    h = h + 1 == hi ? 0 : h + 1;
+    h += kProbeBatch;
+    if (h >= hi) h -= hi;
   }
   ctr->err = 2;
   return false;
@@ -525,7 +559,9 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
 // evictable slots (stamp < limit, oldest first) passes need; r of the slots stamped T go too.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
-                                               int* __restrict__ age_hist, int* hist, int t, int lookahead, int C, uint32_t hi,
+                                               int* __restrict__ age_hist,
+                                               int* __restrict__ tile_reuse, int reuse_tiles,
+                                               int* hist, int t, int lookahead, int C, uint32_t hi,
                                                Ctr* ctr) {
   static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
@@ -535,6 +571,10 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
   const int f = ctr->f;
   const int oldest = ctr->oldest;
   const int ntiles = (U + kVidTile - 1) / kVidTile;
+  // deleted index entries that the previous step's miss assignment took back into use
+  int reuse = 0;
+  for (int i = (int)threadIdx.x; i < reuse_tiles; i += 1024) { reuse += tile_reuse[i]; tile_reuse[i] = 0; }
+  reuse = block_sum(reuse, smem);
   // hits by age: thread a owns age a.  hist[t] gains the hits, hist[t - a] loses its share.
   {
     const int a = (int)threadIdx.x;
@@ -608,6 +648,7 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     ctr->need = need; ctr->T = T; ctr->r = r;
     ctr->f_old = f; ctr->f = f_new;
     if (need > 0 && T > oldest) ctr->oldest = T;
+    ctr->tomb -= reuse;
     // a rebuild asked for by the previous step has run in this step's count / assign passes
     if (ctr->rebuild && U > 0) { ctr->rebuild = 0; ctr->tomb = 0; }
     // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
@@ -729,7 +770,7 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         int* __restrict__ miss_vids,
                                                         int64_t* __restrict__ slot_id, int* stamp,
                                                         IdxEntry* index, uint32_t hi, int t, int C,
-                                                        Ctr* ctr) {
+                                                        int* __restrict__ tile_reuse, Ctr* ctr) {
   __shared__ int smem[20];
   const int U = ctr->U, K = ctr->K, f = ctr->f_old;
   const int free_slots = C - f;
@@ -756,8 +797,10 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
         reused = index_insert(index, hi, id, s, ctr);
       }
     }
-    const uint64_t m = __ballot(reused);
-    if (m && lane_id() == 0) atomicSub(&ctr->tomb, __popcll(m));
+    // deleted entries taken back into use: tallied per tile for the next plan pass (thousands of
+    // atomics on one counter would serialise at the memory side, about 10 ns each)
+    const int nre = block_sum(reused ? 1 : 0, smem);
+    if (threadIdx.x == 0) tile_reuse[tile] = nre;
   }
 }
 
