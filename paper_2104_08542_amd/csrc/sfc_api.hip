@@ -520,16 +520,16 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt,
                      c->tile_cnt, c->age_hist, x->ctr);
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
-                     c->tile_reuse, (int)(c->max_ids / kVidTile + 1),
+                     c->tile_reuse,
                      c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
   const int gs = grid_for(c->C, kPosChunk, kGridCap);
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
                      x->ctr);
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
-                     c->tile_eq, c->index, c->hi, x->victim_slot, x->victim_id, x->ctr);
+                     c->tile_eq, x->victim_slot, x->victim_id, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->tile_cnt,
-                     c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, c->slot_id,
+                     c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3(nchunk), dim3(256), 0, s, d_inverse,

@@ -31,6 +31,7 @@ struct Ctr {
   int rebuild;    // set when the index must be rebuilt before the next resolve
   int err;        // nonzero: a probe loop ran off its bound
   int fetch_on_main;  // pipelined mode: this step's Host copies ran behind the older steps' updates
+  int U_prev;     // unique ids of the previous step (its per-tile tallies are still to be read)
 };
 
 // Entry of the per-step batch table: key and the smallest position that carries it, one 16-byte

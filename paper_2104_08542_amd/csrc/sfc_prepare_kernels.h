@@ -236,6 +236,7 @@ __global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* cur
   }
   if (threadIdx.x == 0) {
     Ctr c = *prev;
+    c.U_prev = c.U;
     c.U = carry;
     c.M = c.K = c.n_bypass = c.n_hit = 0;
     c.n_invalid = *n_invalid;
@@ -560,9 +561,8 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
                                                int* __restrict__ age_hist,
-                                               int* __restrict__ tile_reuse, int reuse_tiles,
-                                               int* hist, int t, int lookahead, int C, uint32_t hi,
-                                               Ctr* ctr) {
+                                               int* __restrict__ tile_reuse, int* hist, int t,
+                                               int lookahead, int C, uint32_t hi, Ctr* ctr) {
   static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
   __shared__ int s_found;
@@ -573,6 +573,7 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
   const int ntiles = (U + kVidTile - 1) / kVidTile;
   // deleted index entries that the previous step's miss assignment took back into use
   int reuse = 0;
+  const int reuse_tiles = (ctr->U_prev + kVidTile - 1) / kVidTile;
   for (int i = (int)threadIdx.x; i < reuse_tiles; i += 1024) { reuse += tile_reuse[i]; tile_reuse[i] = 0; }
   reuse = block_sum(reuse, smem);
   // hits by age: thread a owns age a.  hist[t] gains the hits, hist[t - a] loses its share.
@@ -692,7 +693,6 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
                                                        const int64_t* __restrict__ slot_id,
                                                        const int* __restrict__ tile_lt,
                                                        const int* __restrict__ tile_eq,
-                                                       IdxEntry* index, uint32_t hi,
                                                        int* __restrict__ victim_slot,
                                                        int64_t* __restrict__ victim_id, Ctr* ctr) {
   __shared__ int smem[20];
@@ -731,28 +731,29 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
     const int both = block_excl_scan((lt << 16) | eq, tot, smem);
     int lt_before = (both >> 16) + pre_lt;
     int eq_before = (both & 0xffff) + pre_eq;
+    // list position of each victim among this thread's eight slots, then the resident ids with all
+    // loads in flight (a thread rarely has more than one victim, but a dependent load per victim
+    // inside this loop made the pass latency-bound)
+    int idx[8];
+    int64_t vid8[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bool is_lt = mlt & (1u << j), is_eq = meq & (1u << j);
+      idx[j] = -1;
       if (is_lt || (is_eq && eq_before < r)) {
-        const int s = base + j;
-        const int idx = lt_before + (eq_before < r ? eq_before : r);
-        const int64_t id = slot_id[s];
-        if (idx < K) {                       // always true while hist mirrors the stamps
-          victim_slot[idx] = s;
-          victim_id[idx] = id;
-          uint32_t where;
-          if (index_find(index, hi, id, &where, ctr) >= 0) index[where].key = kTomb;
-          else ctr->err = 3;
-        } else {
-          ctr->err = 4;
-        }
+        idx[j] = lt_before + (eq_before < r ? eq_before : r);
+        if (idx[j] >= K) { idx[j] = -1; ctr->err = 4; }     // never while hist mirrors the stamps
       }
       lt_before += is_lt;
       eq_before += is_eq;
     }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) if (idx[j] >= 0) vid8[j] = slot_id[base + j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (idx[j] >= 0) { victim_slot[idx[j]] = base + j; victim_id[idx[j]] = vid8[j]; }
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);
+  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);   // deleted by the next pass
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -766,6 +767,7 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         int* __restrict__ cursor,
                                                         const int* __restrict__ tile_moff,
                                                         const int* __restrict__ victim_slot,
+                                                        const int64_t* __restrict__ victim_id,
                                                         int* __restrict__ slot_out,
                                                         int* __restrict__ miss_vids,
                                                         int64_t* __restrict__ slot_id, int* stamp,
@@ -774,6 +776,14 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
   __shared__ int smem[20];
   const int U = ctr->U, K = ctr->K, f = ctr->f_old;
   const int free_slots = C - f;
+  // the victims leave the index: one thread per victim, whole grid.  Inserts below may run before
+  // or after a given deletion: an insert only takes entries it has seen empty or deleted, and no
+  // victim is an id of this batch.
+  for (int k = blockIdx.x * 256 + (int)threadIdx.x; k < K; k += gridDim.x * 256) {
+    uint32_t where;
+    if (index_find(index, hi, victim_id[k], &where, ctr) >= 0) index[where].key = kTomb;
+    else ctr->err = 3;
+  }
   for (int tile = blockIdx.x; tile * kVidTile < U; tile += gridDim.x) {
     const int v = tile * kVidTile + (int)threadIdx.x;
     const bool miss = v < U && slot_out[v] == kMissMark;
