@@ -498,8 +498,12 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   if (hu < 64) hu = 64;                       // the batch table is empty between steps: any size works
   const int nchunk = (n + kPosChunk - 1) / kPosChunk;
   if (n > 0) {
-    hipLaunchKernelGGL(k_uniq_insert, dim3((n + kUniqChunk - 1) / kUniqChunk), dim3(256), 0, s,
-                       d_ids, n, c->V, c->utab, hu, c->hslot, c->n_invalid);
+    const int nub = (n + kUniqChunk - 1) / kUniqChunk, head = nub < kHeadBlocks ? nub : kHeadBlocks;
+    hipLaunchKernelGGL(k_uniq_insert, dim3(head), dim3(256), 0, s, d_ids, n, c->V, c->utab, hu,
+                       c->hslot, c->n_invalid, 0);
+    if (nub > head)
+      hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, s, d_ids, n, c->V, c->utab,
+                         hu, c->hslot, c->n_invalid, head);
     hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
                        c->blk_cnt, c->index, c->hi, prev->ctr);
   }
@@ -509,8 +513,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
     hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
                        c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt, c->index, c->hi,
                        c->slot_id, x->ctr);
-    hipLaunchKernelGGL(k_uniq_inverse, dim3(nchunk), dim3(256), 0, s, c->hslot, c->uvid, n,
-                       d_inverse, c->cnt);
+    hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s,
+                       c->hslot, c->uvid, n, d_inverse, c->cnt);
     if (d_offsets)
       hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
                          d_offsets, (int)n_bags, n, c->pos2bag);
@@ -532,7 +536,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
-    hipLaunchKernelGGL(k_scatter, dim3(nchunk), dim3(256), 0, s, d_inverse,
+    hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor,
                        x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff);
   HIPCHK(hipGetLastError());

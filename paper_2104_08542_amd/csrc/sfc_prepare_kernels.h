@@ -12,6 +12,8 @@ namespace sfc {
 
 constexpr int kPosChunk = 2048;   // positions (or slots) per block in the scan passes
 constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
+constexpr int kSortPer = 8;       // positions per thread in the count / group passes (16 measured slower)
+constexpr int kSortChunk = 256 * kSortPer;
 
 // ---------------------------------------------------------------------------------------------
 // VSI pass 1: insert every position's id into the batch table (open addressing, linear probing,
@@ -24,10 +26,16 @@ constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
 // comes first (the table entry of a key never changes once set, and a stale smallest-position
 // word can only be too large), and an atomic is issued only when the load has not already seen
 // the key / a small enough position.
+// The kernel is launched twice: the first kHeadBlocks blocks, then the rest.  When all blocks
+// start together they all find the table empty, and every block's copy of a frequent key goes
+// through the claim / re-read / minimum atomics on one address (thousands in a row, about 10 ns
+// each); after the head of the batch has been inserted the frequent keys are in the table with
+// a smaller position than any later block holds, and the plain load settles them.
 // hslot[p] = HBM table entry of position p; bit 31 marks the one position per (block, key) that
 // can still be the key's first appearance, so the later passes test only those.
 // ---------------------------------------------------------------------------------------------
 constexpr int kUniqChunk = 2048;   // positions per block
+constexpr int kHeadBlocks = 64;    // blocks of the first of the two launches
 constexpr int kLdsTab = 4096;      // LDS table entries per block
 constexpr unsigned kCandBit = 0x80000000u;
 
@@ -39,7 +47,7 @@ __device__ __forceinline__ T coherent_load(const T* p) {
 __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__ ids, int n,
                                                       int64_t V, UEntry* utab, uint32_t hu,
                                                       int* __restrict__ hslot,
-                                                      int* __restrict__ n_invalid) {
+                                                      int* __restrict__ n_invalid, int block0) {
   __shared__ int64_t lkey[kLdsTab];
   __shared__ int lval[kLdsTab];               // smallest position of the key in this block; later its HBM entry
   __shared__ unsigned short lst[kUniqChunk];  // occupied LDS entries, compacted
@@ -48,7 +56,7 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
   for (int i = threadIdx.x; i < kLdsTab; i += 256) { lkey[i] = kEmpty; lval[i] = kIntMax; }
   if (threadIdx.x < kUniqChunk / 32) cand[threadIdx.x] = 0;
   __syncthreads();
-  const int base = blockIdx.x * kUniqChunk;
+  const int base = (block0 + (int)blockIdx.x) * kUniqChunk;
   int ls[8];
   int64_t idv[8];
 #pragma unroll
@@ -298,17 +306,17 @@ __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hs
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
-  const int base = blockIdx.x * kPosChunk;
-  int hv[8], vv[8];
+  const int base = blockIdx.x * kSortChunk;
+  int hv[kSortPer], vv[kSortPer];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {          // eight loads in flight per level of indirection
+  for (int j = 0; j < kSortPer; ++j) {          // eight loads in flight per level of indirection
     const int p = base + j * 256 + (int)threadIdx.x;
     hv[j] = p < n ? (int)((unsigned)hslot[p] & ~kCandBit) : -1;
   }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) vv[j] = hv[j] >= 0 ? uvid[hv[j]] : -1;
+  for (int j = 0; j < kSortPer; ++j) vv[j] = hv[j] >= 0 ? uvid[hv[j]] : -1;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kSortPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     const int v = vv[j];
     if (v >= 0) {
@@ -350,27 +358,27 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
-  const int base = blockIdx.x * kPosChunk;
-  int vv[8], rr[8], sv[8], cv[8], pay[8];
+  const int base = blockIdx.x * kSortChunk;
+  int vv[kSortPer], rr[kSortPer], sv[kSortPer], cv[kSortPer], pay[kSortPer];
   // three levels of indirection, eight loads in flight at each: position -> vid -> slot / count
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kSortPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     vv[j] = p < n ? inverse[p] : -1;
     pay[j] = (p < n && pos2bag) ? pos2bag[p] : p;
   }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kSortPer; ++j) {
     sv[j] = vv[j] >= 0 ? slot[vv[j]] : -1;
     cv[j] = vv[j] >= kHotBins ? cnt[vv[j]] : 0;
   }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {          // cold ids: a single occurrence needs no atomic
+  for (int j = 0; j < kSortPer; ++j) {          // cold ids: a single occurrence needs no atomic
     rr[j] = 0;
     if (vv[j] >= kHotBins) rr[j] = cv[j] == 1 ? cursor[vv[j]] : atomicAdd(&cursor[vv[j]], 1);
   }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kSortPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     if (vv[j] < 0) continue;
     pos_slot[p] = sv[j] >= C ? sv[j] + boff : sv[j];   // row index for the forward gather
@@ -389,7 +397,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   }
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
+  for (int j = 0; j < kSortPer; ++j)
     if (vv[j] >= 0 && vv[j] < kHotBins)
       perm64[lh[vv[j]] + rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
 }
