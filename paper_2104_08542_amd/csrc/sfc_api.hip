@@ -106,6 +106,7 @@ struct sfc_cache {
   int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
   int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
   int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
+  int *cnt_rep = nullptr, *cur_rep = nullptr;   // [kHotRep, kHotBins] copies of both for the lowest virtual ids
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
   int* tile_reuse = nullptr;                    // [max_ids / kVidTile + 1] deleted index entries reused per tile
@@ -403,6 +404,8 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->tile_reuse, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->age_hist, (int64_t)kAgeBins))) goto bad;
     if ((rc = dalloc(c, &c->n_invalid, 1))) goto bad;
+    if ((rc = dalloc(c, &c->cnt_rep, (int64_t)kHotRep * kHotBins))) goto bad;
+    if ((rc = dalloc(c, &c->cur_rep, (int64_t)kHotRep * kHotBins))) goto bad;
     {
       const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;
       const int64_t nwmax = nw > 4104 ? nw : 4104;     // the stream never has more wavefronts
@@ -432,6 +435,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
     fill<int>(s, c->age_hist, (int64_t)kAgeBins, 0);
     fill<int>(s, c->n_invalid, 1, 0);
+    fill<int>(s, c->cnt_rep, (int64_t)kHotRep * kHotBins, 0);
     fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
@@ -514,14 +518,14 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                        c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt, c->index, c->hi,
                        c->slot_id, x->ctr);
     hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s,
-                       c->hslot, c->uvid, n, d_inverse, c->cnt);
+                       c->hslot, c->uvid, n, d_inverse, c->cnt, c->cnt_rep);
     if (d_offsets)
       hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
                          d_offsets, (int)n_bags, n, c->pos2bag);
   }
   const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
-                     c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt,
+                     c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt, c->cnt_rep,
                      c->tile_cnt, c->age_hist, x->ctr);
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
                      c->tile_reuse,
@@ -532,12 +536,13 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
                      c->tile_eq, x->victim_slot, x->victim_id, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);
-  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->tile_cnt,
+  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->cnt_rep,
+                     c->cur_rep, c->tile_cnt,
                      c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
-                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor,
+                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor, c->cur_rep,
                        x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;

@@ -299,10 +299,16 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
 // batch are (nearly all) among the lowest ones: those are counted in an LDS histogram per block
 // and flushed with one coalesced atomic per bin; the rest go to HBM atomics on distinct words.
 constexpr int kHotBins = 8192;
+// Every block adds its tally of a frequent id to one counter: a thousand atomics in a row on one
+// address (about 10 ns each).  The counters of the hot bins are therefore kept in kHotRep copies,
+// block b using copy b mod kHotRep; resolve folds the copies into cnt, the miss assignment turns
+// them into one group cursor per copy.
+constexpr int kHotRep = 32;
 
 __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hslot,
                                                        const int* __restrict__ uvid, int n,
-                                                       int* __restrict__ inverse, int* cnt) {
+                                                       int* __restrict__ inverse, int* cnt,
+                                                       int* cnt_rep) {
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
@@ -326,9 +332,10 @@ __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hs
     }
   }
   __syncthreads();
+  int* mine = cnt_rep + (blockIdx.x & (kHotRep - 1)) * kHotBins;
   for (int b = threadIdx.x; b < kHotBins; b += 256) {
     const int c = lh[b];
-    if (c) atomicAdd(&cnt[b], c);
+    if (c) atomicAdd(&mine[b], c);
   }
 }
 
@@ -352,6 +359,7 @@ __global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ off
 __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse,
                                                   const int* __restrict__ pos2bag, int n,
                                                   const int* __restrict__ cnt, int* cursor,
+                                                  int* cur_rep,
                                                   int64_t* __restrict__ perm64,
                                                   const int* __restrict__ slot,
                                                   int* __restrict__ pos_slot, int C, int boff) {
@@ -386,12 +394,13 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
     else perm64[rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
   }
   __syncthreads();
+  int* mine = cur_rep + (blockIdx.x & (kHotRep - 1)) * kHotBins;
   for (int b0 = threadIdx.x; b0 < kHotBins; b0 += 256 * 4) {
     int c[4], r[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) c[u] = lh[b0 + u * 256];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) r[u] = c[u] ? atomicAdd(&cursor[b0 + u * 256], c[u]) : 0;
+    for (int u = 0; u < 4; ++u) r[u] = c[u] ? atomicAdd(&mine[b0 + u * 256], c[u]) : 0;
 #pragma unroll
     for (int u = 0; u < 4; ++u) if (c[u]) lh[b0 + u * 256] = r[u];
   }
@@ -493,7 +502,8 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
                                                   int* stamp, int* hist, int t,
                                                   int* __restrict__ slot_out,
                                                   int* __restrict__ tile_miss,
-                                                  const int* __restrict__ cnt,
+                                                  int* __restrict__ cnt,
+                                                  const int* __restrict__ cnt_rep,
                                                   int* __restrict__ tile_cnt,
                                                   int* __restrict__ age_hist, Ctr* ctr) {
   __shared__ int smem[20];
@@ -512,7 +522,17 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
     for (int k = 0; k < 4; ++k) {
       const int v = (tile0 + k) * kVidTile + (int)threadIdx.x;
       hs[k] = -1; cc[k] = 0; id[k] = -1;
-      if (v < U) { hs[k] = vid_hslot[v]; cc[k] = cnt[v]; id[k] = unique_ids[v]; }
+      if (v < U) {
+        hs[k] = vid_hslot[v]; id[k] = unique_ids[v];
+        if (v < kHotBins) {                     // fold the copies of a hot bin
+          int c = 0;
+#pragma unroll
+          for (int r = 0; r < kHotRep; ++r) c += cnt_rep[r * kHotBins + v];
+          cnt[v] = c; cc[k] = c;
+        } else {
+          cc[k] = cnt[v];
+        }
+      }
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -771,6 +791,8 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict__ unique_ids,
                                                         const int* __restrict__ cnt,
+                                                        int* __restrict__ cnt_rep,
+                                                        int* __restrict__ cur_rep,
                                                         const int* __restrict__ tile_coff,
                                                         int* __restrict__ cursor,
                                                         const int* __restrict__ tile_moff,
@@ -799,6 +821,16 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
     // start of the group of virtual id v in perm64 = exclusive scan of cnt
     const int off = block_excl_scan(v < U ? cnt[v] : 0, tot, smem) + tile_coff[tile];
     if (v < U) cursor[v] = off;
+    if (v < U && v < kHotBins) {                // one cursor per copy of a hot bin; copies back to zero
+      int at = off;
+#pragma unroll
+      for (int r = 0; r < kHotRep; ++r) {
+        const int c = cnt_rep[r * kHotBins + v];
+        cur_rep[r * kHotBins + v] = at;
+        at += c;
+        cnt_rep[r * kHotBins + v] = 0;
+      }
+    }
     const int i = block_excl_scan(miss ? 1 : 0, tot, smem) + tile_moff[tile];
     bool reused = false;
     if (miss) {
