@@ -536,6 +536,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
                      c->tile_eq, x->victim_slot, x->victim_id, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);
+  hipLaunchKernelGGL(k_victim_unmap, dim3(gv), dim3(256), 0, s, x->victim_id, c->index, c->hi,
+                     x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->cnt_rep,
                      c->cur_rep, c->tile_cnt,
                      c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, c->slot_id,
@@ -703,7 +705,13 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out) {
   if (c->last_prepared < 0) return SFC_OK;
   Ctr h;
   HIPCHK(hipMemcpy(&h, c->ctx[c->last_prepared].ctr, sizeof h, hipMemcpyDeviceToHost));
-  if (h.err) return fail(SFC_EHIP, "cache index probe ran off its bound (index corrupt)");
+  if (h.err) {
+    // 1: a lookup walked the whole index, 2: so did an insert, 3: a victim was not in the index,
+    // 4: more victims than the recency histogram promised
+    char msg[96];
+    snprintf(msg, sizeof msg, "cache manager state is inconsistent (device check %d)", h.err);
+    return fail(SFC_EHIP, msg);
+  }
   const int64_t rowbytes = (int64_t)sizeof(float) * (c->D + c->S);
   h_out->n_unique = h.U; h_out->n_hit = h.n_hit; h_out->n_miss = h.M; h_out->n_evict = h.K;
   h_out->n_bypass = h.n_bypass; h_out->n_invalid = h.n_invalid;

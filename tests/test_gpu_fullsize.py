@@ -108,3 +108,47 @@ def test_low_locality_configuration_shape():
     assert pr.stats["n_bypass"] > 0          # 5e6 new ids per step against 8e5 slots
     p.finish()
     p.close()
+
+
+@pytest.mark.parametrize("lookahead", [0, 2])
+def test_long_run_keeps_every_resident_id_findable(lookahead):
+    """640 steps at the target batch size against a 2e6-row cache (about 1e5 victims per step, an
+    index rebuild every few dozen steps), no oracle beside it: the device-side consistency checks
+    must stay silent, and afterwards a batch made of resident ids must resolve to hits only."""
+    import torch
+    import paper_2104_08542_amd as sfc
+    w = si.WORKLOADS["c2"]
+    C = 2_000_000
+    if psutil.virtual_memory().available < 2 * w.vocab * w.dim * 4 + 8e9:
+        pytest.skip("needs the 1e8-row Host table")
+    dev = torch.device("cuda:0")
+    table = sfc.HostTable(w.vocab, w.dim)
+    table.acc[:] = 0.1
+    cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lookahead=lookahead, max_steps=2000)
+    out = torch.empty(w.n_bags, w.dim, device=dev)
+    g = w.batch_grads(0, dev)
+    t0 = time.time()
+    step = 0
+    for _ in range(lookahead):
+        cache.prepare(w.batch_ids(step, dev)[0]); cache.fetch_misses(); step += 1
+    for t in range(640):
+        ids = w.batch_ids(step, dev)[0]; step += 1
+        if lookahead:
+            cache.lookup(out); cache.prepare(ids); cache.fetch_misses(); cache.backward_update(g)
+        else:
+            cache.prepare(ids); cache.fetch_misses(); cache.lookup(out); cache.backward_update(g)
+        if t % 80 == 79:
+            st = cache.stats()                       # raises if a device check has fired
+            assert st["n_evict"] > 50_000
+    for _ in range(lookahead):
+        cache.lookup(out); cache.backward_update(g)
+    _say("640 steps at lookahead %d in %.0fs" % (lookahead, time.time() - t0))
+    sid, _ = cache.state()
+    res = sid[sid >= 0]
+    assert res.size == C and np.unique(res).size == C
+    probe = torch.from_numpy(np.random.default_rng(0).choice(res, 1_000_000, replace=False)).to(dev)
+    for _ in range(lookahead + 1):                   # fills every step context
+        cache.prepare(probe); cache.fetch_misses()
+        st = cache.stats()
+        assert st["n_miss"] == 0 and st["n_hit"] == st["n_unique"] == 1_000_000
+    cache.close(); table.free()

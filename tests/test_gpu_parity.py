@@ -249,3 +249,22 @@ def test_pipelined_multihot(lookahead):
         bs.append((si.zipf_ids(int(off[-1]), 1.1, V, 79, t).numpy(), si.grads(nb, D, 79, t).numpy(), off))
     p.run_pipelined(bs, False)
     p.close()
+
+
+@pytest.mark.parametrize("lookahead", [0, 2])
+def test_many_rebuilds_with_many_victims(lookahead):
+    # a cache much smaller than the id range with thousands of victims per step: the index fills
+    # with deleted entries and is rebuilt every few steps, also while other steps are in flight
+    V, D, n, C = 400_000, 4, 30_000, 40_000
+    p = Pair(V, D, C=C, max_ids=n, lookahead=lookahead)
+    bs = [(si.zipf_ids(n, 1.05, V, 77, t).numpy(), si.grads(n, D, 77, t).numpy(), None) for t in range(60)]
+    if lookahead:
+        expect = p.run_pipelined(bs, False)
+        assert sum(pr.stats["n_evict"] for pr, _ in expect) > 5 * C
+    else:
+        ev = 0
+        for ids, g, _ in bs:
+            ev += p.step(ids, g, check_common=False, check_rows=False).stats["n_evict"]
+        assert ev > 5 * C
+        p.finish()
+    p.close()
