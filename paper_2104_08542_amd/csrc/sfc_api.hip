@@ -67,6 +67,8 @@ struct StepCtx {
   int* pos_slot = nullptr;            // [max_ids] cache row of each position
   int* victim_slot = nullptr;         // [max_ids]
   int64_t* victim_id = nullptr;       // [max_ids]
+  int* miss_row = nullptr;            // [max_ids] cache row of each miss (bypass rows already offset)
+  int64_t* miss_id = nullptr;         // [max_ids] id of each miss
   int boff = 0;                       // bypass slot C + j lives at row C + boff + j
   hipEvent_t ev_prepared = nullptr;   // the step's prepare kernels have run
   hipEvent_t ev_fetched = nullptr;    // the side-stream launch of the step's Host copies has run
@@ -213,10 +215,10 @@ int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
   if (s != c->prep) HIPCHK(hipStreamWaitEvent(s, x->ev_prepared, 0));
   if ((rc = prof_begin(c, P_FETCH, s, &ep))) return rc;
   ep.extra = main_variant != 0;          // the second launch of a step: same call
-  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * 2 * c->d4, 256, kSwapBlocks)), dim3(256), 0, s,
-                     x->d_miss, x->d_unique, x->d_slot, x->victim_id, (float4*)c->cw,
-                     (float4*)c->ca, c->host, c->d4, c->s4, (int)c->C, x->boff, x->ctr, x->older1,
-                     x->older2, x->chain, main_variant);
+  hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * (c->d4 + c->s4), 256, kSwapBlocks)),
+                     dim3(256), 0, s,
+                     x->miss_row, x->miss_id, x->victim_id, (float4*)c->cw, (float4*)c->ca, c->host,
+                     c->d4, c->s4, x->ctr, x->older1, x->older2, x->chain, main_variant);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
   if (main_variant) x->main_pending = false;
@@ -420,6 +422,8 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       if ((rc = dalloc(c, &x->pos_slot, c->max_ids))) goto bad;
       if ((rc = dalloc(c, &x->victim_slot, c->max_ids))) goto bad;
       if ((rc = dalloc(c, &x->victim_id, c->max_ids))) goto bad;
+      if ((rc = dalloc(c, &x->miss_row, c->max_ids))) goto bad;
+      if ((rc = dalloc(c, &x->miss_id, c->max_ids))) goto bad;
       x->boff = (int)(k * c->max_ids);
       if ((e = hipEventCreateWithFlags(&x->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
           (e = hipEventCreateWithFlags(&x->ev_fetched, hipEventDisableTiming)) != hipSuccess) {
@@ -540,7 +544,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->cnt_rep,
                      c->cur_rep, c->tile_cnt,
-                     c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, c->slot_id,
+                     c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, x->miss_row,
+                     x->miss_id, x->boff, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,

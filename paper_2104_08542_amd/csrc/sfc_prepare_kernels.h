@@ -817,6 +817,8 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         const int64_t* __restrict__ victim_id,
                                                         int* __restrict__ slot_out,
                                                         int* __restrict__ miss_vids,
+                                                        int* __restrict__ miss_row,
+                                                        int64_t* __restrict__ miss_id, int boff,
                                                         int64_t* __restrict__ slot_id, int* stamp,
                                                         IdxEntry* index, uint32_t hi, int t, int C,
                                                         int* __restrict__ tile_reuse, Ctr* ctr) {
@@ -849,8 +851,10 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
       else if (i - K < free_slots) s = f + (i - K);
       else s = C + (i - K - free_slots);
       slot_out[v] = s;
+      const int64_t id = unique_ids[v];
+      miss_row[i] = s >= C ? s + boff : s;      // for the Host copies: cache row and Host row per miss
+      miss_id[i] = id;
       if (s < C) {
-        const int64_t id = unique_ids[v];
         slot_id[s] = id;
         stamp[s] = t;
         reused = index_insert(index, hi, id, s, ctr);

@@ -46,14 +46,12 @@ struct HostRows {
   int64_t has4;   // row stride of a in float4
 };
 
-__global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_vids,
-                                                    const int64_t* __restrict__ unique_ids,
-                                                    const int* __restrict__ slot,
+__global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_row,
+                                                    const int64_t* __restrict__ miss_id,
                                                     const int64_t* __restrict__ victim_id,
                                                     float4* __restrict__ cw, float4* __restrict__ ca,
-                                                    HostRows h, int d4, int s4, int C, int boff,
-                                                    Ctr* ctr, const Ctr* older1,
-                                                    const Ctr* older2, int chain,
+                                                    HostRows h, int d4, int s4, Ctr* ctr,
+                                                    const Ctr* older1, const Ctr* older2, int chain,
                                                     int main_variant) {
   const bool on_main = (older1 && older1->n_bypass != 0) || (older2 && older2->n_bypass != 0) ||
                        (chain && older1 && older1->fetch_on_main != 0);
@@ -62,7 +60,18 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
   const int K = ctr->K;
   const int w2 = d4 + s4;                   // chunks of a row and of its optimizer state
   const int64_t total = (int64_t)ctr->M * w2;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  // A thread's chunks are a serial chain, and with few blocks (see the launch) the chain is long:
+  // the list entries of the next chunk are fetched while this chunk's Host read is in flight, so
+  // that the chain is one Host round trip per chunk and nothing that waits on HBM.
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int row = 0;
+  int64_t id = 0, vic = 0;
+  if (i < total) {
+    const int k = (int)(i / w2);
+    row = miss_row[k]; id = miss_id[k]; vic = k < K ? victim_id[k] : -1;
+  }
+  while (i < total) {
     const int k = (int)(i / w2);
     int c = (int)(i - (int64_t)k * w2);
     const bool acc = c >= d4;
@@ -71,13 +80,17 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
     float4* cb = acc ? ca : cw;
     const int64_t hst = acc ? h.has4 : h.hs4;
     const int cst = acc ? s4 : d4;
-    const int v = miss_vids[k];
-    int row = slot[v];
-    if (row >= C) row += boff;              // bypass rows of this step's own region
-    const int64_t src = unique_ids[v] * hst + c, dst = (int64_t)row * cst + c;
-    const float4 nv = hb[src];
-    if (k < K) hb[victim_id[k] * hst + c] = cb[dst];
+    const int64_t dst = (int64_t)row * cst + c;
+    const float4 nv = hb[id * hst + c];
+    const int64_t vnow = vic;
+    const int64_t inext = i + stride;
+    if (inext < total) {
+      const int kn = (int)(inext / w2);
+      row = miss_row[kn]; id = miss_id[kn]; vic = kn < K ? victim_id[kn] : -1;
+    }
+    if (vnow >= 0) hb[vnow * hst + c] = cb[dst];
     cb[dst] = nv;
+    i = inext;
   }
 }
 
