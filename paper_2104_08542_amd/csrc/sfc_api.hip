@@ -544,7 +544,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->cnt_rep,
                      c->cur_rep, c->tile_cnt,
-                     c->cursor, c->tile_miss, x->victim_slot, x->victim_id, d_slot, d_miss_vids, x->miss_row,
+                     c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)

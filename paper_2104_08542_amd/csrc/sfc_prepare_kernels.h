@@ -784,11 +784,6 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
   if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);   // deleted by the next pass
 }
 
-// ---------------------------------------------------------------------------------------------
-// Assignment: the i-th miss in virtual-id order takes the i-th slot of (victims u free) in
-// ascending slot order: victims (all below the watermark) first, then never-used slots from the
-// watermark up, then transient bypass rows C + j.
-// ---------------------------------------------------------------------------------------------
 // The victims leave the index: one thread per victim.  A kernel of its own, before the inserts:
 // with deletions and inserts in one kernel a resident id went missing from the index about once in
 // a hundred steps at the target size (plain stores and memory-side atomics on neighbouring
@@ -806,6 +801,11 @@ __global__ __launch_bounds__(256) void k_victim_unmap(const int64_t* __restrict_
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Assignment: the i-th miss in virtual-id order takes the i-th slot of (victims u free) in
+// ascending slot order: victims (all below the watermark) first, then never-used slots from the
+// watermark up, then transient bypass rows C + j.
+// ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict__ unique_ids,
                                                         const int* __restrict__ cnt,
                                                         int* __restrict__ cnt_rep,
@@ -814,7 +814,6 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         int* __restrict__ cursor,
                                                         const int* __restrict__ tile_moff,
                                                         const int* __restrict__ victim_slot,
-                                                        const int64_t* __restrict__ victim_id,
                                                         int* __restrict__ slot_out,
                                                         int* __restrict__ miss_vids,
                                                         int* __restrict__ miss_row,
