@@ -614,33 +614,47 @@ __global__ __launch_bounds__(256) void k_rowwise_adagrad_rows(const float4* __re
     }
     return;
   }
-  // every lane of a wavefront runs the same number of iterations: the shuffles stay convergent
-  const int64_t rounds = (total + stride - 1) / stride;
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  for (int64_t it = 0; it < rounds; ++it, i += stride) {
-    const bool live = i < total;
-    const int vrow = live ? (int)(i / d4) : 0;
-    const int c = live ? (int)(i % d4) : 0;
-    const int sl = live ? slot[vrow] : -1;
-    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (live) g = common[i];
-    float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
-    for (int d = 1; d < d4; d <<= 1) ss += __shfl_xor(ss, d, kWave);
-    if (sl < 0) continue;
-    const int64_t row = sl >= C ? sl + boff : sl;
-    float4 st = cs[row];
-    float4 w = cw[row * d4 + c];
-    const float acc = st.x + ss * inv_d;
-    const float den = sqrtf(acc) + eps;
-    w.x = w.x - lr * g.x / den; w.y = w.y - lr * g.y / den;
-    w.z = w.z - lr * g.z / den; w.w = w.w - lr * g.w / den;
-    cw[row * d4 + c] = w;
-    st.x = acc;
-    if (c == 0) cs[row] = st;
-    if (sl >= C) {
-      const int64_t id = unique_ids[vrow];
-      h.w[id * h.hs4 + c] = w;
-      if (c == 0) h.a[id * h.has4] = st;
+  // every lane of a wavefront runs the same number of iterations: the shuffles stay convergent.
+  // Four rows per thread in flight at each level (slot + gradient, then state + weights).
+  const int64_t rounds = (total + 4 * stride - 1) / (4 * stride);
+  int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (int64_t it = 0; it < rounds; ++it, i0 += 4 * stride) {
+    int vrow[4], c[4], sl[4];
+    float4 g[4], st[4], w[4];
+    float ss[4];
+    int64_t row[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + u * stride;
+      const bool live = i < total;
+      vrow[u] = live ? (int)(i / d4) : 0;
+      c[u] = live ? (int)(i % d4) : 0;
+      sl[u] = live ? slot[vrow[u]] : -1;
+      g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (live) g[u] = common[i];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ss[u] = g[u].x * g[u].x + g[u].y * g[u].y + g[u].z * g[u].z + g[u].w * g[u].w;
+      for (int d = 1; d < d4; d <<= 1) ss[u] += __shfl_xor(ss[u], d, kWave);
+      row[u] = sl[u] >= C ? sl[u] + boff : sl[u];
+      if (sl[u] >= 0) { st[u] = cs[row[u]]; w[u] = cw[row[u] * d4 + c[u]]; }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (sl[u] < 0) continue;
+      const float acc = st[u].x + ss[u] * inv_d;
+      const float den = sqrtf(acc) + eps;
+      w[u].x = w[u].x - lr * g[u].x / den; w[u].y = w[u].y - lr * g[u].y / den;
+      w[u].z = w[u].z - lr * g[u].z / den; w[u].w = w[u].w - lr * g[u].w / den;
+      cw[row[u] * d4 + c[u]] = w[u];
+      st[u].x = acc;
+      if (c[u] == 0) cs[row[u]] = st[u];
+      if (sl[u] >= C) {
+        const int64_t id = unique_ids[vrow[u]];
+        h.w[id * h.hs4 + c[u]] = w[u];
+        if (c[u] == 0) h.a[id * h.has4] = st[u];
+      }
     }
   }
 }
