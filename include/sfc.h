@@ -1,7 +1,7 @@
 /*
  * sfc.h - C ABI of the one-GPU sparse-embedding hot path of ScaleFreeCTR
  * (Virtual Sparse Id + MixCache + gather + gradient segment-sum + sparse
- * Adagrad), implemented with HIP kernels for gfx950 (MI355X).
+ * optimizer update), implemented with HIP kernels for gfx950 (MI355X).
  *
  * One training step is four calls, in this order (with lookahead = L > 0 the first two of step t+L may
  * precede the last of step t; sfc_lookup, sfc_segment_sum and sfc_backward_update always act on
@@ -12,13 +12,13 @@
  *     sfc_prepare          lines 3-4   ids -> global_id / virtual_id, hit / miss / victims, slots
  *     sfc_fetch_misses     lines 5-6   victims cache->Host, missed rows Host->cache (side stream)
  *     sfc_lookup           lines 9,11  [bags, dim] model input from the cached rows
- *     sfc_backward_update  line 14     segment-sum of the gradients per virtual id + Adagrad
+ *     sfc_backward_update  line 14     segment-sum of the gradients per virtual id + optimizer update
  *
  * Conventions
  *   - Every function returns 0 (SFC_OK) or a negative SFC_E* code; nothing throws or aborts.
  *     sfc_last_error() gives a text for the most recent failure on the calling thread.
  *   - Pointers named d_* are DEVICE memory owned by the caller; pointers named h_* are HOST
- *     memory owned by the caller.  The library owns the cache rows, the accumulators, the
+ *     memory owned by the caller.  The library owns the cache rows, their optimizer state, the
  *     cache index and all scratch.  Buffers handed to sfc_prepare are used by the later calls
  *     of the same step and must stay alive and unmodified until sfc_backward_update (or the
  *     next sfc_prepare) has completed on the stream.
@@ -153,9 +153,12 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                 int32_t* d_miss_vids);
 
 /*
- * Step 2 (Algorithm 1 lines 5-6): on the side stream, after the prepare of this step, first
- * write every victim row and accumulator back to the Host table, then copy every missed row and
- * accumulator from the Host table into its slot.  The main stream is made to wait for both.
+ * Step 2 (Algorithm 1 lines 5-6): on the side stream, after the prepare of this step, write every
+ * victim row and its optimizer state back to the Host table and copy every missed row and its
+ * state from the Host table into its slot (a victim's row is read before its slot is
+ * overwritten).  The main stream is made to wait for it before it touches the step's rows.
+ * With lookahead > 0 the copies run behind the updates of older steps still in flight whenever
+ * one of those had bypass rows (their rows reach the Host table only with the update).
  */
 int sfc_fetch_misses(sfc_cache* c);
 
