@@ -9,8 +9,7 @@ LIB = os.path.join(HERE, "libsfc.so")
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-    "-munsafe-fp-atomics",          # hardware fp64 atomic add for the gradient scratch
-    "-ffp-contract=off",            # Adagrad arithmetic rounds like the plain formula
+    "-ffp-contract=off",            # optimizer arithmetic rounds like the plain formulas
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
@@ -27,6 +26,22 @@ def build(verbose=False):
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(HERE, "examples", "abi_client.cpp")
+EXAMPLE_BIN = os.path.join(HERE, "examples", "abi_client")
+
+
+def build_example(verbose=False):
+    """The plain C++ client of the C ABI (no torch): links libsfc.so by path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "-ffp-contract=off", "--offload-arch=gfx950", EXAMPLE_SRC, "-o", EXAMPLE_BIN,
+           "-L" + HERE, "-lsfc", "-Wl,-rpath,$ORIGIN/.."]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     build(verbose=True)
+    build_example(verbose=True)
     print(LIB)
