@@ -410,7 +410,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->cur_rep, (int64_t)kHotRep * kHotBins))) goto bad;
     {
       const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;
-      const int64_t nwmax = nw > 4104 ? nw : 4104;     // the stream never has more wavefronts
+      const int64_t nwmax = nw > kSegTargetWaves + 8 ? nw : kSegTargetWaves + 8;
       if ((rc = dalloc(c, &c->bp, 2 * nwmax * c->D))) goto bad;
       if ((rc = dalloc(c, &c->bp_vid, 2 * nwmax))) goto bad;
     }

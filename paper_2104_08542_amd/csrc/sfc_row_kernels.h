@@ -217,14 +217,17 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 #define SFC_SEG_CHUNK 4
 #endif
 constexpr int kSegChunk = SFC_SEG_CHUNK;        // entries per group per loop iteration
+// the stream never has more wavefronts than this: 48 per compute unit measured best at the target
+// size (16: stream 82 us + finish 10; 48: 75 + 14; the finish pass grows with the number of blocks)
+constexpr int kSegTargetWaves = 256 * 48;
 
 struct SegGeom { int G, L, waves; };
-// L is chosen so that the stream has about 16 wavefronts per compute unit, never below 32 entries.
+// L is chosen so that the stream has about kSegTargetWaves wavefronts, never below 32 entries.
 inline SegGeom seg_geom(int D, int64_t n) {
   SegGeom g;
   g.G = 64 / (D / 4);
   if (g.G < 1) g.G = 1;
-  const int64_t target_waves = 256 * 16;
+  const int64_t target_waves = kSegTargetWaves;
   int64_t L = (n + g.G * target_waves - 1) / (g.G * target_waves);
   if (L < 32) L = 32;
   L = (L + kSegChunk - 1) / kSegChunk * kSegChunk;
