@@ -385,13 +385,14 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
     rr[j] = 0;
     if (vv[j] >= kHotBins) rr[j] = cv[j] == 1 ? cursor[vv[j]] : atomicAdd(&cursor[vv[j]], 1);
   }
+  // the cold ids' cursors are on their way (returning atomics, microseconds each); the hot ids'
+  // ranks come from LDS meanwhile, and every group entry is written at the end
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     if (vv[j] < 0) continue;
     pos_slot[p] = sv[j] >= C ? sv[j] + boff : sv[j];   // row index for the forward gather
     if (vv[j] < kHotBins) rr[j] = atomicAdd(&lh[vv[j]], 1);
-    else perm64[rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
   }
   __syncthreads();
   int* mine = cur_rep + (blockIdx.x & (kHotRep - 1)) * kHotBins;
@@ -407,8 +408,10 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j)
-    if (vv[j] >= 0 && vv[j] < kHotBins)
-      perm64[lh[vv[j]] + rr[j]] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
+    if (vv[j] >= 0) {
+      const int at = vv[j] < kHotBins ? lh[vv[j]] + rr[j] : rr[j];
+      perm64[at] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
