@@ -13,9 +13,10 @@ BIN = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "paper_2104_08542_amd", "examples", "abi_client")
 
 
-def test_plain_cpp_client_trains_through_the_c_abi():
+@pytest.mark.parametrize("lookahead", [0, 1, 2])
+def test_plain_cpp_client_trains_through_the_c_abi(lookahead):
     assert os.path.exists(BIN), "examples/abi_client is not built: run python paper_2104_08542_amd/build.py"
-    r = subprocess.run([BIN], capture_output=True, text=True, timeout=120)
+    r = subprocess.run([BIN, str(lookahead)], capture_output=True, text=True, timeout=120)
     print(r.stdout, r.stderr)
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
-    assert "OK: 0 mismatches" in r.stdout
+    assert "OK: lookahead %d, 0 mismatches" % lookahead in r.stdout
