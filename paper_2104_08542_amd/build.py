@@ -38,6 +38,12 @@ def build_example(verbose=False):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    # the access-pattern ceilings that the kernel durations are read against
+    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", os.path.join(HERE, "examples", "hbm_ceilings.hip"),
+           "-o", os.path.join(HERE, "examples", "hbm_ceilings")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
     return EXAMPLE_BIN
 
 
