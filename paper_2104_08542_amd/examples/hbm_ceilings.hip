@@ -65,6 +65,19 @@ __global__ __launch_bounds__(256) void k_gather(const float4* __restrict__ a, si
   }
   if (s == 12345.678f) *sink = s;
 }
+// the mirror image: rows read in order, written to pseudo-random places (each row once)
+__global__ __launch_bounds__(256) void k_scatter_rows(const float4* __restrict__ a, float4* __restrict__ b, size_t rows,
+                                                      int d4, size_t chunks, uint64_t mul) {
+  const size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const size_t j = i + k * 256;
+    if (j < chunks) {
+      const size_t r = ((j / d4) * mul) % rows;          // a bijection for odd mul and rows a power of two
+      __builtin_nontemporal_store(*(const vf4*)&a[j], (vf4*)&b[r * d4 + j % d4]);
+    }
+  }
+}
 __global__ __launch_bounds__(256) void k_atomic(int* c, size_t words, size_t n, int same) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) atomicAdd(&c[same ? 0 : mix(i) % words], 1);
@@ -105,6 +118,11 @@ int main() {
     const size_t rows = n / d4;
     ms = best_ms([&] { hipLaunchKernelGGL(k_gather, grd, blk, 0, 0, a, rows, d4, n, sink); });
     printf("random gather of %3d-byte rows     %7.1f us  %6.2f TB/s\n", d4 * 16, ms * 1e3, bytes / ms / 1e9);
+  }
+  for (int d4 : {8}) {
+    const size_t rows = n / d4;
+    ms = best_ms([&] { hipLaunchKernelGGL(k_scatter_rows, grd, blk, 0, 0, a, b, rows, d4, n, 2654435761ull); });
+    printf("copy with random %3d-byte row writes %5.1f us  %6.2f TB/s (read + written)\n", d4 * 16, ms * 1e3, 2.0 * bytes / ms / 1e9);
   }
   int* c = (int*)b;
   const size_t na = (size_t)1 << 24;
