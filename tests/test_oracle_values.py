@@ -101,7 +101,7 @@ def test_adagrad_one_step_closed_form():
 
 
 @pytest.mark.parametrize("C,lookahead,multihot", [(0, 0, False), (7, 0, False), (64, 0, False),
-                                                  (64, 1, False), (1000, 0, False),
+                                                  (64, 1, False), (64, 2, False), (1000, 0, False),
                                                   (40, 0, True), (1000, 0, True)])
 def test_cache_is_transparent(C, lookahead, multihot):
     """Training through the cache equals training a plain table (consistency of Host and
@@ -130,7 +130,7 @@ def test_results_do_not_depend_on_capacity():
     """The cache only moves bytes: final tables are bit-identical for every capacity."""
     V, D, steps = 300, 4, 10
     finals = []
-    for C, la in [(0, 0), (5, 0), (50, 1), (300, 0)]:
+    for C, la in [(0, 0), (5, 0), (50, 1), (50, 2), (300, 0)]:
         w, a = make_table(V, D)
         o = Oracle(C, D, w, a, lookahead=la)
         for t in range(steps):
