@@ -152,3 +152,66 @@ def test_long_run_keeps_every_resident_id_findable(lookahead):
         st = cache.stats()
         assert st["n_miss"] == 0 and st["n_hit"] == st["n_unique"] == 1_000_000
     cache.close(); table.free()
+
+
+def test_host_row_offsets_beyond_32_bits():
+    """A 1e8-row Host table of dim 64 (51 GB pinned, the largest this box pins in one piece): Host
+    row offsets beyond 2^31 sixteen-byte chunks and 2^32 bytes.  No oracle beside it (it would need
+    a second table): the rows of the batch are planted on the host, and every output is checked
+    against numpy and the planted values.  (Ids beyond 2^31 would need a table of more than 2^31
+    rows, which cannot be pinned here.)"""
+    import torch
+    import paper_2104_08542_amd as sfc
+    V, D, n, C = 100_000_000, 64, 20_000, 6_000
+    need = V * 2 * D * 4 + 8e9
+    if psutil.virtual_memory().available < need:
+        pytest.skip("needs %.0f GB of free host memory" % (need / 1e9))
+    t0 = time.time()
+    dev = torch.device("cuda:0")
+    try:
+        table = sfc.HostTable(V, D)
+    except sfc.SfcError as e:
+        pytest.skip("cannot pin the table on this box: %s" % e)
+    _say("1e8 x 64 table pinned after %.0fs" % (time.time() - t0))
+    cache = sfc.Cache(table, C, n)
+    rng = np.random.default_rng(3)
+    planted = {}
+    for t in range(3):
+        ids = rng.integers(V // 2, V, size=n, dtype=np.int64)  # upper half: offsets beyond 2^31 chunks
+        ids[:50] = V - 1 - np.arange(50)                      # the very end of the table
+        ids[50:60] = [-7, V, V + 123, 2**40, -1, V, V, -2, 2**62, V + 1]   # outside [0, V): null entry
+        ok = (ids >= 0) & (ids < V)
+        for i in np.unique(ids[ok]):                          # plant weights / accumulators of new rows
+            if int(i) not in planted:
+                w = (np.arange(D) + (int(i) % 1000) * 1e-3).astype(np.float32)
+                table.w[i] = w; table.acc[i] = 0.1
+                planted[int(i)] = (w.copy(), np.full(D, 0.1, np.float32))
+        d_ids = torch.from_numpy(ids).to(dev)
+        g = np.full((n, D), 0.5, np.float32)
+        cache.prepare(d_ids); cache.fetch_misses()
+        out = cache.lookup().cpu().numpy()
+        st = cache.stats()
+        U = st["n_unique"]
+        uniq = cache.unique_ids[:U].cpu().numpy()
+        inv = cache.inverse[:n].cpu().numpy()
+        canon = np.where(ok, ids, -1)
+        assert np.array_equal(uniq[inv], canon)
+        first = np.unique(canon, return_index=True)[1]
+        assert np.array_equal(uniq, canon[np.sort(first)])    # first-appearance order
+        assert st["n_invalid"] == int((~ok).sum())
+        exp = np.stack([planted[int(i)][0] if 0 <= i < V else np.zeros(D, np.float32) for i in ids])
+        assert np.array_equal(out, exp), "lookup rows"
+        cache.backward_update(torch.from_numpy(g).to(dev))
+        # host-side Adagrad on the planted copies: one update per id from the summed gradient
+        cnt = dict(zip(*np.unique(ids[ok], return_counts=True)))
+        for i, c in cnt.items():
+            w, a = planted[int(i)]
+            gs = np.float32(0.5 * c)
+            a += gs * gs
+            w -= np.float32(0.01) * gs / (np.sqrt(a) + np.float32(1e-8))
+        _say("step %d with ids up to %d: U=%d miss=%d evict=%d bypass=%d" % (
+            t, ids[ok].max(), U, st["n_miss"], st["n_evict"], st["n_bypass"]))
+    cache.flush()
+    for i, (w, a) in planted.items():
+        assert np.allclose(table.w[i], w, rtol=1e-5, atol=1e-6) and np.allclose(table.acc[i], a, rtol=1e-5, atol=1e-6)
+    cache.close(); table.free()
