@@ -21,8 +21,8 @@ constexpr int kSortChunk = 256 * kSortPer;
 //
 // Same-address atomics serialise at the memory side (about 10 ns each on this chip), and the
 // hottest id of a power-law batch owns a fifth of all positions.  So each block first
-// deduplicates its 2048 positions in an LDS table (key -> smallest position in the block) and
-// only the distinct keys of the block go to HBM, four per thread in flight.  There a plain load
+// deduplicates its kUniqChunk positions in an LDS table (key -> smallest position in the block) and
+// only the distinct keys of the block go to HBM, up to four per thread in flight.  There a plain load
 // comes first (the table entry of a key never changes once set, and a stale smallest-position
 // word can only be too large), and an atomic is issued only when the load has not already seen
 // the key / a small enough position.
@@ -34,9 +34,11 @@ constexpr int kSortChunk = 256 * kSortPer;
 // hslot[p] = HBM table entry of position p; bit 31 marks the one position per (block, key) that
 // can still be the key's first appearance, so the later passes test only those.
 // ---------------------------------------------------------------------------------------------
-constexpr int kUniqChunk = 2048;   // positions per block
+constexpr int kUniqChunk = 512;    // positions per block (2048 with its 53 KB of LDS left 12 wavefronts per compute unit: 20 us slower)
+constexpr int kUniqPer = kUniqChunk / 256;
+constexpr int kLdsPer = 2 * kUniqChunk / 256;
 constexpr int kHeadBlocks = 64;    // blocks of the first of the two launches
-constexpr int kLdsTab = 4096;      // LDS table entries per block
+constexpr int kLdsTab = 2 * kUniqChunk;      // LDS table entries per block
 constexpr unsigned kCandBit = 0x80000000u;
 
 template <typename T>
@@ -57,15 +59,15 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
   if (threadIdx.x < kUniqChunk / 32) cand[threadIdx.x] = 0;
   __syncthreads();
   const int base = (block0 + (int)blockIdx.x) * kUniqChunk;
-  int ls[8];
-  int64_t idv[8];
+  int ls[kUniqPer];
+  int64_t idv[kUniqPer];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {          // all eight loads in flight before the LDS work starts
+  for (int j = 0; j < kUniqPer; ++j) {      // all loads in flight before the LDS work starts
     const int p = base + j * 256 + (int)threadIdx.x;
     idv[j] = p < n ? ids[p] : 0;
   }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kUniqPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     bool invalid = false;
     ls[j] = 0;
@@ -95,12 +97,12 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
   {
     unsigned occ = 0;
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
-      if (lkey[threadIdx.x * 16 + k] != kEmpty) occ |= 1u << k;
+    for (int k = 0; k < kLdsPer; ++k)
+      if (lkey[threadIdx.x * kLdsPer + k] != kEmpty) occ |= 1u << k;
     int at = block_excl_scan(__popc(occ), nocc, smem);
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
-      if (occ & (1u << k)) lst[at++] = (unsigned short)(threadIdx.x * 16 + k);
+    for (int k = 0; k < kLdsPer; ++k)
+      if (occ & (1u << k)) lst[at++] = (unsigned short)(threadIdx.x * kLdsPer + k);
   }
   __syncthreads();
   // distinct keys of the block -> HBM table, four per thread in flight; one 16-byte load brings
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
   }
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
+  for (int j = 0; j < kUniqPer; ++j) {
     const int q = j * 256 + (int)threadIdx.x;
     const int p = base + q;
     if (p < n) {
