@@ -291,8 +291,10 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
   // per wavefront: [2G slots][D] doubles (2*G*D <= 512) and the slots' vids
   __shared__ double part[4][512];
   __shared__ int pvid[4][128];
-  __shared__ double wpart[8 * 256];     // [4 wavefronts][2][D]
   __shared__ int wvid[8];
+  // [4 wavefronts][2][D] (8 * D <= 2048 doubles): reuses part once every wavefront has chained its
+  // own slots, which keeps the block at 18 KB of LDS and the kernel register-limited
+  double* const wpart = &part[0][0];
   const int lane = lane_id(), wib = (int)(threadIdx.x >> 6);
   const int wave = (int)blockIdx.x * 4 + wib;
   const int g = lane / d4, c4 = lane - g * d4;
@@ -380,10 +382,14 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  int wbv0 = -1, wbv1 = -1;
+  D4 wb0, wb1;
+  d4_zero(wb0); d4_zero(wb1);
+  if (lane < d4) chain_slots(2 * G, pvid[wib], part[wib], D, d4, c4, common, wbv0, wb0, wbv1, wb1);
+  __syncthreads();                       // every wavefront has read its part of `part`
   if (lane < d4) {
-    int bv0, bv1;
-    D4 b0, b1;
-    chain_slots(2 * G, pvid[wib], part[wib], D, d4, c4, common, bv0, b0, bv1, b1);
+    const int bv0 = wbv0, bv1 = wbv1;
+    const D4 b0 = wb0, b1 = wb1;
     // the wavefront's own head / tail become slots 2*wib, 2*wib+1 of the block's chain
     double* o0 = &wpart[(2 * wib) * D + 4 * c4];
     o0[0] = b0.x; o0[1] = b0.y; o0[2] = b0.z; o0[3] = b0.w;
