@@ -116,9 +116,12 @@ def main():
         for i, b in enumerate(batches):
             g = grads[(k0 + i) % 4]
             if args.lookahead and overlap:
-                cache.lookup(out)
+                # prepare first: it waits for what the main stream has been given so far, and
+                # issued here that is the previous update (whose context it reuses), not this
+                # step's lookup
                 cache.prepare(b[0], b[1])
                 cache.fetch_misses()
+                cache.lookup(out)
                 cache.backward_update(g)
             elif args.lookahead:
                 # same calls, same kernels, but the next step's prepare is issued after this
