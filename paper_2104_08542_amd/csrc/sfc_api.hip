@@ -522,7 +522,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                        c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt, c->index, c->hi,
                        c->slot_id, x->ctr);
     hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s,
-                       c->hslot, c->uvid, n, d_inverse, c->cnt, c->cnt_rep);
+                       c->hslot, c->uvid, n, d_inverse, c->cnt, c->cnt_rep, x->pos_slot);
     if (d_offsets)
       hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
                          d_offsets, (int)n_bags, n, c->pos2bag);
@@ -549,7 +549,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
-                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cnt, c->cursor, c->cur_rep,
+                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cursor, c->cur_rep,
                        x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;

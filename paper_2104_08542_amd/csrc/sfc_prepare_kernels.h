@@ -12,7 +12,7 @@ namespace sfc {
 
 constexpr int kPosChunk = 2048;   // positions (or slots) per block in the scan passes
 constexpr int kVidTile = 256;     // virtual ids per tile in resolve / assign
-constexpr int kSortPer = 8;       // positions per thread in the count / group passes (16 measured slower)
+constexpr int kSortPer = 16;      // positions per thread in the count / group passes (8 and 32 measured slower)
 constexpr int kSortChunk = 256 * kSortPer;
 
 // ---------------------------------------------------------------------------------------------
@@ -297,6 +297,8 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
 }
 
 // VSI pass 4: virtual id of every position, and cnt[v] = number of positions of virtual id v.
+// For the ids outside the LDS range the atomic that counts a position also ranks it inside its
+// group (rank[p]): the grouping pass then needs no atomic of its own for them.
 // Virtual ids are handed out in order of first appearance, so the frequent ids of a power-law
 // batch are (nearly all) among the lowest ones: those are counted in an LDS histogram per block
 // and flushed with one coalesced atomic per bin; the rest go to HBM atomics on distinct words.
@@ -310,14 +312,14 @@ constexpr int kHotRep = 32;
 __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hslot,
                                                        const int* __restrict__ uvid, int n,
                                                        int* __restrict__ inverse, int* cnt,
-                                                       int* cnt_rep) {
+                                                       int* cnt_rep, int* __restrict__ rank) {
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
   const int base = blockIdx.x * kSortChunk;
   int hv[kSortPer], vv[kSortPer];
 #pragma unroll
-  for (int j = 0; j < kSortPer; ++j) {          // eight loads in flight per level of indirection
+  for (int j = 0; j < kSortPer; ++j) {          // kSortPer loads in flight per level of indirection
     const int p = base + j * 256 + (int)threadIdx.x;
     hv[j] = p < n ? (int)((unsigned)hslot[p] & ~kCandBit) : -1;
   }
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hs
     if (v >= 0) {
       inverse[p] = v;
       if (v < kHotBins) atomicAdd(&lh[v], 1);
-      else atomicAdd(&cnt[v], 1);
+      else rank[p] = atomicAdd(&cnt[v], 1);      // arrival order inside the group, for k_scatter
     }
   }
   __syncthreads();
@@ -354,47 +356,44 @@ __global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ off
 
 // Grouping of positions by virtual id (counting sort): perm64[cursor[v]++] = (v << 32) | payload,
 // payload = position (one-hot) or bag index (multi-hot).  cursor[v] starts at the exclusive scan
-// of cnt.  Same LDS treatment of the low virtual ids as above; an id that occurs once needs no
-// atomic at all.  The order inside a group is the order in which the atomics land.
+// of cnt.  Same LDS treatment of the low virtual ids as above; the others already carry their rank
+// inside the group from the counting pass (rank_slot[p], the array this pass then overwrites with
+// pos_slot[p]).  The order inside a group is the order in which the atomics land.
 // Also writes pos_slot[p] = row of slot[inverse[p]] for the forward gather (a bypass slot C + j
 // lives at row C + boff + j: each step in flight has its own bypass region).
 __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse,
                                                   const int* __restrict__ pos2bag, int n,
-                                                  const int* __restrict__ cnt, int* cursor,
+                                                  const int* __restrict__ cursor,
                                                   int* cur_rep,
                                                   int64_t* __restrict__ perm64,
                                                   const int* __restrict__ slot,
-                                                  int* __restrict__ pos_slot, int C, int boff) {
+                                                  int* rank_slot, int C, int boff) {
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
   const int base = blockIdx.x * kSortChunk;
-  int vv[kSortPer], rr[kSortPer], sv[kSortPer], cv[kSortPer], pay[kSortPer];
-  // three levels of indirection, eight loads in flight at each: position -> vid -> slot / count
+  int vv[kSortPer], rr[kSortPer], sv[kSortPer], cb[kSortPer], pay[kSortPer];
+  // two levels of indirection, kSortPer loads in flight at each: position -> vid -> slot / group start
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     vv[j] = p < n ? inverse[p] : -1;
+    rr[j] = p < n ? rank_slot[p] : 0;           // meaningful for the ids outside the LDS range only
     pay[j] = (p < n && pos2bag) ? pos2bag[p] : p;
   }
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
     sv[j] = vv[j] >= 0 ? slot[vv[j]] : -1;
-    cv[j] = vv[j] >= kHotBins ? cnt[vv[j]] : 0;
+    cb[j] = vv[j] >= kHotBins ? cursor[vv[j]] : 0;
   }
-#pragma unroll
-  for (int j = 0; j < kSortPer; ++j) {          // cold ids: a single occurrence needs no atomic
-    rr[j] = 0;
-    if (vv[j] >= kHotBins) rr[j] = cv[j] == 1 ? cursor[vv[j]] : atomicAdd(&cursor[vv[j]], 1);
-  }
-  // the cold ids' cursors are on their way (returning atomics, microseconds each); the hot ids'
-  // ranks come from LDS meanwhile, and every group entry is written at the end
+  // the hot ids' ranks come from LDS; every group entry is written at the end
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
     const int p = base + j * 256 + (int)threadIdx.x;
     if (vv[j] < 0) continue;
-    pos_slot[p] = sv[j] >= C ? sv[j] + boff : sv[j];   // row index for the forward gather
+    rank_slot[p] = sv[j] >= C ? sv[j] + boff : sv[j];   // pos_slot: row index for the forward gather
     if (vv[j] < kHotBins) rr[j] = atomicAdd(&lh[vv[j]], 1);
+    else rr[j] += cb[j];
   }
   __syncthreads();
   int* mine = cur_rep + (blockIdx.x & (kHotRep - 1)) * kHotBins;
