@@ -135,6 +135,32 @@ def test_long_groups_cross_many_spans():
     p.finish(); p.close()
 
 
+def test_frequent_ids_that_first_appear_late():
+    # the grouping passes treat the lowest virtual ids (the early, usually frequent ones) in LDS and
+    # rank the others with atomics: here the batch opens with 9000 distinct ids, so the frequent ids
+    # that follow get virtual ids beyond that range and their long groups take the other path;
+    # multi-hot as well, where the payload of a grouped entry is the bag, not the position
+    V, D, n = 40_000, 16, 120_000
+    rng = np.random.default_rng(21)
+    head = rng.permutation(V)[:9000]
+    r = rng.random(n - 9000)
+    tail = np.where(r < 0.4, 39_000, np.where(r < 0.7, 39_001, np.where(r < 0.8, head[17],
+                                                                        rng.integers(0, V, n - 9000))))
+    ids = np.concatenate([head, tail])
+    p = Pair(V, D, C=30_000, max_ids=n)
+    p.step(ids, si.grads(n, D, 22, 0).numpy())
+    p.step(np.concatenate([head[::-1], tail[::-1]]), si.grads(n, D, 22, 1).numpy())
+    p.finish(); p.close()
+    lens = rng.integers(0, 7, 30_000)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    m = int(offsets[-1])
+    ids = np.concatenate([head, tail])[:m] if m <= n else None
+    assert ids is not None
+    p = Pair(V, D, C=30_000, max_ids=n, max_bags=lens.size)
+    p.step(ids, si.grads(lens.size, D, 23, 0).numpy(), offsets)
+    p.finish(); p.close()
+
+
 def test_same_stream_and_separate_host_arrays():
     # copies on the main stream; Host weights and accumulators as two separate arrays
     V, D, n = 4000, 32, 2000
