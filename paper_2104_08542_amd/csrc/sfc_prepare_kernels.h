@@ -308,6 +308,7 @@ constexpr int kHotBins = 8192;
 // block b using copy b mod kHotRep; resolve folds the copies into cnt, the miss assignment turns
 // them into one group cursor per copy.
 constexpr int kHotRep = 32;
+constexpr int kFlushPer = 16;     // bins per thread and round when k_scatter flushes its LDS tallies
 
 __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hslot,
                                                        const int* __restrict__ uvid, int n,
@@ -397,14 +398,17 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   }
   __syncthreads();
   int* mine = cur_rep + (blockIdx.x & (kHotRep - 1)) * kHotBins;
-  for (int b0 = threadIdx.x; b0 < kHotBins; b0 += 256 * 4) {
-    int c[4], r[4];
+  // the block's share of each non-empty bin's cursor: returning atomics, sixteen in flight per
+  // thread (each round of them is a round trip to the memory side)
+  static_assert(kHotBins % (256 * kFlushPer) == 0, "flush rounds cover the bins exactly");
+  for (int b0 = threadIdx.x; b0 < kHotBins; b0 += 256 * kFlushPer) {
+    int c[kFlushPer], r[kFlushPer];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) c[u] = lh[b0 + u * 256];
+    for (int u = 0; u < kFlushPer; ++u) c[u] = lh[b0 + u * 256];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) r[u] = c[u] ? atomicAdd(&mine[b0 + u * 256], c[u]) : 0;
+    for (int u = 0; u < kFlushPer; ++u) r[u] = c[u] ? atomicAdd(&mine[b0 + u * 256], c[u]) : 0;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) if (c[u]) lh[b0 + u * 256] = r[u];
+    for (int u = 0; u < kFlushPer; ++u) if (c[u]) lh[b0 + u * 256] = r[u];
   }
   __syncthreads();
 #pragma unroll
