@@ -93,6 +93,11 @@ struct sfc_cache {
   hipStream_t st = nullptr, side = nullptr;     // main stream; stream of the Host copies
   hipStream_t prep = nullptr;                   // stream of the prepare kernels
   bool own_prep = false;                        // prep was created here (lookahead 2)
+  // lookahead 2: the insert pass of a step runs on a stream of its own as soon as the previous
+  // step's resolve has emptied the batch table, beside the rest of that step's prepare
+  hipStream_t ins = nullptr;
+  hipEvent_t ev_resolved = nullptr, ev_inserted = nullptr;
+  bool resolved_once = false;                   // ev_resolved has been recorded
   hipEvent_t ev_tmp = nullptr;                  // cross-stream ordering inside one call
   // device memory
   float *cw = nullptr, *ca = nullptr;           // rows [(C + nctx * max_ids), D] and their optimizer state [.., S]
@@ -256,6 +261,7 @@ int sync_all(sfc_cache* c) {
   HIPCHK(hipStreamSynchronize(c->st));
   if (c->side != c->st) HIPCHK(hipStreamSynchronize(c->side));
   if (c->prep != c->st && c->prep != c->side) HIPCHK(hipStreamSynchronize(c->prep));
+  if (c->ins) HIPCHK(hipStreamSynchronize(c->ins));
   return SFC_OK;
 }
 
@@ -292,6 +298,7 @@ void sfc_cache_destroy(sfc_cache* c) {
   (void)hipStreamSynchronize(c->st);
   if (c->side != c->st) (void)hipStreamSynchronize(c->side);
   if (c->own_prep && c->prep) (void)hipStreamSynchronize(c->prep);
+  if (c->ins) (void)hipStreamSynchronize(c->ins);
   for (int w = 0; w < P_N; ++w)
     for (EventPair& ep : c->pending[w]) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
   for (EventPair& ep : c->spare) { (void)hipEventDestroy(ep.a); (void)hipEventDestroy(ep.b); }
@@ -301,6 +308,9 @@ void sfc_cache_destroy(sfc_cache* c) {
     if (c->ctx[k].ev_fetched) (void)hipEventDestroy(c->ctx[k].ev_fetched);
   }
   if (c->own_prep && c->prep) (void)hipStreamDestroy(c->prep);
+  if (c->ins) (void)hipStreamDestroy(c->ins);
+  if (c->ev_resolved) (void)hipEventDestroy(c->ev_resolved);
+  if (c->ev_inserted) (void)hipEventDestroy(c->ev_inserted);
   for (void* p : c->allocs) (void)hipFree(p);
   delete c;
 }
@@ -380,6 +390,14 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       rc = fail(SFC_EHIP, "hipStreamCreate", e); goto bad;
     }
     c->own_prep = true;
+    if ((e = hipStreamCreateWithFlags(&c->ins, hipStreamNonBlocking)) != hipSuccess) {
+      c->ins = nullptr;
+      rc = fail(SFC_EHIP, "hipStreamCreate", e); goto bad;
+    }
+    if ((e = hipEventCreateWithFlags(&c->ev_resolved, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&c->ev_inserted, hipEventDisableTiming)) != hipSuccess) {
+      rc = fail(SFC_EHIP, "hipEventCreate", e); goto bad;
+    }
   }
 
   {
@@ -491,7 +509,15 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
     HIPCHK(hipStreamWaitEvent(s, c->ev_tmp, 0));
     // a context taken over from a step that was never updated: its copies may still be reading its lists
     if (x->state == FETCHED && s != c->side) HIPCHK(hipStreamWaitEvent(s, x->ev_fetched, 0));
+    if (c->ins) {
+      // the insert pass touches only the batch table, the per-position table slots and the tally
+      // of invalid ids, all of which the previous step's prepare has finished with once its
+      // resolve has run: it need not wait for that step's victim, assignment and grouping passes
+      HIPCHK(hipStreamWaitEvent(c->ins, c->ev_tmp, 0));
+      if (c->resolved_once) HIPCHK(hipStreamWaitEvent(c->ins, c->ev_resolved, 0));
+    }
   }
+  hipStream_t si = c->ins ? c->ins : s;          // stream of the insert pass
   c->t += 1;
   x->t = c->t; x->state = PREPARED; x->updated = false; x->main_pending = false;
   x->n_ids = n_ids; x->n_bags = n_bags; x->d_offsets = d_offsets;
@@ -507,11 +533,15 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int nchunk = (n + kPosChunk - 1) / kPosChunk;
   if (n > 0) {
     const int nub = (n + kUniqChunk - 1) / kUniqChunk, head = nub < kHeadBlocks ? nub : kHeadBlocks;
-    hipLaunchKernelGGL(k_uniq_insert, dim3(head), dim3(256), 0, s, d_ids, n, c->V, c->utab, hu,
+    hipLaunchKernelGGL(k_uniq_insert, dim3(head), dim3(256), 0, si, d_ids, n, c->V, c->utab, hu,
                        c->hslot, c->n_invalid, 0);
     if (nub > head)
-      hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, s, d_ids, n, c->V, c->utab,
+      hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, si, d_ids, n, c->V, c->utab,
                          hu, c->hslot, c->n_invalid, head);
+    if (si != s) {
+      HIPCHK(hipEventRecord(c->ev_inserted, si));
+      HIPCHK(hipStreamWaitEvent(s, c->ev_inserted, 0));
+    }
     hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
                        c->blk_cnt, c->index, c->hi, prev->ctr);
   }
@@ -531,6 +561,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt, c->cnt_rep,
                      c->tile_cnt, c->age_hist, x->ctr);
+  if (c->ins) { HIPCHK(hipEventRecord(c->ev_resolved, s)); c->resolved_once = true; }
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
                      c->tile_reuse,
                      c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
