@@ -131,6 +131,9 @@ void sfc_cache_destroy(sfc_cache* c);
 /*
  * Step 1 (Algorithm 1 lines 3-4; Data-Loader section, Host-Manager section).
  *  d_ids       [n_ids] int64 raw feature ids, row-major [batch, fields] or the concatenated bags.
+ *              Produced on `stream` before this call (or already complete): with lookahead > 0 the
+ *              prepare runs on other streams (side_stream, or streams the library creates for
+ *              lookahead 2), which first wait for what `stream` has been given so far.
  *  d_offsets   NULL for one-hot input (then n_bags must equal n_ids), else [n_bags+1] int64 CSR
  *              offsets with d_offsets[0] = 0 and d_offsets[n_bags] = n_ids, non-decreasing.
  *  outputs (each sized for n_ids entries by the caller):
