@@ -93,8 +93,9 @@ struct sfc_cache {
   hipStream_t st = nullptr, side = nullptr;     // main stream; stream of the Host copies
   hipStream_t prep = nullptr;                   // stream of the prepare kernels
   bool own_prep = false;                        // prep was created here (lookahead 2)
-  // lookahead 2: the insert pass of a step runs on a stream of its own as soon as the previous
-  // step's resolve has emptied the batch table, beside the rest of that step's prepare
+  // lookahead 2: the unique passes of a step (insert, count, scan, assign, inverse) run on a
+  // stream of their own as soon as the previous step's resolve has emptied the batch table,
+  // beside the rest of that step's prepare
   hipStream_t ins = nullptr;
   hipEvent_t ev_resolved = nullptr, ev_inserted = nullptr;
   bool resolved_once = false;                   // ev_resolved has been recorded
@@ -112,8 +113,14 @@ struct sfc_cache {
   int* blk_cnt = nullptr;                       // [max_ids / kPosChunk + 1]
   int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
   int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
-  int* cnt = nullptr; int* cursor = nullptr;    // [max_ids] positions per virtual id; group cursor
-  int *cnt_rep = nullptr, *cur_rep = nullptr;   // [kHotRep, kHotBins] copies of both for the lowest virtual ids
+  // positions per virtual id [max_ids] and its copies for the lowest virtual ids [kHotRep, kHotBins]:
+  // two sets, used by steps of even / odd number, so that the unique passes of a step can run
+  // beside the previous step's miss assignment and grouping, which still read that step's counts
+  int* cnt2[2] = {nullptr, nullptr};
+  int* cnt_rep2[2] = {nullptr, nullptr};
+  int* cursor = nullptr;                        // [max_ids] group cursor
+  int* cur_rep = nullptr;                       // [kHotRep, kHotBins] its copies for the lowest virtual ids
+  int* n_unique = nullptr;                      // unique ids of the step whose unique passes ran last
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
   int* tile_reuse = nullptr;                    // [max_ids / kVidTile + 1] deleted index entries reused per tile
@@ -417,14 +424,17 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->tile_miss, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_lt, c->C / kPosChunk + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_eq, c->C / kPosChunk + 2))) goto bad;
-    if ((rc = dalloc(c, &c->cnt, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->cnt2[0], c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->cnt2[1], c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->n_unique, 1))) goto bad;
     if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_reuse, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->age_hist, (int64_t)kAgeBins))) goto bad;
     if ((rc = dalloc(c, &c->n_invalid, 1))) goto bad;
-    if ((rc = dalloc(c, &c->cnt_rep, (int64_t)kHotRep * kHotBins))) goto bad;
+    if ((rc = dalloc(c, &c->cnt_rep2[0], (int64_t)kHotRep * kHotBins))) goto bad;
+    if ((rc = dalloc(c, &c->cnt_rep2[1], (int64_t)kHotRep * kHotBins))) goto bad;
     if ((rc = dalloc(c, &c->cur_rep, (int64_t)kHotRep * kHotBins))) goto bad;
     {
       const int64_t nw = seg_geom(c->D, c->max_ids).waves + 8;
@@ -457,7 +467,9 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
     fill<int>(s, c->age_hist, (int64_t)kAgeBins, 0);
     fill<int>(s, c->n_invalid, 1, 0);
-    fill<int>(s, c->cnt_rep, (int64_t)kHotRep * kHotBins, 0);
+    fill<int>(s, c->cnt_rep2[0], (int64_t)kHotRep * kHotBins, 0);
+    fill<int>(s, c->cnt_rep2[1], (int64_t)kHotRep * kHotBins, 0);
+    fill<int>(s, c->n_unique, 1, 0);
     fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
@@ -510,19 +522,24 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
     // a context taken over from a step that was never updated: its copies may still be reading its lists
     if (x->state == FETCHED && s != c->side) HIPCHK(hipStreamWaitEvent(s, x->ev_fetched, 0));
     if (c->ins) {
-      // the insert pass touches only the batch table, the per-position table slots and the tally
-      // of invalid ids, all of which the previous step's prepare has finished with once its
-      // resolve has run: it need not wait for that step's victim, assignment and grouping passes
+      // The unique passes touch the batch table, the per-position table slots, the tally of
+      // invalid ids, this step's set of counts, its context's position array and the caller's
+      // buffers of this step: the previous step's prepare has finished with the shared ones once
+      // its resolve has run, so they need not wait for that step's victim, assignment and
+      // grouping passes (small grids that leave most of the GPU idle).
       HIPCHK(hipStreamWaitEvent(c->ins, c->ev_tmp, 0));
+      if (x->state == FETCHED) HIPCHK(hipStreamWaitEvent(c->ins, x->ev_fetched, 0));
       if (c->resolved_once) HIPCHK(hipStreamWaitEvent(c->ins, c->ev_resolved, 0));
     }
   }
-  hipStream_t si = c->ins ? c->ins : s;          // stream of the insert pass
+  hipStream_t su = c->ins ? c->ins : s;          // stream of the unique passes
   c->t += 1;
   x->t = c->t; x->state = PREPARED; x->updated = false; x->main_pending = false;
   x->n_ids = n_ids; x->n_bags = n_bags; x->d_offsets = d_offsets;
   x->d_unique = d_unique_ids; x->d_inverse = d_inverse; x->d_slot = d_slot; x->d_miss = d_miss_vids;
   c->last_prepared = (int)(x - c->ctx);
+  int* const cnt = c->cnt2[x->t & 1];
+  int* const cnt_rep = c->cnt_rep2[x->t & 1];
 
   EventPair ep{};
   int rc;
@@ -533,33 +550,35 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int nchunk = (n + kPosChunk - 1) / kPosChunk;
   if (n > 0) {
     const int nub = (n + kUniqChunk - 1) / kUniqChunk, head = nub < kHeadBlocks ? nub : kHeadBlocks;
-    hipLaunchKernelGGL(k_uniq_insert, dim3(head), dim3(256), 0, si, d_ids, n, c->V, c->utab, hu,
+    hipLaunchKernelGGL(k_uniq_insert, dim3(head), dim3(256), 0, su, d_ids, n, c->V, c->utab, hu,
                        c->hslot, c->n_invalid, 0);
     if (nub > head)
-      hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, si, d_ids, n, c->V, c->utab,
+      hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, su, d_ids, n, c->V, c->utab,
                          hu, c->hslot, c->n_invalid, head);
-    if (si != s) {
-      HIPCHK(hipEventRecord(c->ev_inserted, si));
-      HIPCHK(hipStreamWaitEvent(s, c->ev_inserted, 0));
-    }
-    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
-                       c->blk_cnt, c->index, c->hi, prev->ctr);
+    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n, c->blk_cnt);
   }
-  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, s, c->blk_cnt, nchunk, x->ctr, prev->ctr,
-                     c->n_invalid);
+  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, su, c->blk_cnt, nchunk, c->n_unique);
   if (n > 0) {
-    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, s, c->hslot, c->utab, n,
-                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, c->cnt, c->index, c->hi,
-                       c->slot_id, x->ctr);
-    hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s,
-                       c->hslot, c->uvid, n, d_inverse, c->cnt, c->cnt_rep, x->pos_slot);
-    if (d_offsets)
-      hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
-                         d_offsets, (int)n_bags, n, c->pos2bag);
+    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n,
+                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, cnt);
+    hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, su,
+                       c->hslot, c->uvid, n, d_inverse, cnt, cnt_rep, x->pos_slot);
   }
+  if (su != s) {
+    HIPCHK(hipEventRecord(c->ev_inserted, su));
+    HIPCHK(hipStreamWaitEvent(s, c->ev_inserted, 0));
+  }
+  // from here on behind the whole prepare of the previous step: the step's counters start from
+  // that step's, the index is rebuilt if its plan asked for it
+  hipLaunchKernelGGL(k_ctr_init, dim3(1), dim3(64), 0, s, x->ctr, prev->ctr, c->n_unique, c->n_invalid);
+  hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, x->ctr);
+  hipLaunchKernelGGL(k_index_refill, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
+  if (n > 0 && d_offsets)
+    hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
+                       d_offsets, (int)n_bags, n, c->pos2bag);
   const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
-                     c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, c->cnt, c->cnt_rep,
+                     c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, cnt, cnt_rep,
                      c->tile_cnt, c->age_hist, x->ctr);
   if (c->ins) { HIPCHK(hipEventRecord(c->ev_resolved, s)); c->resolved_once = true; }
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
@@ -573,7 +592,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int gv = grid_for(n, kVidTile, kGridCap);
   hipLaunchKernelGGL(k_victim_unmap, dim3(gv), dim3(256), 0, s, x->victim_id, c->index, c->hi,
                      x->ctr);
-  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, c->cnt, c->cnt_rep,
+  hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, cnt, cnt_rep,
                      c->cur_rep, c->tile_cnt,
                      c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,

@@ -181,7 +181,6 @@ __global__ __launch_bounds__(256) void k_uniq_insert(const int64_t* __restrict__
   }
 }
 
-// VSI pass 2: per chunk of positions, how many are the first appearance of their id.
 // Rebuild of the cache index, second half (the first half empties it): every resident id goes
 // back in.  Grid-stride over the occupied slots [0, f).
 __device__ __forceinline__ void index_reinsert(IdxEntry* index, uint32_t hi,
@@ -202,17 +201,11 @@ __device__ __forceinline__ void index_reinsert(IdxEntry* index, uint32_t hi,
   }
 }
 
+// VSI pass 2: per chunk of positions, how many are the first appearance of their id.
 __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslot,
                                                      const UEntry* __restrict__ utab, int n,
-                                                     int* __restrict__ blk_cnt, IdxEntry* index,
-                                                     uint32_t hi, const Ctr* prev) {
+                                                     int* __restrict__ blk_cnt) {
   __shared__ int smem[20];
-  // cache index due for a rebuild (the previous step's plan asked for it): empty it here, the
-  // assign pass re-inserts the resident ids
-  if (prev->rebuild) {
-    IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
-    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
-  }
   const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
   int c = 0;
 #pragma unroll
@@ -227,13 +220,9 @@ __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslo
   if (threadIdx.x == 0) blk_cnt[blockIdx.x] = tot;
 }
 
-// One block, after the count pass: scans the per-chunk counts, and starts the step's counters:
-// they inherit the cache-wide fields (watermark, oldest stamp, tombstones, rebuild flag, error)
-// from the previous step's and start their own tallies at zero.  Steps in flight on the other
-// streams keep reading their own copy.  n_invalid is the insert pass's tally of out-of-range
-// positions, returned to zero here.
-__global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* cur, const Ctr* prev,
-                                                      int* n_invalid) {
+// One block, after the count pass: scans the per-chunk counts; their total is the number of
+// unique ids, left in *n_unique for k_ctr_init.
+__global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, int* n_unique) {
   __shared__ int smem[20];
   int carry = 0;
   for (int b = 0; b < n; b += 1024) {
@@ -244,29 +233,48 @@ __global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, Ctr* cur
     if (i < n) data[i] = carry + e;
     carry += tot;
   }
-  if (threadIdx.x == 0) {
-    Ctr c = *prev;
-    c.U_prev = c.U;
-    c.U = carry;
-    c.M = c.K = c.n_bypass = c.n_hit = 0;
-    c.n_invalid = *n_invalid;
-    *n_invalid = 0;
-    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
-    *cur = c;
-  }
+  if (threadIdx.x == 0) *n_unique = carry;
 }
+
+// Starts the step's counters, once the previous step's prepare has run to its end: they inherit the
+// cache-wide fields (watermark, oldest stamp, tombstones, rebuild flag, error) from the previous
+// step's and start their own tallies at zero.  Steps in flight on the other streams keep reading
+// their own copy.  n_invalid is the insert pass's tally of out-of-range positions, returned to
+// zero here.
+__global__ void k_ctr_init(Ctr* cur, const Ctr* prev, const int* n_unique, int* n_invalid) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  Ctr c = *prev;
+  c.U_prev = c.U;
+  c.U = *n_unique;
+  c.M = c.K = c.n_bypass = c.n_hit = 0;
+  c.n_invalid = *n_invalid;
+  *n_invalid = 0;
+  c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
+  *cur = c;
+}
+
+// Rebuild of the cache index when the previous step's plan asked for it (too many deleted
+// entries): the first kernel empties it, the second puts every resident id back.  Both run between
+// the last index update of one step and the resolve of the next, and return at once otherwise.
+__global__ __launch_bounds__(256) void k_index_clear(IdxEntry* index, uint32_t hi, const Ctr* ctr) {
+  if (!ctr->rebuild) return;
+  IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
+  for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
+}
+__global__ __launch_bounds__(256) void k_index_refill(IdxEntry* index, uint32_t hi,
+                                                       const int64_t* __restrict__ slot_id,
+                                                       const Ctr* ctr) {
+  if (ctr->rebuild) index_reinsert(index, hi, slot_id, ctr->f);
+}
+
 __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hslot,
                                                       const UEntry* __restrict__ utab, int n,
                                                       const int* __restrict__ blk_off,
                                                       int64_t* __restrict__ unique_ids,
                                                       int* __restrict__ uvid,
                                                       int* __restrict__ vid_hslot,
-                                                      int* __restrict__ cnt, IdxEntry* index,
-                                                      uint32_t hi,
-                                                      const int64_t* __restrict__ slot_id,
-                                                      const Ctr* ctr) {
+                                                      int* __restrict__ cnt) {
   __shared__ int smem[20];
-  if (ctr->rebuild) index_reinsert(index, hi, slot_id, ctr->f);
   const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
   int hs[8];
   unsigned flags = 0;
@@ -686,8 +694,8 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     ctr->f_old = f; ctr->f = f_new;
     if (need > 0 && T > oldest) ctr->oldest = T;
     ctr->tomb -= reuse;
-    // a rebuild asked for by the previous step has run in this step's count / assign passes
-    if (ctr->rebuild && U > 0) { ctr->rebuild = 0; ctr->tomb = 0; }
+    // a rebuild asked for by the previous step has run ahead of this step's resolve
+    if (ctr->rebuild) { ctr->rebuild = 0; ctr->tomb = 0; }
     // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
     // eighth of the index would be deleted entries
     if ((unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
