@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
-    ap.add_argument("--lookahead", type=int, default=2, choices=[0, 1, 2],
+    ap.add_argument("--lookahead", type=int, default=2, choices=[0, 1, 2, 3],
                     help="L > 0: prepare/fetch of step t+L overlap lookup/update of step t; with 2 "
                          "the copies of step t+1 also overlap the prepare of step t+2 (default)")
     ap.add_argument("--optimizer", default="adagrad", choices=["adagrad", "adam", "rowwise_adagrad"],

@@ -83,7 +83,7 @@ typedef struct {
                                  link moves fastest. */
   float lr;                   /* learning rate */
   float eps;                  /* epsilon, added outside the square root */
-  int32_t lookahead;          /* L = 0, 1 or 2: how many steps may be prepared ahead of the one being
+  int32_t lookahead;          /* L = 0 .. 3: how many steps may be prepared ahead of the one being
                                  trained.  Rows used by the batch being prepared and by the L
                                  batches before it are protected from eviction.
                                  0: calls of a step go prepare, fetch_misses, lookup,
@@ -92,9 +92,11 @@ typedef struct {
                                  sfc_fetch_misses of step t+L may be called before
                                  sfc_backward_update of step t; they run on other streams while the
                                  main stream works on step t (the paper's pipeline of Data-Loader,
-                                 Host-Manager and GPU-Worker stages).  With L = 2 the Host copies of
-                                 step t+1 also overlap the prepare of step t+2.  The caller rotates
-                                 L + 1 sets of prepare buffers. */
+                                 Host-Manager and GPU-Worker stages).  With L >= 2 the prepare has
+                                 streams of its own, so that the Host copies of one step also
+                                 overlap the prepare of the next; L = 3 adds a step context, which
+                                 takes the reuse of a context out of the critical path.  The caller
+                                 rotates L + 1 sets of prepare buffers. */
   int32_t max_steps;          /* steps this cache may run (sizes the recency histogram); 0 = 1<<20 */
   void* stream;               /* hipStream_t for prepare / lookup / backward_update */
   void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */
@@ -133,7 +135,7 @@ void sfc_cache_destroy(sfc_cache* c);
  *  d_ids       [n_ids] int64 raw feature ids, row-major [batch, fields] or the concatenated bags.
  *              Produced on `stream` before this call (or already complete): with lookahead > 0 the
  *              prepare runs on other streams (side_stream, or streams the library creates for
- *              lookahead 2), which first wait for what `stream` has been given so far.
+ *              lookahead >= 2), which first wait for what `stream` has been given so far.
  *  d_offsets   NULL for one-hot input (then n_bags must equal n_ids), else [n_bags+1] int64 CSR
  *              offsets with d_offsets[0] = 0 and d_offsets[n_bags] = n_ids, non-decreasing.
  *  outputs (each sized for n_ids entries by the caller):

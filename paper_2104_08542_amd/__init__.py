@@ -271,7 +271,7 @@ class Cache:
     """One sfc_cache with its output buffers; methods mirror the C calls of a step.
 
     lookahead = 0: prepare, fetch_misses, lookup, backward_update in that order.
-    lookahead = L (1 or 2): prepare / fetch_misses of step t+L may be issued before backward_update
+    lookahead = L (1 .. 3): prepare / fetch_misses of step t+L may be issued before backward_update
     of step t (they run on other streams meanwhile); lookup and backward_update always act on the
     oldest step that has not been updated.  lookahead + 1 sets of output buffers rotate.
     """

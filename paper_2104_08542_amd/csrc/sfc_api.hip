@@ -8,7 +8,8 @@
 // L = 0 runs the prepare on the main stream; L = 1 runs prepare and Host copies of step t+1 on
 // the side stream while lookup / backward_update of step t run on the main stream; L = 2 gives
 // the prepare a stream of its own, so that prepare(t+2), the copies of t+1 and lookup / update
-// of t overlap (the paper's pipeline of Data-Loader, Host-Manager and GPU-Worker stages).
+// of t overlap (the paper's pipeline of Data-Loader, Host-Manager and GPU-Worker stages); L = 3
+// is L = 2 with one more context, so that a prepare need not wait for the update three steps back.
 // Streams are ordered by events only; the host never waits.
 #include "../../include/sfc.h"
 
@@ -75,15 +76,15 @@ struct StepCtx {
   hipEvent_t ev_fetched = nullptr;    // the side-stream launch of the step's Host copies has run
   bool updated = false;               // backward_update has been enqueued for this step
   // pipelined mode: the second launch of the Host copies, due on the main stream behind the
-  // update of step main_after (see k_swap_rows); older1 / older2 = counters of the older steps
+  // update of step main_after (see k_swap_rows); older1 .. older3 = counters of the older steps
   // that were still in flight when the fetch was issued
   bool main_pending = false;
   int main_after = 0;
-  const Ctr *older1 = nullptr, *older2 = nullptr;
+  const Ctr *older1 = nullptr, *older2 = nullptr, *older3 = nullptr;
   int chain = 0;
 };
 
-constexpr int kMaxCtx = 3;
+constexpr int kMaxCtx = 4;
 
 }  // namespace
 
@@ -93,8 +94,8 @@ struct sfc_cache {
   int D = 0, d4 = 0, nctx = 1;
   hipStream_t st = nullptr, side = nullptr;     // main stream; stream of the Host copies
   hipStream_t prep = nullptr;                   // stream of the prepare kernels
-  bool own_prep = false;                        // prep was created here (lookahead 2)
-  // lookahead 2: the unique passes of a step (insert, count, scan, assign, inverse) run on a
+  bool own_prep = false;                        // prep was created here (lookahead >= 2)
+  // lookahead >= 2: the unique passes of a step (insert, count, scan, assign, inverse) run on a
   // stream of their own as soon as the previous step's resolve has emptied the batch table,
   // beside the rest of that step's prepare
   hipStream_t ins = nullptr;
@@ -231,7 +232,7 @@ int launch_swap(sfc_cache* c, StepCtx* x, hipStream_t s, int main_variant) {
   hipLaunchKernelGGL(k_swap_rows, dim3(grid_for(x->n_ids * (c->d4 + c->s4), 256, kSwapBlocks)),
                      dim3(256), 0, s,
                      x->miss_row, x->miss_id, x->victim_id, (float4*)c->cw, (float4*)c->ca, c->host,
-                     c->d4, c->s4, x->ctr, x->older1, x->older2, x->chain, main_variant);
+                     c->d4, c->s4, x->ctr, x->older1, x->older2, x->older3, x->chain, main_variant);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_FETCH, s, &ep))) return rc;
   if (main_variant) x->main_pending = false;
@@ -336,7 +337,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     return fail(SFC_EINVAL, "the Prefetch strategy needs capacity_rows = 0 and lookahead = 1");
   if (cfg->max_ids_per_batch < 1 || cfg->max_bags_per_batch < 1 || cfg->host_rows < 1)
     return fail(SFC_EINVAL, "max_ids_per_batch, max_bags_per_batch and host_rows must be >= 1");
-  if (cfg->lookahead < 0 || cfg->lookahead > 2) return fail(SFC_EINVAL, "lookahead must be 0, 1 or 2");
+  if (cfg->lookahead < 0 || cfg->lookahead > 3) return fail(SFC_EINVAL, "lookahead must be 0, 1, 2 or 3");
   if (cfg->lookahead > 0 && (!cfg->side_stream || cfg->side_stream == cfg->stream))
     return fail(SFC_EINVAL, "lookahead > 0 needs a side_stream different from stream");
   const int64_t nctx = cfg->lookahead + 1;
@@ -394,7 +395,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   // lookahead 0: prepare on the main stream; 1: on the side stream, ahead of that step's copies;
   // 2: on a stream of its own, so that the copies of step t+1 overlap the prepare of step t+2
   c->prep = cfg->lookahead == 0 ? c->st : c->side;
-  if (cfg->lookahead == 2) {
+  if (cfg->lookahead >= 2) {
     if ((e = hipStreamCreateWithFlags(&c->prep, hipStreamNonBlocking)) != hipSuccess) {
       c->prep = nullptr;
       rc = fail(SFC_EHIP, "hipStreamCreate", e); goto bad;
@@ -619,13 +620,14 @@ int sfc_fetch_misses(sfc_cache* c) {
   if (!x || x->state != PREPARED) return fail(SFC_ESTATE, "sfc_fetch_misses needs a preceding sfc_prepare");
   // older steps whose update has not been enqueued yet: their bypass rows are not in the Host
   // table yet (k_swap_rows decides on the device which of its two launches does the work)
-  x->older1 = x->older2 = nullptr;
+  x->older1 = x->older2 = x->older3 = nullptr;
   x->chain = 0; x->main_pending = false; x->main_after = 0;
   for (int k = 0; k < c->nctx && c->cfg.policy != SFC_POLICY_PREFETCH; ++k) {
     StepCtx* o = &c->ctx[k];
     if (o == x || o->state != FETCHED || o->updated) continue;
     if (o->t == x->t - 1) { x->older1 = o->ctr; x->chain = o->main_pending ? 1 : 0; }
     else if (o->t == x->t - 2) x->older2 = o->ctr;
+    else if (o->t == x->t - 3) x->older3 = o->ctr;
     if (o->t > x->main_after) x->main_after = o->t;
   }
   if (c->side != c->st) {
@@ -636,7 +638,7 @@ int sfc_fetch_misses(sfc_cache* c) {
   }
   int rc = launch_swap(c, x, c->side, 0);
   if (rc) return rc;
-  x->main_pending = x->older1 || x->older2;
+  x->main_pending = x->older1 || x->older2 || x->older3;
   x->state = FETCHED;
   return SFC_OK;
 }

@@ -51,9 +51,10 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
                                                     const int64_t* __restrict__ victim_id,
                                                     float4* __restrict__ cw, float4* __restrict__ ca,
                                                     HostRows h, int d4, int s4, Ctr* ctr,
-                                                    const Ctr* older1, const Ctr* older2, int chain,
-                                                    int main_variant) {
+                                                    const Ctr* older1, const Ctr* older2,
+                                                    const Ctr* older3, int chain, int main_variant) {
   const bool on_main = (older1 && older1->n_bypass != 0) || (older2 && older2->n_bypass != 0) ||
+                       (older3 && older3->n_bypass != 0) ||
                        (chain && older1 && older1->fetch_on_main != 0);
   if (blockIdx.x == 0 && threadIdx.x == 0) ctr->fetch_on_main = on_main;   // same value from both launches
   if (on_main != (main_variant != 0)) return;

@@ -27,8 +27,8 @@
   } while (0)
 
 int main(int argc, char** argv) {
-  const int L = argc > 1 ? atoi(argv[1]) : 0;            // lookahead 0, 1 or 2
-  if (L < 0 || L > 2) { printf("usage: abi_client [lookahead 0|1|2]\n"); return 2; }
+  const int L = argc > 1 ? atoi(argv[1]) : 0;            // lookahead 0 .. 3
+  if (L < 0 || L > 3) { printf("usage: abi_client [lookahead 0|1|2|3]\n"); return 2; }
   const int64_t V = 5000, C = 700, N = 2048;
   const int D = 16, T = 8;
   const float lr = 0.05f, eps = 1e-8f;

@@ -13,7 +13,7 @@ BIN = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "paper_2104_08542_amd", "examples", "abi_client")
 
 
-@pytest.mark.parametrize("lookahead", [0, 1, 2])
+@pytest.mark.parametrize("lookahead", [0, 1, 2, 3])
 def test_plain_cpp_client_trains_through_the_c_abi(lookahead):
     assert os.path.exists(BIN), "examples/abi_client is not built: run python paper_2104_08542_amd/build.py"
     r = subprocess.run([BIN, str(lookahead)], capture_output=True, text=True, timeout=120)

@@ -227,7 +227,7 @@ def _batches(V, D, n, s, seed, steps):
             for t in range(steps)]
 
 
-@pytest.mark.parametrize("lookahead", [1, 2])
+@pytest.mark.parametrize("lookahead", [1, 2, 3])
 @pytest.mark.parametrize("sync_every_call", [True, False])
 def test_pipelined_steps_match_sequential_oracle(sync_every_call, lookahead):
     # prepare / fetch of later steps overlap lookup / update of the current one; the cache is
@@ -238,7 +238,7 @@ def test_pipelined_steps_match_sequential_oracle(sync_every_call, lookahead):
     p.close()
 
 
-@pytest.mark.parametrize("lookahead", [1, 2])
+@pytest.mark.parametrize("lookahead", [1, 2, 3])
 @pytest.mark.parametrize("sync_every_call", [True, False])
 def test_pipelined_steps_with_bypass_rows(sync_every_call, lookahead):
     # the working set of two consecutive batches exceeds the cache: rows bypass it, and a row that
@@ -250,11 +250,12 @@ def test_pipelined_steps_with_bypass_rows(sync_every_call, lookahead):
     p.close()
 
 
-def test_pipelined_mixed_bypass_and_none():
+@pytest.mark.parametrize("lookahead", [2, 3])
+def test_pipelined_mixed_bypass_and_none(lookahead):
     # steps with and without bypass rows alternate, so the Host copies switch between the two
     # streams from step to step
     V, D = 6000, 8
-    p = Pair(V, D, C=1000, max_ids=4096, lookahead=2)
+    p = Pair(V, D, C=1000, max_ids=4096, lookahead=lookahead)
     bs = []
     for t in range(16):
         n = 3500 if t % 5 == 0 else 300
@@ -265,7 +266,7 @@ def test_pipelined_mixed_bypass_and_none():
     p.close()
 
 
-@pytest.mark.parametrize("lookahead", [1, 2])
+@pytest.mark.parametrize("lookahead", [1, 2, 3])
 def test_pipelined_multihot(lookahead):
     V, D, nb = 8000, 8, 700
     p = Pair(V, D, C=5000, max_ids=nb * 20, max_bags=nb, lookahead=lookahead)
@@ -277,7 +278,7 @@ def test_pipelined_multihot(lookahead):
     p.close()
 
 
-@pytest.mark.parametrize("lookahead", [0, 2])
+@pytest.mark.parametrize("lookahead", [0, 2, 3])
 def test_many_rebuilds_with_many_victims(lookahead):
     # a cache much smaller than the id range with thousands of victims per step: the index fills
     # with deleted entries and is rebuilt every few steps, also while other steps are in flight
