@@ -79,7 +79,8 @@ class BruteCache:
 
 @pytest.mark.parametrize("C,lookahead,vocab", [(8, 0, 20), (8, 1, 20), (5, 0, 40), (1, 0, 6),
                                                (0, 0, 10), (16, 1, 18), (12, 0, 13),
-                                               (8, 2, 20), (16, 2, 18), (24, 2, 40)])
+                                               (8, 2, 20), (16, 2, 18), (24, 2, 40),
+                                               (8, 3, 20), (30, 3, 40)])
 def test_p1_against_brute_force(C, lookahead, vocab):
     rng = np.random.default_rng(100 + C + lookahead)
     D = 2

@@ -101,7 +101,7 @@ def test_adagrad_one_step_closed_form():
 
 
 @pytest.mark.parametrize("C,lookahead,multihot", [(0, 0, False), (7, 0, False), (64, 0, False),
-                                                  (64, 1, False), (64, 2, False), (1000, 0, False),
+                                                  (64, 1, False), (64, 2, False), (64, 3, False), (1000, 0, False),
                                                   (40, 0, True), (1000, 0, True)])
 def test_cache_is_transparent(C, lookahead, multihot):
     """Training through the cache equals training a plain table (consistency of Host and
