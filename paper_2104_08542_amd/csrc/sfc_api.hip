@@ -71,8 +71,7 @@ struct StepCtx {
   int* miss_row = nullptr;            // [max_ids] cache row of each miss (bypass rows already offset)
   int64_t* miss_id = nullptr;         // [max_ids] id of each miss
   int boff = 0;                       // bypass slot C + j lives at row C + boff + j
-  hipEvent_t ev_prepared = nullptr;   // the step's miss and victim lists are complete: the copies may start
-  hipEvent_t ev_grouped = nullptr;    // the step's last prepare kernel (grouping, pos_slot) has run
+  hipEvent_t ev_prepared = nullptr;   // the step's prepare kernels have run
   hipEvent_t ev_fetched = nullptr;    // the side-stream launch of the step's Host copies has run
   bool updated = false;               // backward_update has been enqueued for this step
   // pipelined mode: the second launch of the Host copies, due on the main stream behind the
@@ -245,7 +244,6 @@ int rows_ready(sfc_cache* c, StepCtx* x) {
   int rc;
   if (x->main_pending && (rc = launch_swap(c, x, c->st, 1))) return rc;
   if (c->side != c->st) HIPCHK(hipStreamWaitEvent(c->st, x->ev_fetched, 0));
-  if (c->prep != c->st) HIPCHK(hipStreamWaitEvent(c->st, x->ev_grouped, 0));
   return SFC_OK;
 }
 
@@ -315,7 +313,6 @@ void sfc_cache_destroy(sfc_cache* c) {
   if (c->ev_tmp) (void)hipEventDestroy(c->ev_tmp);
   for (int k = 0; k < kMaxCtx; ++k) {
     if (c->ctx[k].ev_prepared) (void)hipEventDestroy(c->ctx[k].ev_prepared);
-    if (c->ctx[k].ev_grouped) (void)hipEventDestroy(c->ctx[k].ev_grouped);
     if (c->ctx[k].ev_fetched) (void)hipEventDestroy(c->ctx[k].ev_fetched);
   }
   if (c->own_prep && c->prep) (void)hipStreamDestroy(c->prep);
@@ -458,7 +455,6 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       if ((rc = dalloc(c, &x->miss_id, c->max_ids))) goto bad;
       x->boff = (int)(k * c->max_ids);
       if ((e = hipEventCreateWithFlags(&x->ev_prepared, hipEventDisableTiming)) != hipSuccess ||
-          (e = hipEventCreateWithFlags(&x->ev_grouped, hipEventDisableTiming)) != hipSuccess ||
           (e = hipEventCreateWithFlags(&x->ev_fetched, hipEventDisableTiming)) != hipSuccess) {
         rc = fail(SFC_EHIP, "hipEventCreate", e); goto bad;
       }
@@ -602,15 +598,13 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
-  // the Host copies need the lists only; lookup and update also wait for the grouping
-  HIPCHK(hipEventRecord(x->ev_prepared, s));
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cursor, c->cur_rep,
                        x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
-  HIPCHK(hipEventRecord(x->ev_grouped, s));
+  HIPCHK(hipEventRecord(x->ev_prepared, s));
   return SFC_OK;
 }
 
