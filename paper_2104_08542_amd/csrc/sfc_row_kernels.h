@@ -58,6 +58,7 @@ __global__ __launch_bounds__(256) void k_swap_rows(const int* __restrict__ miss_
                        (chain && older1 && older1->fetch_on_main != 0);
   if (blockIdx.x == 0 && threadIdx.x == 0) ctr->fetch_on_main = on_main;   // same value from both launches
   if (on_main != (main_variant != 0)) return;
+  __builtin_amdgcn_s_setprio(3);            // few waves, long round trips: issue ahead of the kernels beside them
   const int K = ctr->K;
   const int w2 = d4 + s4;                   // chunks of a row and of its optimizer state
   const int64_t total = (int64_t)ctr->M * w2;
