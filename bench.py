@@ -44,7 +44,8 @@ def main():
     ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
     ap.add_argument("--lookahead", type=int, default=2, choices=[0, 1, 2, 3],
                     help="L > 0: prepare/fetch of step t+L overlap lookup/update of step t; with 2 "
-                         "the copies of step t+1 also overlap the prepare of step t+2 (default)")
+                         "(default) the copies of step t+1 also overlap the prepare of step t+2; 3 adds a step "
+                         "context")
     ap.add_argument("--optimizer", default="adagrad", choices=["adagrad", "adam", "rowwise_adagrad"],
                     help="adagrad is the benchmark's; adam is the paper's (state 2x the row)")
     ap.add_argument("--strategy", default="cache", choices=["cache", "host", "prefetch"],

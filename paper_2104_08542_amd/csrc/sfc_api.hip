@@ -7,9 +7,10 @@
 // of positions, its victim list and its bypass region.  lookahead = L has L + 1 contexts.
 // L = 0 runs the prepare on the main stream; L = 1 runs prepare and Host copies of step t+1 on
 // the side stream while lookup / backward_update of step t run on the main stream; L = 2 gives
-// the prepare a stream of its own, so that prepare(t+2), the copies of t+1 and lookup / update
-// of t overlap (the paper's pipeline of Data-Loader, Host-Manager and GPU-Worker stages); L = 3
-// is L = 2 with one more context, so that a prepare need not wait for the update three steps back.
+// the prepare two streams of its own (one for the unique passes, one for the cache manager's
+// kernels), so that prepare(t+2), the copies of t+1 and lookup / update of t overlap (the paper's
+// pipeline of Data-Loader, Host-Manager and GPU-Worker stages); L = 3 is L = 2 with one more
+// context, so that a prepare need not wait for the update three steps back.
 // Streams are ordered by events only; the host never waits.
 #include "../../include/sfc.h"
 
