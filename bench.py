@@ -289,11 +289,20 @@ def main():
             done_ids += ids_np.size
             steps_done += 1
             log("oracle step %d: %.2fs so far" % (steps_done, cpu_t))
+        cpu_model = "unknown CPU"
+        try:
+            with open("/proc/cpuinfo") as f:
+                for line in f:
+                    if line.startswith("model name"):
+                        cpu_model = line.split(":", 1)[1].strip()
+                        break
+        except OSError:
+            pass
         result["cpu_baseline"] = {
             "value": done_ids / cpu_t, "unit": "ids/s", "cores": 1, "kind": "oracle",
             "sample": "first %d steps of the same seeded batch sequence from a cold cache, "
-                      "%.1f s of single-thread oracle time (host has %d logical CPUs)"
-                      % (steps_done, cpu_t, os.cpu_count()),
+                      "%.1f s of single-thread oracle time (%s, %d logical CPUs)"
+                      % (steps_done, cpu_t, cpu_model, os.cpu_count()),
         }
     if args.calibrate_copy:
         # a plain copy-like kernel of known size, with an instantiation nothing else in this
