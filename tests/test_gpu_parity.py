@@ -267,6 +267,22 @@ def test_pipelined_mixed_bypass_and_none(lookahead):
 
 
 @pytest.mark.parametrize("lookahead", [1, 2, 3])
+def test_pipelined_degenerate_batches(lookahead):
+    # empty batches, a single id, only out-of-range ids and full-size batches in flight together
+    V, D = 300, 4
+    p = Pair(V, D, C=64, max_ids=512, lookahead=lookahead)
+    g = lambda n, t: si.grads(n, D, 81, t).numpy()
+    ids = [np.zeros(0, np.int64), np.full(300, 42), np.zeros(0, np.int64), np.array([-5, V, 10 ** 12, -1]),
+           np.arange(512) % V, np.array([3, -1, 3, 200, 7]), np.zeros(0, np.int64), np.zeros(0, np.int64),
+           np.arange(200)[::-1].copy(), np.arange(512) % 100]
+    p.run_pipelined([(a, g(a.size, t), None) for t, a in enumerate(ids)], False)
+    p.close()
+    p = Pair(V, D, C=64, max_ids=512, lookahead=lookahead)
+    p.run_pipelined([(a, g(a.size, t), None) for t, a in enumerate(ids)], True)
+    p.close()
+
+
+@pytest.mark.parametrize("lookahead", [1, 2, 3])
 def test_pipelined_multihot(lookahead):
     V, D, nb = 8000, 8, 700
     p = Pair(V, D, C=5000, max_ids=nb * 20, max_bags=nb, lookahead=lookahead)
