@@ -68,6 +68,8 @@ def main():
     import numpy as np
     import torch
     import sfc_inputs as si
+    import __graft_entry__
+    __graft_entry__.build_if_missing()          # loads what is built; compiles only if nothing is
     import paper_2104_08542_amd as sfc
 
     dev = torch.device("cuda:0")
