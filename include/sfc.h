@@ -212,7 +212,8 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
 
 /*
  * Device timing.  level 1: hipEvents bracket the work of each step call on the stream it runs
- * on.  level 2: also each of the three kernels inside sfc_backward_update (the extra events
+ * on (with lookahead >= 2 the prepare runs on two library streams; its events sit on the one of
+ * the cache manager's kernels and include its wait for the unique passes on the other).  level 2: also each of the three kernels inside sfc_backward_update (the extra events
  * lengthen the call a little, so call timings are best read at level 1).  level 0: off.
  * sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare, fetch_misses,
  * lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel, Adagrad kernel),
