@@ -572,8 +572,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   }
   // from here on behind the whole prepare of the previous step: the step's counters start from
   // that step's, the index is rebuilt if its plan asked for it
-  hipLaunchKernelGGL(k_ctr_init, dim3(1), dim3(64), 0, s, x->ctr, prev->ctr, c->n_unique, c->n_invalid);
-  hipLaunchKernelGGL(k_index_clear, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, x->ctr);
+  hipLaunchKernelGGL(k_ctr_init, dim3(kGridCap), dim3(256), 0, s, x->ctr, prev->ctr, c->n_unique,
+                     c->n_invalid, c->index, c->hi);
   hipLaunchKernelGGL(k_index_refill, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
   if (n > 0 && d_offsets)
     hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,

@@ -241,23 +241,25 @@ __global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, int* n_u
 // step's and start their own tallies at zero.  Steps in flight on the other streams keep reading
 // their own copy.  n_invalid is the insert pass's tally of out-of-range positions, returned to
 // zero here.
-__global__ void k_ctr_init(Ctr* cur, const Ctr* prev, const int* n_unique, int* n_invalid) {
-  if (blockIdx.x != 0 || threadIdx.x != 0) return;
-  Ctr c = *prev;
-  c.U_prev = c.U;
-  c.U = *n_unique;
-  c.M = c.K = c.n_bypass = c.n_hit = 0;
-  c.n_invalid = *n_invalid;
-  *n_invalid = 0;
-  c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
-  *cur = c;
-}
-
-// Rebuild of the cache index when the previous step's plan asked for it (too many deleted
-// entries): the first kernel empties it, the second puts every resident id back.  Both run between
-// the last index update of one step and the resolve of the next, and return at once otherwise.
-__global__ __launch_bounds__(256) void k_index_clear(IdxEntry* index, uint32_t hi, const Ctr* ctr) {
-  if (!ctr->rebuild) return;
+// The same launch empties the cache index when the previous step's plan asked for a rebuild (too
+// many deleted entries); k_index_refill then puts every resident id back.  Both run between the
+// last index update of one step and the resolve of the next.  They read the flag and the
+// watermark from the previous step's counters, which no kernel changes any more (on the very
+// first step prev == cur and both fields are zero before and after).
+__global__ __launch_bounds__(256) void k_ctr_init(Ctr* cur, const Ctr* prev, const int* n_unique,
+                                                  int* n_invalid, IdxEntry* index, uint32_t hi) {
+  const bool rebuild = prev->rebuild != 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    Ctr c = *prev;
+    c.U_prev = c.U;
+    c.U = *n_unique;
+    c.M = c.K = c.n_bypass = c.n_hit = 0;
+    c.n_invalid = *n_invalid;
+    *n_invalid = 0;
+    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
+    *cur = c;
+  }
+  if (!rebuild) return;
   IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
   for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
 }
