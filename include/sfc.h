@@ -92,11 +92,11 @@ typedef struct {
                                  sfc_fetch_misses of step t+L may be called before
                                  sfc_backward_update of step t; they run on other streams while the
                                  main stream works on step t (the paper's pipeline of Data-Loader,
-                                 Host-Manager and GPU-Worker stages).  With L >= 2 the prepare has
-                                 streams of its own, so that the Host copies of one step also
-                                 overlap the prepare of the next; L = 3 adds a step context, which
-                                 takes the reuse of a context out of the critical path.  The caller
-                                 rotates L + 1 sets of prepare buffers. */
+                                 Host-Manager and GPU-Worker stages): the prepare on two streams
+                                 the library creates, the Host copies on side_stream.  Each
+                                 further step of lookahead adds a step context, so that a prepare
+                                 waits for an older update.  The caller rotates L + 1 sets of
+                                 prepare buffers. */
   int32_t max_steps;          /* steps this cache may run (sizes the recency histogram); 0 = 1<<20 */
   void* stream;               /* hipStream_t for prepare / lookup / backward_update */
   void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */
@@ -134,8 +134,8 @@ void sfc_cache_destroy(sfc_cache* c);
  * Step 1 (Algorithm 1 lines 3-4; Data-Loader section, Host-Manager section).
  *  d_ids       [n_ids] int64 raw feature ids, row-major [batch, fields] or the concatenated bags.
  *              Produced on `stream` before this call (or already complete): with lookahead > 0 the
- *              prepare runs on other streams (side_stream, or streams the library creates for
- *              lookahead >= 2), which first wait for what `stream` has been given so far.
+ *              prepare runs on other streams (streams the library creates; side_stream for
+ *              SFC_POLICY_PREFETCH), which first wait for what `stream` has been given so far.
  *  d_offsets   NULL for one-hot input (then n_bags must equal n_ids), else [n_bags+1] int64 CSR
  *              offsets with d_offsets[0] = 0 and d_offsets[n_bags] = n_ids, non-decreasing.
  *  outputs (each sized for n_ids entries by the caller):
@@ -212,7 +212,7 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
 
 /*
  * Device timing.  level 1: hipEvents bracket the work of each step call on the stream it runs
- * on (with lookahead >= 2 the prepare runs on two library streams; its events sit on the one of
+ * on (with lookahead >= 1 the prepare runs on two library streams; its events sit on the one of
  * the cache manager's kernels and include its wait for the unique passes on the other).  level 2: also each of the three kernels inside sfc_backward_update (the extra events
  * lengthen the call a little, so call timings are best read at level 1).  level 0: off.
  * sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare, fetch_misses,

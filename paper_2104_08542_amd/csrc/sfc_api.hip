@@ -5,12 +5,12 @@
 //
 // A step in flight is a StepCtx: the caller's buffers, the step's device counters, its grouping
 // of positions, its victim list and its bypass region.  lookahead = L has L + 1 contexts.
-// L = 0 runs the prepare on the main stream; L = 1 runs prepare and Host copies of step t+1 on
-// the side stream while lookup / backward_update of step t run on the main stream; L = 2 gives
-// the prepare two streams of its own (one for the unique passes, one for the cache manager's
-// kernels), so that prepare(t+2), the copies of t+1 and lookup / update of t overlap (the paper's
-// pipeline of Data-Loader, Host-Manager and GPU-Worker stages); L = 3 is L = 2 with one more
-// context, so that a prepare need not wait for the update three steps back.
+// L = 0 runs the prepare on the main stream.  L >= 1 gives the prepare two streams of its own (one
+// for the unique passes, one for the cache manager's kernels) and the Host copies run on the side
+// stream, so that the prepare of step t+L, the copies of the step before it and lookup / update of
+// step t overlap (the paper's pipeline of Data-Loader, Host-Manager and GPU-Worker stages); a
+// larger L means more contexts, i.e. a prepare need not wait for the most recent update.  The
+// Prefetch comparison strategy keeps its prepare on the side stream, ahead of its copies.
 // Streams are ordered by events only; the host never waits.
 #include "../../include/sfc.h"
 
@@ -94,8 +94,8 @@ struct sfc_cache {
   int D = 0, d4 = 0, nctx = 1;
   hipStream_t st = nullptr, side = nullptr;     // main stream; stream of the Host copies
   hipStream_t prep = nullptr;                   // stream of the prepare kernels
-  bool own_prep = false;                        // prep was created here (lookahead >= 2)
-  // lookahead >= 2: the unique passes of a step (insert, count, scan, assign, inverse) run on a
+  bool own_prep = false;                        // prep was created here (lookahead >= 1)
+  // lookahead >= 1: the unique passes of a step (insert, count, scan, assign, inverse) run on a
   // stream of their own as soon as the previous step's resolve has emptied the batch table,
   // beside the rest of that step's prepare
   hipStream_t ins = nullptr;
@@ -390,10 +390,10 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   c->host.a = (float4*)dp;
   c->host.hs4 = (cfg->host_row_stride ? cfg->host_row_stride : cfg->dim) / 4;
   c->host.has4 = (cfg->host_state_stride ? cfg->host_state_stride : S) / 4;
-  // lookahead 0: prepare on the main stream; 1: on the side stream, ahead of that step's copies;
-  // 2: on a stream of its own, so that the copies of step t+1 overlap the prepare of step t+2
+  // lookahead 0: prepare on the main stream; otherwise on two streams of its own, beside the Host
+  // copies of the step before (the Prefetch strategy: on the side stream, ahead of its copies)
   c->prep = cfg->lookahead == 0 ? c->st : c->side;
-  if (cfg->lookahead >= 2) {
+  if (cfg->lookahead >= 1 && cfg->policy != SFC_POLICY_PREFETCH) {
     if ((e = hipStreamCreateWithFlags(&c->prep, hipStreamNonBlocking)) != hipSuccess) {
       c->prep = nullptr;
       rc = fail(SFC_EHIP, "hipStreamCreate", e); goto bad;
