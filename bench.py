@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--align-floats", type=int, default=32,
                     help="pad each Host row block [weights | state] to a multiple of this many floats")
     ap.add_argument("--cache-rows", type=int, default=None, help="override the workload's cache size")
+    ap.add_argument("--host-rows", type=int, default=None,
+                    help="override the rows of the Host table (the ids are drawn over that range): for "
+                         "workloads whose table the box cannot pin, e.g. c4 needs 128 GB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -75,6 +78,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = si.WORKLOADS[args.workload]
+    if args.host_rows is not None:
+        import dataclasses
+        w = dataclasses.replace(w, vocab=args.host_rows)
     K, W = args.steps, args.warmup
     D, V, C = w.dim, w.vocab, w.cache_rows
     if args.cache_rows is not None:
@@ -231,7 +237,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {
-            "workload": "%s: batch %d x %d fields%s, ids %s over %.0e rows, dim %d fp32, cache %d rows LRU, %s"
+            "workload": "%s: batch %d x %d fields%s, ids %s over %.3g rows, dim %d fp32, cache %d rows LRU, %s"
                         % (w.name, w.batch, w.fields,
                            "" if w.one_hot else " (bags of %d-%d ids)" % (w.bag_lo, w.bag_hi),
                            "uniform" if w.zipf_s is None else "Zipf(s=%.2f)" % w.zipf_s, V, D, C,
