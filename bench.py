@@ -3,8 +3,10 @@
 
 One step = sfc_prepare + sfc_fetch_misses + sfc_lookup + sfc_backward_update over one seeded
 synthetic batch whose ids already sit in HBM.  Prints ONE JSON line: whole-job raw ids/s, the
-roofline of the dominant kernel (hipEvent-timed inside the timed region) and the CPU oracle timed
-on a bounded sample of the same workload.
+roofline of the dominant kernel (hipEvent-timed in this run on the batches that follow the timed
+region, see roofline.timing_source) and the CPU oracle timed on a bounded sample of the same
+workload.  An untimed fill phase first steps the seeded batch sequence until the cache is full
+and evicting at a steady rate, whatever --warmup says.
 """
 import argparse
 import json
@@ -40,7 +42,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--max-fill-steps", type=int, default=400,
+                    help="cap on the untimed fill phase that precedes the warm-up: batches of the seeded "
+                         "sequence are stepped until the cache is full and evicting at a steady rate")
     ap.add_argument("--workload", default="c2", help="tiny | c1 | c2 | c3 | c4 (see sfc_inputs.WORKLOADS)")
     ap.add_argument("--lookahead", type=int, default=2, choices=[0, 1, 2, 3],
                     help="L > 0: prepare/fetch of step t+L overlap lookup/update of step t; with 2 "
@@ -147,16 +152,37 @@ def main():
                 cache.lookup(out)
                 cache.backward_update(g)
 
-    # warm-up: fills the cache and reaches the steady-state hit rate
+    # Fill phase (untimed, independent of --warmup): the timed region must show the regime the
+    # workload is defined for, a full cache that evicts on every step.  Batches of the seeded
+    # sequence are stepped until the device reports evictions and their number has levelled off
+    # (mean of the last 8 steps within 5 % of the 8 before), or until nothing can change any more
+    # (a cache that holds the whole table never evicts: there the misses must level off instead).
+    # The counters come from the pinned status block, so the loop never waits for the device
+    # except where it reads them.
     t0 = time.time()
-    hit_curve = {}
+    hit_curve, ev_hist, miss_hist = {}, [], []
+    fill_steps = 0
+    never_evicts = C >= V or C == 0
+    while fill_steps < args.max_fill_steps:
+        run_steps([next_batch()], fill_steps)
+        fill_steps += 1
+        torch.cuda.synchronize()
+        st, _ = cache.peek_stats()                     # of the most recently planned batch
+        ev_hist.append(st["n_evict"]); miss_hist.append(st["n_miss"])
+        if fill_steps % 10 == 1:
+            hit_curve[step_no[0]] = round(st["n_hit"] / max(1, st["n_hit"] + st["n_miss"]), 4)
+        if fill_steps >= 16:
+            h = miss_hist if never_evicts else ev_hist
+            a, b = sum(h[-8:]) / 8.0, sum(h[-16:-8]) / 8.0
+            if (never_evicts or a > 0) and abs(a - b) <= 0.05 * max(a, b, 1.0):
+                break
+    cache.check()
+    log("fill phase: %d steps in %.1fs, evictions per step now %d" % (fill_steps, time.time() - t0,
+                                                                    ev_hist[-1] if ev_hist else 0))
+    # warm-up proper: W untimed steps in the timed region's order
     for t in range(W):
         run_steps([next_batch()], t)
-        if t % max(1, W // 10) == 0 or t == W - 1:     # hit rate on the way to the plateau (untimed)
-            st = cache.stats()                          # of the most recently prepared batch
-            hit_curve[step_no[0]] = round(st["n_hit"] / max(1, st["n_hit"] + st["n_miss"]), 4)
     torch.cuda.synchronize()
-    log("warm-up %d steps in %.1fs" % (W, time.time() - t0))
 
     batches = [next_batch() for _ in range(K)]
     n_ids_total = sum(b[0].numel() for b in batches)
@@ -217,7 +243,7 @@ def main():
     RS = R + 4 * S                                                    # a row and its optimizer state
     b_update = bags * R + 4 * N + 4 * U + 2 * U * RS + extra         # sfc_backward_update as a whole
     kernels = {
-        "k_lookup": (b_lookup, ms["lookup"]),
+        ("k_lookup_onehot" if w.one_hot else "k_lookup_bags"): (b_lookup, ms["lookup"]),
         "k_seg_stream": (bags * R + 4 * N + U * R + extra, ms["k_seg_stream"]),   # grad + grouping in, common out
         "k_%s_rows" % args.optimizer: (4 * U + U * R + 2 * U * RS, ms["k_adagrad_rows"]),
     }
@@ -247,6 +273,7 @@ def main():
             "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
             "bypass_per_step": avg["n_bypass"], "lookahead": args.lookahead,
             "strategy": args.strategy,
+            "fill_steps": fill_steps,
             "hit_rate_by_batch": hit_curve,
             "host_to_gpu_rows_per_unique": avg["n_miss"] / max(1.0, U),
             "gpu_to_host_rows_per_unique": (avg["n_evict"] + avg["n_bypass"]) / max(1.0, U),
@@ -255,6 +282,12 @@ def main():
             "bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
             "algorithmic_bytes_per_launch": kernels[dom][0], "avg_ms": kernels[dom][1],
+            "timing_source": "hipEvents on the kernel's own stream in this run, pass 2: the same "
+                             "calls on the batches that follow the timed region, issued so that "
+                             "the streams do not overlap (each kernel has the GPU to itself)",
+            "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                              "earlier run of this command, calibrated against a copy kernel); not "
+                              "measured in this run",
         },
         "kernels": {k: {"algorithmic_bytes": v[0], "avg_ms": v[1],
                         "GB/s": (v[0] / (v[1] * 1e-3) / 1e9 if v[1] else None)} for k, v in kernels.items()},

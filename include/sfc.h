@@ -23,8 +23,13 @@
  *     of the same step and must stay alive and unmodified until sfc_backward_update (or the
  *     next sfc_prepare) has completed on the stream.
  *   - All work is enqueued on the streams given at creation and is asynchronous to the host,
- *     except sfc_cache_create, sfc_flush, sfc_get_stats, sfc_cache_state and sfc_cache_destroy,
- *     which synchronise.  No call allocates device memory after sfc_cache_create.
+ *     except sfc_cache_create, sfc_flush, sfc_get_stats, sfc_cache_state, sfc_verify and
+ *     sfc_cache_destroy, which synchronise.  No call allocates device memory after
+ *     sfc_cache_create (sfc_verify, a test aid, excepted).
+ *   - Errors that only the device can see (a consistency check of the cache manager that fired,
+ *     malformed bag offsets) are written by the kernels into a pinned status block.  Every step
+ *     call looks at it first, without waiting, and refuses to go on (SFC_ECORRUPT) once the manager
+ *     state is inconsistent; sfc_check reads the same block on demand.
  *   - One sfc_cache must be driven by one host thread at a time.
  *   - Rows are fp32, row-major, dim floats each; dim must be a multiple of 4 and all row
  *     buffers 16-byte aligned.
@@ -44,6 +49,7 @@ extern "C" {
 #define SFC_EHIP (-3)    /* a HIP runtime call failed; see sfc_last_error() */
 #define SFC_ENOMEM (-4)  /* device or host allocation failed */
 #define SFC_ELIMIT (-5)  /* more steps than max_steps */
+#define SFC_ECORRUPT (-6) /* a device-side consistency check of the cache manager has fired */
 
 #define SFC_POLICY_LRU_BATCH 0
 /* The "Prefetch" strategy of the paper's MixCache ablation (RQ3), for comparison runs: nothing is
@@ -115,9 +121,17 @@ typedef struct {
   int64_t n_invalid;  /* positions whose id was outside [0, V) */
   int64_t h2d_bytes;  /* Host->cache bytes of this step (rows + optimizer state) */
   int64_t d2h_bytes;  /* cache->Host bytes of this step (victims + bypass rows) */
+  int64_t n_bad_offsets; /* violations found in d_offsets (0 for well-formed input) */
 } sfc_stats;
 
-/* Pinned, device-mapped Host memory suitable for h_weights / h_acc.  Returns NULL on failure. */
+/* Pinned, device-mapped Host memory suitable for h_weights / h_acc.  Returns NULL on failure.
+ * One table should be ONE allocation (weights and state interleaved, see host_row_stride): the
+ * runtime has been seen to refuse a single piece beyond about 50 GB and to crash at the next
+ * kernel launch after two pieces of 35 GB each, so this call refuses (NULL) a request that would
+ * take the total handed out by it in this process beyond SFC_HOST_ALLOC_MAX_BYTES while another
+ * piece of at least SFC_HOST_ALLOC_LARGE_BYTES is alive. */
+#define SFC_HOST_ALLOC_MAX_BYTES ((int64_t)56 << 30)
+#define SFC_HOST_ALLOC_LARGE_BYTES ((int64_t)8 << 30)
 void* sfc_host_alloc(int64_t bytes);
 void sfc_host_free(void* p);
 
@@ -151,7 +165,15 @@ void sfc_cache_destroy(sfc_cache* c);
  * the `lookahead` batches before it), those whose last use is oldest, ties by lower slot; the
  * i-th miss takes the i-th slot of (free + victim slots) in ascending slot order.
  * Errors: SFC_EINVAL (null pointers, n_ids > max_ids_per_batch, n_bags > max_bags_per_batch,
- * one-hot with n_bags != n_ids), SFC_ELIMIT, SFC_EHIP.  Malformed offsets are not detected.
+ * one-hot with n_bags != n_ids, multi-hot with ids but no bags), SFC_ESTATE (the previous step has
+ * not been fetched yet, or all lookahead + 1 step contexts hold steps that have not been updated:
+ * finish one with sfc_backward_update or give it up with sfc_discard), SFC_ELIMIT, SFC_EHIP,
+ * SFC_ECORRUPT.
+ * Malformed offsets live in device memory, so the host cannot refuse them here: the prepare
+ * kernels check them (first 0, last n_ids, none decreasing), count the violations in
+ * sfc_stats.n_bad_offsets and report the step through sfc_check.  Such a step reads and writes
+ * inside its buffers only, and the cache manager state stays consistent (it depends on the ids
+ * alone), but its lookup output and its update are meaningless.
  */
 int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t* d_offsets,
                 int64_t n_bags, int64_t* d_unique_ids, int32_t* d_inverse, int32_t* d_slot,
@@ -196,11 +218,41 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad);
  */
 int sfc_backward_update(sfc_cache* c, const float* d_grad);
 
+/*
+ * Gives up the oldest step that has been fetched and not updated (a batch that was only looked
+ * up, e.g. for inference): its step context becomes free, its rows stay in the cache unchanged.
+ * SFC_ESTATE if there is no such step or its rows are still on their way.
+ */
+int sfc_discard(sfc_cache* c);
+
 /* Write every resident row and accumulator to the Host table and wait; the cache stays warm. */
 int sfc_flush(sfc_cache* c);
 
 /* Counters of the most recent sfc_prepare; waits for the streams. */
 int sfc_get_stats(sfc_cache* c, sfc_stats* h_out);
+
+/*
+ * What the device has reported so far, without waiting for any stream (one read of pinned
+ * memory).  sfc_check returns SFC_ECORRUPT once a consistency check of the cache manager has
+ * fired on the device (the cache must not be used any further; sfc_last_error names the check and
+ * its step), SFC_EINVAL if a step since the last sfc_check had malformed bag offsets (reported
+ * once; sfc_last_error names the step), else SFC_OK.
+ * sfc_peek_stats returns the counters of the most recent step whose cache-manager plan has run on
+ * the device and that step's number in *h_step (0: none yet); the byte counts are derived from
+ * them.  A training loop can poll both every step at no cost.
+ */
+int sfc_check(sfc_cache* c);
+int sfc_peek_stats(sfc_cache* c, sfc_stats* h_out, int64_t* h_step);
+
+/*
+ * Test aid: waits for the streams, then recounts the manager state on the device.  h_bad[0]:
+ * occupied slots whose id the index does not map to that slot; h_bad[1]: live index entries that
+ * do not point at a slot holding their id (stale or duplicate entries); h_bad[2]: words of the
+ * recency histogram that differ from a recount of the slots' stamps; h_bad[3]: live entries minus
+ * occupied slots.  Returns SFC_ECORRUPT if any is nonzero.  Needs every step context free or
+ * fetched (no prepare without its fetch).  Allocates and frees a scratch histogram.
+ */
+int sfc_verify(sfc_cache* c, int64_t* h_bad /* [4] */);
 
 /*
  * Snapshot of the cache for inspection; waits for the streams.  Any pointer may be NULL.

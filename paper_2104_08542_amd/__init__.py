@@ -20,7 +20,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsfc.so")
 
-SFC_OK, SFC_EINVAL, SFC_ESTATE, SFC_EHIP, SFC_ENOMEM, SFC_ELIMIT = 0, -1, -2, -3, -4, -5
+SFC_OK, SFC_EINVAL, SFC_ESTATE, SFC_EHIP, SFC_ENOMEM, SFC_ELIMIT, SFC_ECORRUPT = 0, -1, -2, -3, -4, -5, -6
 SFC_POLICY_LRU_BATCH = 0
 SFC_POLICY_PREFETCH = 1
 
@@ -28,7 +28,7 @@ EXPORTS = [
     "sfc_host_alloc", "sfc_host_free", "sfc_cache_create", "sfc_cache_destroy", "sfc_prepare",
     "sfc_fetch_misses", "sfc_lookup", "sfc_segment_sum", "sfc_backward_update", "sfc_flush",
     "sfc_get_stats", "sfc_cache_state", "sfc_profile_enable", "sfc_profile_read", "sfc_strerror",
-    "sfc_last_error",
+    "sfc_last_error", "sfc_check", "sfc_peek_stats", "sfc_discard", "sfc_verify",
 ]
 
 
@@ -53,7 +53,7 @@ class sfc_config(ctypes.Structure):
 class sfc_stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in
                 ("n_unique", "n_hit", "n_miss", "n_evict", "n_bypass", "n_invalid", "h2d_bytes",
-                 "d2h_bytes")]
+                 "d2h_bytes", "n_bad_offsets")]
 
 
 def _load():
@@ -79,6 +79,11 @@ def _load():
     lib.sfc_profile_enable.restype, lib.sfc_profile_enable.argtypes = ci, [vp, i32]
     lib.sfc_profile_read.restype = ci
     lib.sfc_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.sfc_check.restype, lib.sfc_check.argtypes = ci, [vp]
+    lib.sfc_peek_stats.restype = ci
+    lib.sfc_peek_stats.argtypes = [vp, ctypes.POINTER(sfc_stats), ctypes.POINTER(i64)]
+    lib.sfc_discard.restype, lib.sfc_discard.argtypes = ci, [vp]
+    lib.sfc_verify.restype, lib.sfc_verify.argtypes = ci, [vp, ctypes.POINTER(i64)]
     lib.sfc_strerror.restype, lib.sfc_strerror.argtypes = ctypes.c_char_p, [ci]
     lib.sfc_last_error.restype, lib.sfc_last_error.argtypes = ctypes.c_char_p, []
     return lib
@@ -161,6 +166,30 @@ def sfc_get_stats(h) -> dict:
     st = sfc_stats()
     _check(_lib.sfc_get_stats(ctypes.c_void_p(h), ctypes.byref(st)))
     return {k: int(getattr(st, k)) for k, _ in sfc_stats._fields_}
+
+
+def sfc_check(h) -> None:
+    """Raises SfcError if the device has reported an inconsistency or malformed offsets; never waits."""
+    _check(_lib.sfc_check(ctypes.c_void_p(h)))
+
+
+def sfc_peek_stats(h):
+    """(stats dict, step) of the latest step the device has planned; never waits.  step 0: none yet."""
+    st, step = sfc_stats(), ctypes.c_int64()
+    _check(_lib.sfc_peek_stats(ctypes.c_void_p(h), ctypes.byref(st), ctypes.byref(step)))
+    return {k: int(getattr(st, k)) for k, _ in sfc_stats._fields_}, step.value
+
+
+def sfc_discard(h) -> None:
+    _check(_lib.sfc_discard(ctypes.c_void_p(h)))
+
+
+def sfc_verify(h):
+    """Recount of the manager state on the device (test aid, synchronises): the four violation
+    counts of include/sfc.h; raises SfcError(SFC_ECORRUPT) if any is nonzero."""
+    bad = (ctypes.c_int64 * 4)()
+    _check(_lib.sfc_verify(ctypes.c_void_p(h), bad))
+    return list(bad)
 
 
 def sfc_cache_state(h, capacity_rows, dim, rows=False, state_dim=None):
@@ -319,15 +348,17 @@ class Cache:
 
     def prepare(self, ids: torch.Tensor, offsets: Optional[torch.Tensor] = None) -> StepBuffers:
         b = self.bufs[self._next]
+        if b in self.inflight:            # rotation order broken by a discard: any set not in flight
+            free = [x for x in self.bufs if x not in self.inflight]
+            if free:
+                b = free[0]
         n_ids = ids.numel()
         n_bags = n_ids if offsets is None else offsets.numel() - 1
         sfc_prepare(self.h, ids, n_ids, offsets, n_bags, b.unique_ids, b.inverse, b.slot, b.miss_vids)
         b.n_ids, b.n_bags, b.keep = n_ids, n_bags, (ids, offsets)
-        if b in self.inflight:            # a step that was only read is dropped by the library
-            self.inflight.remove(b)
         self.inflight.append(b)
         self.last = b
-        self._next = (self._next + 1) % len(self.bufs)
+        self._next = (self.bufs.index(b) + 1) % len(self.bufs)
         return b
 
     def fetch_misses(self):
@@ -354,6 +385,21 @@ class Cache:
         sfc_backward_update(self.h, grad)
         if self.inflight:
             self.inflight.pop(0)
+
+    def discard(self):
+        """Give up the oldest fetched step without updating it (its rows stay cached)."""
+        sfc_discard(self.h)
+        if self.inflight:
+            self.inflight.pop(0)
+
+    def check(self):
+        sfc_check(self.h)
+
+    def peek_stats(self):
+        return sfc_peek_stats(self.h)
+
+    def verify(self):
+        return sfc_verify(self.h)
 
     def flush(self):
         sfc_flush(self.h)

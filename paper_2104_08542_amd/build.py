@@ -33,13 +33,14 @@ EXAMPLE_BIN = os.path.join(HERE, "examples", "abi_client")
 def build_example(verbose=False):
     """The plain C++ client of the C ABI (no torch): links libsfc.so by path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O2", "-std=c++17", "-ffp-contract=off", "--offload-arch=gfx950", EXAMPLE_SRC, "-o", EXAMPLE_BIN,
-           "-L" + HERE, "-lsfc", "-Wl,-rpath,$ORIGIN/.."]
+    nopk = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    cmd = [hipcc, "-O2", "-std=c++17", "-ffp-contract=off", "--offload-arch=gfx950"] + nopk + [
+           EXAMPLE_SRC, "-o", EXAMPLE_BIN, "-L" + HERE, "-lsfc", "-Wl,-rpath,$ORIGIN/.."]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     # the access-pattern ceilings that the kernel durations are read against
-    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", os.path.join(HERE, "examples", "hbm_ceilings.hip"),
+    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950"] + nopk + [os.path.join(HERE, "examples", "hbm_ceilings.hip"),
            "-o", os.path.join(HERE, "examples", "hbm_ceilings")]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -16,10 +16,13 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -32,6 +35,8 @@ using namespace sfc;
 namespace {
 
 thread_local std::string g_err;
+std::mutex g_host_mu;
+std::map<void*, int64_t> g_host_allocs;     // pieces handed out by sfc_host_alloc and still alive
 
 int fail(int code, const char* what, hipError_t e = hipSuccess) {
   char buf[512];
@@ -75,6 +80,7 @@ struct StepCtx {
   hipEvent_t ev_prepared = nullptr;   // the step's prepare kernels have run
   hipEvent_t ev_fetched = nullptr;    // the side-stream launch of the step's Host copies has run
   bool updated = false;               // backward_update has been enqueued for this step
+  bool discarded = false;             // freed by sfc_discard: the step's copies may still be running
   // pipelined mode: the second launch of the Host copies, due on the main stream behind the
   // update of step main_after (see k_swap_rows); older1 .. older3 = counters of the older steps
   // that were still in flight when the fetch was issued
@@ -131,6 +137,10 @@ struct sfc_cache {
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
   HostRows host{};                              // device view of the Host table
+  HostStatus* hstat = nullptr;                  // pinned status block (host view); d_hstat its device view
+  HostStatus* d_hstat = nullptr;
+  int reported_bad_step = 0;                    // last malformed-offsets step that sfc_check has returned
+  int device = 0;                               // the GPU this cache lives on
   std::vector<void*> allocs;
   // steps
   StepCtx ctx[kMaxCtx];
@@ -198,6 +208,20 @@ int prof_collect(sfc_cache* c) {
       c->spare.push_back(ep);
     }
     c->pending[w].clear();
+  }
+  return SFC_OK;
+}
+
+// One read of pinned memory, no waiting: has a device-side consistency check fired?
+int healthy(sfc_cache* c) {
+  const volatile HostStatus* h = c->hstat;
+  if (h && h->err) {
+    // 1: a lookup walked the whole index, 2: so did an insert, 3: a victim was not in the index,
+    // 4: more victims than the recency histogram promised
+    char msg[128];
+    snprintf(msg, sizeof msg, "cache manager state is inconsistent (device check %d at step %d)",
+             h->err, h->err_step);
+    return fail(SFC_ECORRUPT, msg);
   }
   return SFC_OK;
 }
@@ -286,6 +310,7 @@ const char* sfc_strerror(int code) {
     case SFC_EHIP: return "HIP runtime error";
     case SFC_ENOMEM: return "out of memory";
     case SFC_ELIMIT: return "step limit reached";
+    case SFC_ECORRUPT: return "cache manager state inconsistent";
     default: return "unknown error";
   }
 }
@@ -294,13 +319,33 @@ const char* sfc_last_error(void) { return g_err.c_str(); }
 void* sfc_host_alloc(int64_t bytes) {
   void* p = nullptr;
   if (bytes <= 0) return nullptr;
+  {
+    // several large pinned pieces at once have crashed the runtime at the next kernel launch
+    // (see the header): refuse that layout instead of handing it out
+    std::lock_guard<std::mutex> lk(g_host_mu);
+    int64_t total = bytes;
+    bool other_large = false;
+    for (auto& kv : g_host_allocs) { total += kv.second; other_large |= kv.second >= SFC_HOST_ALLOC_LARGE_BYTES; }
+    if (other_large && bytes >= SFC_HOST_ALLOC_LARGE_BYTES && total > SFC_HOST_ALLOC_MAX_BYTES) {
+      fail(SFC_ENOMEM, "sfc_host_alloc: a second large pinned piece would take the total beyond "
+                       "SFC_HOST_ALLOC_MAX_BYTES; allocate the table as one interleaved piece");
+      return nullptr;
+    }
+  }
   if (hipHostMalloc(&p, (size_t)bytes, hipHostMallocMapped | hipHostMallocPortable) != hipSuccess) {
     (void)hipGetLastError();
+    fail(SFC_ENOMEM, "hipHostMalloc failed");
     return nullptr;
   }
+  std::lock_guard<std::mutex> lk(g_host_mu);
+  g_host_allocs[p] = bytes;
   return p;
 }
-void sfc_host_free(void* p) { if (p) (void)hipHostFree(p); }
+void sfc_host_free(void* p) {
+  if (!p) return;
+  { std::lock_guard<std::mutex> lk(g_host_mu); g_host_allocs.erase(p); }
+  (void)hipHostFree(p);
+}
 
 void sfc_cache_destroy(sfc_cache* c) {
   if (!c) return;
@@ -321,6 +366,7 @@ void sfc_cache_destroy(sfc_cache* c) {
   if (c->ev_resolved) (void)hipEventDestroy(c->ev_resolved);
   if (c->ev_inserted) (void)hipEventDestroy(c->ev_inserted);
   for (void* p : c->allocs) (void)hipFree(p);
+  if (c->hstat) (void)hipHostFree(c->hstat);
   delete c;
 }
 
@@ -368,6 +414,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   c->st = (hipStream_t)cfg->stream;
   c->side = cfg->side_stream ? (hipStream_t)cfg->side_stream : c->st;
   c->hist_len = (cfg->max_steps ? cfg->max_steps : (1 << 20)) + 2;
+  (void)hipGetDevice(&c->device);
   {
     // four entries per possible resident id keep probe sequences short (HBM is plentiful); two
     // where four would not fit a 32-bit entry number
@@ -410,8 +457,21 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   }
 
   {
+    void* hp = nullptr;
+    if ((e = hipHostMalloc(&hp, sizeof(HostStatus), hipHostMallocMapped | hipHostMallocPortable)) != hipSuccess) {
+      rc = fail(SFC_ENOMEM, "hipHostMalloc (status block)", e); goto bad;
+    }
+    c->hstat = (HostStatus*)hp;
+    memset(c->hstat, 0, sizeof(HostStatus));
+    if ((e = hipHostGetDevicePointer(&dp, hp, 0)) != hipSuccess) {
+      rc = fail(SFC_EHIP, "hipHostGetDevicePointer (status block)", e); goto bad;
+    }
+    c->d_hstat = (HostStatus*)dp;
+  }
+  {
     const int64_t rows = c->C + nctx * c->max_ids;
-    const int64_t hu = 2 * c->max_ids;
+    // the batch table of a step has max(2 * n_ids, 64) entries (see sfc_prepare)
+    const int64_t hu = 2 * c->max_ids < 64 ? 64 : 2 * c->max_ids;
     if ((rc = dalloc(c, &c->cw, rows * c->D))) goto bad;
     if ((rc = dalloc(c, &c->ca, rows * c->S))) goto bad;
     if ((rc = dalloc(c, &c->slot_id, c->C))) goto bad;
@@ -475,7 +535,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
-    Ctr z; memset(&z, 0, sizeof z); z.oldest = 1;
+    Ctr z; memset(&z, 0, sizeof z); z.oldest = 1; z.hstat = c->d_hstat;
     for (int k = 0; k < c->nctx; ++k)
       if ((e = hipMemcpyAsync(c->ctx[k].ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess) {
         rc = fail(SFC_EHIP, "cache initialisation", e); goto bad;
@@ -496,24 +556,23 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                 int64_t n_bags, int64_t* d_unique_ids, int32_t* d_inverse, int32_t* d_slot,
                 int32_t* d_miss_vids) {
   if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
   if (n_ids < 0 || n_bags < 0 || n_ids > c->max_ids || n_bags > c->max_bags)
     return fail(SFC_EINVAL, "n_ids / n_bags out of range");
   if (!d_offsets && n_bags != n_ids) return fail(SFC_EINVAL, "one-hot input needs n_bags == n_ids");
+  if (d_offsets && n_bags == 0 && n_ids > 0) return fail(SFC_EINVAL, "multi-hot input with ids but no bags");
   if ((n_ids > 0 && !d_ids) || !d_unique_ids || !d_inverse || !d_slot || !d_miss_vids)
     return fail(SFC_EINVAL, "null buffer");
   if (c->last_prepared >= 0 && c->ctx[c->last_prepared].state == PREPARED)
     return fail(SFC_ESTATE, "sfc_prepare twice without sfc_fetch_misses: missed rows would never arrive");
   if (c->t + 1 >= c->hist_len - 1) return fail(SFC_ELIMIT, "max_steps reached");
 
-  // a free context; with every context busy, the oldest step whose rows were only read is dropped
   StepCtx* x = nullptr;
   for (int k = 0; k < c->nctx; ++k)
     if (c->ctx[k].state == FREE) { x = &c->ctx[k]; break; }
-  if (!x) {
-    x = training_ctx(c);
-    if (!x) return fail(SFC_ESTATE, "no step context free");
-    if (x->main_pending) return fail(SFC_ESTATE, "the oldest step in flight has not been looked up or updated yet");
-  }
+  if (!x)
+    return fail(SFC_ESTATE, "every step context holds a step that has not been updated: call "
+                            "sfc_backward_update (or sfc_discard) first");
   StepCtx* prev = c->last_prepared >= 0 ? &c->ctx[c->last_prepared] : x;
   hipStream_t s = c->prep;
   if (s != c->st) {
@@ -521,8 +580,8 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
     // producer of d_ids and the last update that read this context's buffers
     HIPCHK(hipEventRecord(c->ev_tmp, c->st));
     HIPCHK(hipStreamWaitEvent(s, c->ev_tmp, 0));
-    // a context taken over from a step that was never updated: its copies may still be reading its lists
-    if (x->state == FETCHED && s != c->side) HIPCHK(hipStreamWaitEvent(s, x->ev_fetched, 0));
+    // a context freed by sfc_discard: its copies may still be reading its lists
+    if (x->discarded && s != c->side) HIPCHK(hipStreamWaitEvent(s, x->ev_fetched, 0));
     if (c->ins) {
       // The unique passes touch the batch table, the per-position table slots, the tally of
       // invalid ids, this step's set of counts, its context's position array and the caller's
@@ -530,13 +589,13 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
       // its resolve has run, so they need not wait for that step's victim, assignment and
       // grouping passes (small grids that leave most of the GPU idle).
       HIPCHK(hipStreamWaitEvent(c->ins, c->ev_tmp, 0));
-      if (x->state == FETCHED) HIPCHK(hipStreamWaitEvent(c->ins, x->ev_fetched, 0));
+      if (x->discarded) HIPCHK(hipStreamWaitEvent(c->ins, x->ev_fetched, 0));
       if (c->resolved_once) HIPCHK(hipStreamWaitEvent(c->ins, c->ev_resolved, 0));
     }
   }
   hipStream_t su = c->ins ? c->ins : s;          // stream of the unique passes
   c->t += 1;
-  x->t = c->t; x->state = PREPARED; x->updated = false; x->main_pending = false;
+  x->t = c->t; x->state = PREPARED; x->updated = false; x->main_pending = false; x->discarded = false;
   x->n_ids = n_ids; x->n_bags = n_bags; x->d_offsets = d_offsets;
   x->d_unique = d_unique_ids; x->d_inverse = d_inverse; x->d_slot = d_slot; x->d_miss = d_miss_vids;
   c->last_prepared = (int)(x - c->ctx);
@@ -573,11 +632,11 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   // from here on behind the whole prepare of the previous step: the step's counters start from
   // that step's, the index is rebuilt if its plan asked for it
   hipLaunchKernelGGL(k_ctr_init, dim3(kGridCap), dim3(256), 0, s, x->ctr, prev->ctr, c->n_unique,
-                     c->n_invalid, c->index, c->hi);
+                     c->n_invalid, c->index, c->hi, x->t);
   hipLaunchKernelGGL(k_index_refill, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
   if (n > 0 && d_offsets)
     hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
-                       d_offsets, (int)n_bags, n, c->pos2bag);
+                       d_offsets, (int)n_bags, n, c->pos2bag, x->ctr);
   const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, cnt, cnt_rep,
@@ -602,7 +661,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cursor, c->cur_rep,
-                       x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff);
+                       x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff, (int)n_bags);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
   HIPCHK(hipEventRecord(x->ev_prepared, s));
@@ -611,6 +670,7 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
 
 int sfc_fetch_misses(sfc_cache* c) {
   if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
   StepCtx* x = c->last_prepared >= 0 ? &c->ctx[c->last_prepared] : nullptr;
   if (!x || x->state != PREPARED) return fail(SFC_ESTATE, "sfc_fetch_misses needs a preceding sfc_prepare");
   // older steps whose update has not been enqueued yet: their bypass rows are not in the Host
@@ -640,6 +700,7 @@ int sfc_fetch_misses(sfc_cache* c) {
 
 int sfc_lookup(sfc_cache* c, float* d_out) {
   if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
   StepCtx* x = training_ctx(c);
   if (!x) return fail(SFC_ESTATE, "sfc_lookup needs sfc_prepare and sfc_fetch_misses first");
   if (x->n_bags > 0 && !d_out) return fail(SFC_EINVAL, "null output");
@@ -659,7 +720,7 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
     } else {
       hipLaunchKernelGGL(k_lookup_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                          x->d_offsets, x->pos_slot, (const float4*)c->cw, (float4*)d_out, total,
-                         c->d4);
+                         c->d4, x->n_ids);
     }
   }
   HIPCHK(hipGetLastError());
@@ -668,6 +729,7 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
 
 int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
   StepCtx* x = training_ctx(c);
   if (!x) return fail(SFC_ESTATE, "sfc_segment_sum needs sfc_prepare and sfc_fetch_misses first");
   if ((x->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
@@ -681,6 +743,7 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
 
 int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
   StepCtx* x = training_ctx(c);
   if (!x) return fail(SFC_ESTATE, "sfc_backward_update needs sfc_prepare and sfc_fetch_misses first");
   if (x->n_bags > 0 && !d_grad) return fail(SFC_EINVAL, "null gradient");
@@ -764,17 +827,112 @@ int sfc_get_stats(sfc_cache* c, sfc_stats* h_out) {
   Ctr h;
   HIPCHK(hipMemcpy(&h, c->ctx[c->last_prepared].ctr, sizeof h, hipMemcpyDeviceToHost));
   if (h.err) {
-    // 1: a lookup walked the whole index, 2: so did an insert, 3: a victim was not in the index,
-    // 4: more victims than the recency histogram promised
     char msg[96];
     snprintf(msg, sizeof msg, "cache manager state is inconsistent (device check %d)", h.err);
-    return fail(SFC_EHIP, msg);
+    return fail(SFC_ECORRUPT, msg);
   }
   const int64_t rowbytes = (int64_t)sizeof(float) * (c->D + c->S);
   h_out->n_unique = h.U; h_out->n_hit = h.n_hit; h_out->n_miss = h.M; h_out->n_evict = h.K;
   h_out->n_bypass = h.n_bypass; h_out->n_invalid = h.n_invalid;
   h_out->h2d_bytes = h.M * rowbytes;
   h_out->d2h_bytes = ((int64_t)h.K + h.n_bypass) * rowbytes;
+  h_out->n_bad_offsets = h.bad_offsets;
+  return SFC_OK;
+}
+
+int sfc_check(sfc_cache* c) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
+  const int bad = ((const volatile HostStatus*)c->hstat)->bad_offsets_step;
+  if (bad > c->reported_bad_step) {
+    c->reported_bad_step = bad;
+    char msg[96];
+    snprintf(msg, sizeof msg, "malformed bag offsets in step %d (most recent such step)", bad);
+    return fail(SFC_EINVAL, msg);
+  }
+  return SFC_OK;
+}
+
+int sfc_peek_stats(sfc_cache* c, sfc_stats* h_out, int64_t* h_step) {
+  if (!c || !h_out || !h_step) return fail(SFC_EINVAL, "null argument");
+  const volatile HostStatus* h = c->hstat;
+  memset(h_out, 0, sizeof *h_out);
+  *h_step = 0;
+  // the kernel that publishes makes the sequence word odd, writes, makes it even: take a copy
+  // that has the same even sequence word before and after
+  for (int tries = 0; tries < 1000; ++tries) {
+    const int s1 = h->seq;
+    if (s1 & 1) continue;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    const int U = h->U, nh = h->n_hit, M = h->M, K = h->K, nb = h->n_bypass, ni = h->n_invalid,
+              bo = h->n_bad_offsets;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    if (h->seq != s1) continue;
+    const int64_t rowbytes = (int64_t)sizeof(float) * (c->D + c->S);
+    h_out->n_unique = U; h_out->n_hit = nh; h_out->n_miss = M; h_out->n_evict = K;
+    h_out->n_bypass = nb; h_out->n_invalid = ni; h_out->n_bad_offsets = bo;
+    h_out->h2d_bytes = M * rowbytes;
+    h_out->d2h_bytes = ((int64_t)K + nb) * rowbytes;
+    *h_step = s1 / 2;
+    return SFC_OK;
+  }
+  return fail(SFC_EHIP, "status block kept changing");
+}
+
+int sfc_discard(sfc_cache* c) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  StepCtx* x = training_ctx(c);
+  if (!x) return fail(SFC_ESTATE, "no fetched step to give up");
+  if (x->main_pending)
+    return fail(SFC_ESTATE, "the step's copies wait for an older update: it cannot be given up yet");
+  x->state = FREE;
+  x->discarded = true;
+  return SFC_OK;
+}
+
+int sfc_verify(sfc_cache* c, int64_t* h_bad) {
+  if (!c || !h_bad) return fail(SFC_EINVAL, "null argument");
+  for (int k = 0; k < c->nctx; ++k)
+    if (c->ctx[k].state == PREPARED)
+      return fail(SFC_ESTATE, "sfc_verify while a prepared step still waits for its rows");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  for (int k = 0; k < 4; ++k) h_bad[k] = 0;
+  if (c->last_prepared < 0) return SFC_OK;
+  int* recount = nullptr;
+  unsigned long long* d_bad = nullptr;
+  HIPCHK(hipMalloc((void**)&recount, (size_t)c->hist_len * sizeof(int)));
+  if (hipMalloc((void**)&d_bad, 4 * sizeof(unsigned long long)) != hipSuccess) {
+    (void)hipFree(recount);
+    return fail(SFC_ENOMEM, "hipMalloc");
+  }
+  hipStream_t s = c->st;
+  fill<int>(s, recount, (int64_t)c->hist_len, 0);
+  fill<unsigned long long>(s, d_bad, 4, 0ull);
+  Ctr* ctr = c->ctx[c->last_prepared].ctr;
+  hipLaunchKernelGGL(k_verify_slots, dim3(grid_for(c->C, 256, kGridCap)), dim3(256), 0, s,
+                     c->slot_id, c->stamp, c->index, c->hi, recount, c->hist_len, d_bad, ctr);
+  hipLaunchKernelGGL(k_verify_entries, dim3(grid_for((int64_t)c->hi, 256, kGridCap)), dim3(256), 0, s,
+                     c->index, c->hi, c->slot_id, (int)c->C, d_bad);
+  hipLaunchKernelGGL(k_verify_hist, dim3(grid_for((int64_t)c->hist_len, 256, kGridCap)), dim3(256), 0, s,
+                     c->hist, recount, c->hist_len, d_bad);
+  unsigned long long hb[4] = {0, 0, 0, 0};
+  hipError_t e = hipMemcpyAsync(hb, d_bad, sizeof hb, hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(recount);
+  (void)hipFree(d_bad);
+  if (e != hipSuccess) return fail(SFC_EHIP, "sfc_verify", e);
+  Ctr h;
+  HIPCHK(hipMemcpy(&h, ctr, sizeof h, hipMemcpyDeviceToHost));
+  h_bad[0] = (int64_t)hb[0]; h_bad[1] = (int64_t)hb[1]; h_bad[2] = (int64_t)hb[2];
+  h_bad[3] = (int64_t)hb[3] - (int64_t)h.f;          // live entries against occupied slots
+  if (h_bad[0] || h_bad[1] || h_bad[2] || h_bad[3]) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "sfc_verify: %lld slots not findable, %lld stray entries, %lld histogram "
+             "words off, %lld live entries beyond the occupied slots",
+             (long long)h_bad[0], (long long)h_bad[1], (long long)h_bad[2], (long long)h_bad[3]);
+    return fail(SFC_ECORRUPT, msg);
+  }
   return SFC_OK;
 }
 

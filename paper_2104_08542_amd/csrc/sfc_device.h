@@ -13,6 +13,18 @@ constexpr int64_t kTomb = -2;       // cache index: deleted entry (ids in the in
 constexpr int kMissMark = -2;       // d_slot value between resolve and assignment
 constexpr int kIntMax = 0x7fffffff;
 
+// Status block in pinned, device-mapped Host memory: kernels write it, the host reads it without
+// waiting for any stream (sfc_check, sfc_peek_stats and the first lines of every step call).
+// The published counters are guarded by a sequence word: odd while a kernel is writing them.
+struct HostStatus {
+  int err;               // first device-side consistency check that fired (0 = none); never cleared
+  int err_step;          // step of that check
+  int bad_offsets_step;  // most recent step whose bag offsets were malformed (0 = none)
+  int pad;
+  int seq;               // 2 * step once that step's counters below are complete
+  int U, n_hit, M, K, n_bypass, n_invalid, n_bad_offsets;
+};
+
 // Device counters of one cache.  Written by kernels only; the host reads a copy in get_stats.
 struct Ctr {
   int U;          // unique ids of the batch
@@ -32,7 +44,19 @@ struct Ctr {
   int err;        // nonzero: a probe loop ran off its bound
   int fetch_on_main;  // pipelined mode: this step's Host copies ran behind the older steps' updates
   int U_prev;     // unique ids of the previous step (its per-tile tallies are still to be read)
+  int t;          // number of the step these counters belong to
+  int bad_offsets;    // violations found in the step's bag offsets (multi-hot input)
+  HostStatus* hstat;  // device view of the cache's status block
 };
+
+// A device-side consistency check fired: remembered in the step's counters (every later step
+// inherits it) and in the Host status block (plain stores over the link: if several checks fire
+// together any one of their codes is kept, which is all the host needs to know).
+__device__ __forceinline__ void flag_err(Ctr* ctr, int code) {
+  ctr->err = code;
+  volatile HostStatus* h = ctr->hstat;
+  if (h) { h->err_step = ctr->t; h->err = code; }
+}
 
 // Entry of the per-step batch table: key and the smallest position that carries it, one 16-byte
 // access for both.

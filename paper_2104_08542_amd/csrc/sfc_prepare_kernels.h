@@ -247,7 +247,8 @@ __global__ __launch_bounds__(1024) void k_scan_chunks(int* data, int n, int* n_u
 // watermark from the previous step's counters, which no kernel changes any more (on the very
 // first step prev == cur and both fields are zero before and after).
 __global__ __launch_bounds__(256) void k_ctr_init(Ctr* cur, const Ctr* prev, const int* n_unique,
-                                                  int* n_invalid, IdxEntry* index, uint32_t hi) {
+                                                  int* n_invalid, IdxEntry* index, uint32_t hi,
+                                                  int t) {
   const bool rebuild = prev->rebuild != 0;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     Ctr c = *prev;
@@ -257,6 +258,7 @@ __global__ __launch_bounds__(256) void k_ctr_init(Ctr* cur, const Ctr* prev, con
     c.n_invalid = *n_invalid;
     *n_invalid = 0;
     c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
+    c.t = t; c.bad_offsets = 0;
     *cur = c;
   }
   if (!rebuild) return;
@@ -354,15 +356,28 @@ __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hs
   }
 }
 
-// Multi-hot input: bag index of every position.
+// Multi-hot input: bag index of every position.  Also checks the bag structure (first offset 0,
+// last offset n, none decreasing); violations are tallied in the step's counters and reported in
+// the Host status block.  A malformed structure cannot make any kernel leave its buffers: ranges
+// are clamped to [0, n] here and in the forward gather, and a position that no bag covers keeps a
+// stale bag number, which the grouping pass clamps to the step's bags.
 __global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ offsets, int n_bags,
-                                                  int n, int* __restrict__ pos2bag) {
+                                                  int n, int* __restrict__ pos2bag, Ctr* ctr) {
   const int b = blockIdx.x * 256 + (int)threadIdx.x;
-  if (b >= n_bags) return;
-  int64_t lo = offsets[b], hi = offsets[b + 1];
-  if (lo < 0) lo = 0;
-  if (hi > n) hi = n;            // malformed offsets cannot write outside the buffer
-  for (int64_t q = lo; q < hi; ++q) pos2bag[q] = b;
+  bool bad = false;
+  if (b < n_bags) {
+    int64_t lo = offsets[b], hi = offsets[b + 1];
+    bad = hi < lo || (b == 0 && lo != 0) || (b == n_bags - 1 && hi != n);
+    if (lo < 0) lo = 0;
+    if (hi > n) hi = n;
+    for (int64_t q = lo; q < hi; ++q) pos2bag[q] = b;
+  }
+  const uint64_t m = __ballot(bad);
+  if (m && lane_id() == 0) {
+    atomicAdd(&ctr->bad_offsets, __popcll(m));
+    volatile HostStatus* h = ctr->hstat;
+    if (h) h->bad_offsets_step = ctr->t;
+  }
 }
 
 // Grouping of positions by virtual id (counting sort): perm64[cursor[v]++] = (v << 32) | payload,
@@ -378,7 +393,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
                                                   int* cur_rep,
                                                   int64_t* __restrict__ perm64,
                                                   const int* __restrict__ slot,
-                                                  int* rank_slot, int C, int boff) {
+                                                  int* rank_slot, int C, int boff, int n_bags) {
   __shared__ int lh[kHotBins];
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
@@ -391,6 +406,8 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
     vv[j] = p < n ? inverse[p] : -1;
     rr[j] = p < n ? rank_slot[p] : 0;           // meaningful for the ids outside the LDS range only
     pay[j] = (p < n && pos2bag) ? pos2bag[p] : p;
+    // a position that malformed offsets left uncovered carries a stale bag number
+    if (pos2bag && (unsigned)pay[j] >= (unsigned)n_bags) pay[j] = 0;
   }
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
@@ -468,7 +485,7 @@ __device__ __forceinline__ int index_find(const IdxEntry* __restrict__ index, ui
     h += kProbeBatch;
     if (h >= hi) h -= hi;
   }
-  ctr->err = 1;
+  flag_err(ctr, 1);
   return -1;
 }
 
@@ -498,7 +515,7 @@ __device__ __forceinline__ bool index_insert(IdxEntry* index, uint32_t hi, int64
     h += kProbeBatch;
     if (h >= hi) h -= hi;
   }
-  ctr->err = 2;
+  flag_err(ctr, 2);
   return false;
 }
 
@@ -701,6 +718,17 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
     // eighth of the index would be deleted entries
     if ((unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
+    // the step's counters are final: publish them to the Host status block (sequence word odd
+    // while they are being written)
+    volatile HostStatus* h = ctr->hstat;
+    if (h) {
+      h->seq = 2 * t - 1;
+      __threadfence_system();
+      h->U = U; h->n_hit = ctr->n_hit; h->M = M; h->K = K; h->n_bypass = n_bypass;
+      h->n_invalid = ctr->n_invalid; h->n_bad_offsets = ctr->bad_offsets;
+      __threadfence_system();
+      h->seq = 2 * t;
+    }
   }
 }
 
@@ -788,7 +816,7 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
       idx[j] = -1;
       if (is_lt || (is_eq && eq_before < r)) {
         idx[j] = lt_before + (eq_before < r ? eq_before : r);
-        if (idx[j] >= K) { idx[j] = -1; ctr->err = 4; }     // never while hist mirrors the stamps
+        if (idx[j] >= K) { idx[j] = -1; flag_err(ctr, 4); }     // never while hist mirrors the stamps
       }
       lt_before += is_lt;
       eq_before += is_eq;
@@ -815,7 +843,7 @@ __global__ __launch_bounds__(256) void k_victim_unmap(const int64_t* __restrict_
     if (index_find(index, hi, victim_id[k], &where, ctr) >= 0)
       atomicExch((unsigned long long*)&index[where].key, (unsigned long long)kTomb);
     else
-      ctr->err = 3;
+      flag_err(ctr, 3);
   }
 }
 
@@ -882,6 +910,72 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
     const int nre = block_sum(reused ? 1 : 0, smem);
     if (threadIdx.x == 0) tile_reuse[tile] = nre;
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Test aid (sfc_verify): recount of the manager state after a complete prepare.
+//   bad[0]  occupied slots (below the watermark) whose id the index does not map to that slot
+//   bad[1]  live index entries that do not point at a slot holding their id
+//   bad[2]  words of the recency histogram that differ from the recount of the slots' stamps
+//   bad[3]  live index entries (the host compares them with the number of occupied slots)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void tally(unsigned long long* word, int mine) {
+  const int w = wave_sum(mine);
+  if (w && lane_id() == 0) atomicAdd(word, (unsigned long long)w);
+}
+
+__global__ __launch_bounds__(256) void k_verify_slots(const int64_t* __restrict__ slot_id,
+                                                       const int* __restrict__ stamp,
+                                                       const IdxEntry* __restrict__ index,
+                                                       uint32_t hi, int* recount, int hist_len,
+                                                       unsigned long long* bad, Ctr* ctr) {
+  const int f = ctr->f;
+  const int rounds = (f + (int)gridDim.x * 256 - 1) / ((int)gridDim.x * 256);
+  int s = blockIdx.x * 256 + (int)threadIdx.x;
+  for (int it = 0; it < rounds; ++it, s += gridDim.x * 256) {   // every lane stays for the wave sums
+    int lost = 0, off = 0;
+    if (s < f) {
+      const int64_t id = slot_id[s];
+      if (id < 0 || index_find(index, hi, id, nullptr, ctr) != s) lost = 1;
+      const int st = stamp[s];
+      if (st >= 0 && st < hist_len) atomicAdd(&recount[st], 1); else off = 1;
+    }
+    tally(&bad[0], lost);
+    tally(&bad[2], off);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_verify_entries(const IdxEntry* __restrict__ index,
+                                                         uint32_t hi,
+                                                         const int64_t* __restrict__ slot_id, int C,
+                                                         unsigned long long* bad) {
+  const uint32_t stride = gridDim.x * 256;
+  const uint32_t rounds = (hi + stride - 1) / stride;
+  uint32_t i = blockIdx.x * 256 + threadIdx.x;
+  int live = 0, stray = 0;
+  for (uint32_t it = 0; it < rounds; ++it, i += stride) {
+    if (i < hi) {
+      const int4 raw = *reinterpret_cast<const int4*>(&index[i]);
+      const int64_t key = idx_key(raw);
+      if (key >= 0) {
+        ++live;
+        if (raw.z < 0 || raw.z >= C || slot_id[raw.z] != key) ++stray;
+      }
+    }
+  }
+  tally(&bad[3], live);
+  tally(&bad[1], stray);
+}
+
+__global__ __launch_bounds__(256) void k_verify_hist(const int* __restrict__ hist,
+                                                      const int* __restrict__ recount, int hist_len,
+                                                      unsigned long long* bad) {
+  const int stride = (int)gridDim.x * 256;
+  const int rounds = (hist_len + stride - 1) / stride;
+  int i = blockIdx.x * 256 + (int)threadIdx.x, off = 0;
+  for (int it = 0; it < rounds; ++it, i += stride)
+    if (i < hist_len && hist[i] != recount[i]) ++off;
+  tally(&bad[2], off);
 }
 
 }  // namespace sfc

@@ -175,13 +175,16 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
                                                       const int* __restrict__ pos_slot,
                                                       const float4* __restrict__ cw,
                                                       float4* __restrict__ out, int64_t total,
-                                                      int d4) {
+                                                      int d4, int64_t n_ids) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= total) return;
   const int64_t b = i / d4;
   const int c = (int)(i % d4);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int64_t q = offsets[b], e = offsets[b + 1]; q < e; ++q) {
+  int64_t q = offsets[b], e = offsets[b + 1];
+  if (q < 0) q = 0;                   // malformed offsets are reported by the prepare step; here
+  if (e > n_ids) e = n_ids;           // they only must not lead outside pos_slot
+  for (; q < e; ++q) {
     const int s = pos_slot[q];
     if (s >= 0) {
       const float4 v = cw[(int64_t)s * d4 + c];

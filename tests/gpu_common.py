@@ -26,7 +26,7 @@ def same_stats(st, ost, table):
         st = dict(st)
         scale = lambda b: b // (table.dim + 4) * (table.dim + 1)
         st["h2d_bytes"], st["d2h_bytes"] = scale(st["h2d_bytes"]), scale(st["d2h_bytes"])
-    return st == ost
+    return {k: st[k] for k in ost} == ost and st["n_bad_offsets"] == 0
 
 
 class Pair:
@@ -92,6 +92,7 @@ class Pair:
         out = c.lookup()
         assert_close(out.cpu().numpy(), o.lookup(), "lookup")
         if not update:
+            c.discard()
             return pr
         if check_common:
             cg = c.segment_sum(d_grad)
@@ -109,6 +110,8 @@ class Pair:
         return pr
 
     def finish(self, chunk_rows=1 << 20):
+        self.cache.check()                    # nothing reported by the device on the way
+        assert self.cache.verify() == [0, 0, 0, 0]   # index, slots and recency histogram recounted
         self.cache.flush()
         self.orc.flush()
         # chunked: identical chunks (rows never touched) are skipped by a plain memory compare

@@ -35,6 +35,6 @@ def test_error_strings_and_argument_checks_need_no_gpu():
 
 def test_struct_layout_matches_header():
     import paper_2104_08542_amd as sfc
-    assert ctypes.sizeof(sfc.sfc_config) == 128 and ctypes.sizeof(sfc.sfc_stats) == 64
+    assert ctypes.sizeof(sfc.sfc_config) == 128 and ctypes.sizeof(sfc.sfc_stats) == 72
     assert sfc.sfc_config.h_weights.offset == 40 and sfc.sfc_config.stream.offset == 80
     assert sfc.sfc_config.optimizer.offset == 96 and sfc.sfc_config.beta1.offset == 112

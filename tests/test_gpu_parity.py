@@ -311,3 +311,110 @@ def test_many_rebuilds_with_many_victims(lookahead):
         assert ev > 5 * C
         p.finish()
     p.close()
+
+
+@pytest.mark.parametrize("max_ids", [1, 5, 16, 31])
+def test_tiny_max_ids_with_id_zero(max_ids):
+    # batch tables smaller than the 64 entries the unique pass always probes; id 0 is the value
+    # that zero-filled memory would pass for
+    V, D = 50, 4
+    p = Pair(V, D, C=8, max_ids=max_ids)
+    rng = np.random.default_rng(max_ids)
+    for t in range(6):
+        n = max_ids if t % 2 == 0 else max(1, max_ids // 2)
+        ids = rng.integers(0, V, n)
+        ids[rng.integers(0, n)] = 0
+        if n > 2:
+            ids[-1] = 0                      # id 0 again, later: its first appearance must win
+        p.step(ids, si.grads(n, D, 90 + max_ids, t).numpy())
+    p.finish(); p.close()
+
+
+def test_malformed_offsets_are_reported_not_followed():
+    # the oracle refuses such a batch; the device cannot be refused on the host (the offsets live
+    # in device memory), so the kernels count the violations, stay inside their buffers and the
+    # step is reported by sfc_check and in the stats
+    import paper_2104_08542_amd as sfc
+    from oracle import Oracle
+    V, D = 200, 8
+    ids = np.arange(40) % 23
+    good = np.array([0, 5, 5, 17, 30, 40])
+    cases = [np.array([1, 5, 5, 17, 30, 40]),          # does not start at 0
+             np.array([0, 5, 5, 17, 30, 39]),          # does not end at n_ids
+             np.array([0, 5, 5, 17, 30, 4000]),        # ends far outside
+             np.array([0, 17, 5, 30, 30, 40]),         # decreasing
+             np.array([0, -7, 5, 30, 30, 40])]         # negative
+    for k, off in enumerate(cases):
+        p = Pair(V, D, C=64, max_ids=64, max_bags=8)
+        p.step(ids, si.grads(5, D, 3, 0).numpy(), offsets=good)       # a good step first
+        tab = np.zeros((V, D), np.float32)
+        with pytest.raises(ValueError):                 # the oracle's -1
+            Oracle(64, D, tab.copy(), tab.copy()).prepare(ids.astype(np.int64), off.astype(np.int64))
+        c = p.cache
+        c.prepare(torch.from_numpy(ids).to(p.dev), torch.from_numpy(off.astype(np.int64)).to(p.dev))
+        st = c.stats()
+        assert st["n_bad_offsets"] >= 1, (k, st)
+        c.fetch_misses()
+        out = c.lookup()
+        c.backward_update(torch.zeros(5, D, device=p.dev))
+        torch.cuda.synchronize()
+        assert out.shape == (5, D)
+        with pytest.raises(sfc.SfcError) as e:
+            c.check()
+        assert e.value.code == sfc.SFC_EINVAL and "step 2" in str(e.value)
+        c.check()                                       # reported once
+        assert c.verify() == [0, 0, 0, 0]               # the manager state depends on the ids alone
+        pk, step = c.peek_stats()
+        assert step == 2 and pk["n_bad_offsets"] == st["n_bad_offsets"]
+        p.close()
+
+
+def test_status_block_needs_no_waiting():
+    # counters and health of the latest planned step, read from pinned memory
+    V, D, n = 5000, 8, 3000
+    p = Pair(V, D, C=1500, max_ids=4096, lookahead=2)
+    c = p.cache
+    assert c.peek_stats()[1] == 0
+    want = []
+    for t in range(5):
+        ids = si.zipf_ids(n, 1.05, V, 21, t).numpy()
+        pr = p.orc.prepare(ids, None); p.orc.fetch_misses(); p.orc.lookup()
+        p.orc.backward_update(si.grads(n, D, 21, t).numpy())
+        want.append(pr.stats)
+        c.prepare(torch.from_numpy(ids).to(p.dev)); c.fetch_misses()
+        if t >= 2:
+            c.lookup(); c.backward_update(si.grads(n, D, 21, t - 2).to(p.dev))
+        c.check()
+        torch.cuda.synchronize()
+        pk, step = c.peek_stats()
+        assert step == t + 1 and {k: pk[k] for k in want[t]} == want[t]
+    p.close()
+
+
+def test_discard_frees_a_step_that_was_only_read():
+    import paper_2104_08542_amd as sfc
+    V, D, n = 3000, 8, 800
+    p = Pair(V, D, C=1000, max_ids=1024, lookahead=1)
+    c = p.cache
+    ids = [torch.from_numpy(si.zipf_ids(n, 1.1, V, 44, t).numpy()).to(p.dev) for t in range(4)]
+    c.prepare(ids[0]); c.fetch_misses()
+    c.prepare(ids[1]); c.fetch_misses()
+    with pytest.raises(sfc.SfcError) as e:              # both contexts hold steps that were not updated
+        c.prepare(ids[2])
+    assert e.value.code == sfc.SFC_ESTATE
+    a = c.lookup().clone()
+    c.discard()                                          # step 1 given up, rows stay as they are
+    c.prepare(ids[2]); c.fetch_misses()
+    b = c.lookup().clone()                               # step 2
+    c.discard()
+    c.prepare(ids[0]); c.fetch_misses()                  # the ids of step 1 again: all hits now
+    c.lookup(); c.discard()
+    again = c.lookup()                                   # step 4 = ids[0]: same rows as the first lookup
+    assert torch.equal(again, a)
+    assert c.stats()["n_miss"] == 0
+    c.discard()
+    with pytest.raises(sfc.SfcError) as e:
+        c.discard()
+    assert e.value.code == sfc.SFC_ESTATE
+    assert c.verify() == [0, 0, 0, 0]
+    p.close()
