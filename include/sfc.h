@@ -206,6 +206,20 @@ int sfc_lookup(sfc_cache* c, float* d_out);
 int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad);
 
 /*
+ * sfc_segment_sum for callers that must not allocate or depend on allocations made for them: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs and result (bit for bit), but the kernels' scratch (the partial sums of runs that cross
+ * a thread block's edge) lives in a fixed array inside the library's code object instead of the
+ * buffer sfc_cache_create allocated: SFC_STATIC_SCRATCH_BYTES per GPU, held until the process
+ * ends.  Returns SFC_ELIMIT when the step needs more (2 * blocks * (8 * dim + 4) bytes, blocks =
+ * wavefronts of the stream / 4; the target configuration takes 1.6 MB).  Calls no allocating
+ * routine and creates no events.  Every call on one GPU shares the array: calls that overlap on
+ * one GPU (two caches on two streams) race; nothing needs clearing between calls.
+ */
+#define SFC_STATIC_SCRATCH_BYTES (8 << 20)
+int sfc_segment_sum_static(sfc_cache* c, const float* d_grad, float* d_common_grad);
+
+/*
  * Step 4 (GPU-Worker / Backward; Algorithm 1 line 14): segment-sum d_grad [n_bags, D] per
  * virtual id as above and apply one optimizer update per unique row in the cache (fp32):
  *   ADAGRAD          acc += g*g ;  w -= lr * g / (sqrt(acc) + eps)             (element-wise)

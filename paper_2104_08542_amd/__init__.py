@@ -29,6 +29,7 @@ EXPORTS = [
     "sfc_fetch_misses", "sfc_lookup", "sfc_segment_sum", "sfc_backward_update", "sfc_flush",
     "sfc_get_stats", "sfc_cache_state", "sfc_profile_enable", "sfc_profile_read", "sfc_strerror",
     "sfc_last_error", "sfc_check", "sfc_peek_stats", "sfc_discard", "sfc_verify",
+    "sfc_segment_sum_static",
 ]
 
 
@@ -72,6 +73,7 @@ def _load():
     lib.sfc_fetch_misses.restype, lib.sfc_fetch_misses.argtypes = ci, [vp]
     lib.sfc_lookup.restype, lib.sfc_lookup.argtypes = ci, [vp, vp]
     lib.sfc_segment_sum.restype, lib.sfc_segment_sum.argtypes = ci, [vp, vp, vp]
+    lib.sfc_segment_sum_static.restype, lib.sfc_segment_sum_static.argtypes = ci, [vp, vp, vp]
     lib.sfc_backward_update.restype, lib.sfc_backward_update.argtypes = ci, [vp, vp]
     lib.sfc_flush.restype, lib.sfc_flush.argtypes = ci, [vp]
     lib.sfc_get_stats.restype, lib.sfc_get_stats.argtypes = ci, [vp, ctypes.POINTER(sfc_stats)]
@@ -152,6 +154,11 @@ def sfc_lookup(h, d_out):
 def sfc_segment_sum(h, d_grad, d_common_grad):
     _check(_lib.sfc_segment_sum(ctypes.c_void_p(h), _dptr(d_grad, torch.float32),
                                 _dptr(d_common_grad, torch.float32)))
+
+
+def sfc_segment_sum_static(h, d_grad, d_common_grad):
+    _check(_lib.sfc_segment_sum_static(ctypes.c_void_p(h), _dptr(d_grad, torch.float32),
+                                       _dptr(d_common_grad, torch.float32)))
 
 
 def sfc_backward_update(h, d_grad):

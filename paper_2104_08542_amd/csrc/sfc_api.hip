@@ -52,6 +52,28 @@ int fail(int code, const char* what, hipError_t e = hipSuccess) {
     if (e_ != hipSuccess) return fail(SFC_EHIP, #call, e_);     \
   } while (0)
 
+// Scratch of sfc_segment_sum_static: lives in the code object, one copy per GPU that loads the
+// library, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address that kernels and copies use is scratch_ptr[device].
+static __device__ __align__(256) unsigned char scratch[SFC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* scratch_ptr[kMaxDevices] = {};
+std::mutex scratch_mu;
+
+// The device address of `scratch` on the current device (looked up once per device).
+int static_scratch(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return fail(SFC_EINVAL, "device number out of range");
+  std::lock_guard<std::mutex> lk(scratch_mu);
+  if (!scratch_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(SFC_EHIP, "hipGetSymbolAddress(scratch)", e);
+    scratch_ptr[device] = p;
+  }
+  *out = scratch_ptr[device];
+  return SFC_OK;
+}
+
 // life of a step context
 enum State { FREE = 0, PREPARED = 1, FETCHED = 2 };
 enum { P_PREPARE = 0, P_FETCH = 1, P_LOOKUP = 2, P_BACKWARD = 3, P_SEG_STREAM = 4, P_SEG_FINISH = 5,
@@ -273,21 +295,24 @@ int rows_ready(sfc_cache* c, StepCtx* x) {
 }
 
 // common[v] = segment sum of d_grad over the step's grouping: the stream, then the block-edge partials.
-int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common) {
+// bp / bp_vid: the block-edge partial sums and their virtual ids, 2 per block of the stream; timed:
+// bracket the two kernels with profiling events (which may have to be created).
+int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common, double* bp,
+               int* bp_vid, bool timed) {
   const int n = (int)x->n_ids;
   if (n <= 0) return SFC_OK;
   const SegGeom g = seg_geom(c->D, n);
   const int nblk = (g.waves + 3) / 4;
   EventPair e1{}, e2{};
   int rc;
-  if ((rc = prof_begin(c, P_SEG_STREAM, c->st, &e1))) return rc;
+  if (timed && (rc = prof_begin(c, P_SEG_STREAM, c->st, &e1))) return rc;
   hipLaunchKernelGGL(k_seg_stream, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
-                     x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, c->bp, c->bp_vid);
-  if ((rc = prof_end(c, P_SEG_STREAM, c->st, &e1))) return rc;
-  if ((rc = prof_begin(c, P_SEG_FINISH, c->st, &e2))) return rc;
-  hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, c->bp,
-                     c->bp_vid, 2 * nblk, c->d4, (float4*)d_common);
-  return prof_end(c, P_SEG_FINISH, c->st, &e2);
+                     x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
+  if (timed && (rc = prof_end(c, P_SEG_STREAM, c->st, &e1))) return rc;
+  if (timed && (rc = prof_begin(c, P_SEG_FINISH, c->st, &e2))) return rc;
+  hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, bp,
+                     bp_vid, 2 * nblk, c->d4, (float4*)d_common);
+  return timed ? prof_end(c, P_SEG_FINISH, c->st, &e2) : SFC_OK;
 }
 
 int sync_all(sfc_cache* c) {
@@ -736,7 +761,44 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
   int rc;
   if ((rc = rows_ready(c, x))) return rc;
-  if ((rc = seg_launch(c, x, d_grad, d_common_grad))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad, c->bp, c->bp_vid, true))) return rc;
+  HIPCHK(hipGetLastError());
+  return SFC_OK;
+}
+
+int sfc_segment_sum_static(sfc_cache* c, const float* d_grad, float* d_common_grad) {
+  if (!c) return fail(SFC_EINVAL, "null cache");
+  if (int hrc = healthy(c)) return hrc;
+  StepCtx* x = training_ctx(c);
+  if (!x) return fail(SFC_ESTATE, "sfc_segment_sum_static needs sfc_prepare and sfc_fetch_misses first");
+  if ((x->n_bags > 0 && !d_grad) || !d_common_grad) return fail(SFC_EINVAL, "null buffer");
+  if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev != c->device) return fail(SFC_EINVAL, "the cache lives on another device than the current one");
+  // the scratch the step needs: per block of the stream two fp64 rows and two virtual ids
+  const SegGeom g = seg_geom(c->D, x->n_ids > 0 ? x->n_ids : 1);
+  const int64_t nblk = (g.waves + 3) / 4;
+  const int64_t sums = 2 * nblk * c->D * (int64_t)sizeof(double);
+  const int64_t need = sums + 2 * nblk * (int64_t)sizeof(int);
+  if (need > (int64_t)SFC_STATIC_SCRATCH_BYTES) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "sfc_segment_sum_static: this step needs %lld bytes of scratch, the "
+             "fixed array holds %d", (long long)need, (int)SFC_STATIC_SCRATCH_BYTES);
+    return fail(SFC_ELIMIT, msg);
+  }
+  void* base = nullptr;
+  int rc;
+  if ((rc = static_scratch(dev, &base))) return rc;
+  // both launches of the step's copies must have been issued already: issuing the second one here
+  // could create profiling events
+  if (x->main_pending)
+    return fail(SFC_ESTATE, "the step's rows are still due on the main stream: call sfc_lookup first");
+  if (c->side != c->st) HIPCHK(hipStreamWaitEvent(c->st, x->ev_fetched, 0));
+  // every slot that k_seg_finish reads is written by k_seg_stream in the same call: nothing to clear
+  double* bp = (double*)base;
+  int* bp_vid = (int*)((unsigned char*)base + sums);
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad, bp, bp_vid, false))) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -753,7 +815,7 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   hipStream_t s = c->st;
   EventPair ep{}, e1{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
-  if ((rc = seg_launch(c, x, d_grad, c->gsum))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true))) return rc;
   if (c->cfg.policy == SFC_POLICY_PREFETCH) {
     // the copies of a newer step issued so far read the Host table before this update writes it
     for (int k = 0; k < c->nctx; ++k) {
