@@ -57,12 +57,13 @@ class sfc_stats(ctypes.Structure):
                  "d2h_bytes", "n_bad_offsets")]
 
 
-def _load():
-    if not os.path.exists(LIB_PATH):
+def _load(path=None):
+    path = path or LIB_PATH
+    if not os.path.exists(path):
         raise RuntimeError(
             "libsfc.so is not built (%s); run `python paper_2104_08542_amd/build.py` or "
-            "__graft_entry__.build(). There is no fallback path." % LIB_PATH)
-    lib = ctypes.CDLL(LIB_PATH)
+            "__graft_entry__.build(). There is no fallback path." % path)
+    lib = ctypes.CDLL(path)
     vp, i64, i32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int
     lib.sfc_host_alloc.restype, lib.sfc_host_alloc.argtypes = vp, [i64]
     lib.sfc_host_free.restype, lib.sfc_host_free.argtypes = None, [vp]

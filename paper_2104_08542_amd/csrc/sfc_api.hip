@@ -140,9 +140,12 @@ struct sfc_cache {
   UEntry* utab = nullptr; int* uvid = nullptr;  // batch table [2*max_ids]: key + first position; vid
   int* hslot = nullptr;                         // [max_ids]
   int* vid_hslot = nullptr;                     // [max_ids]
-  int* blk_cnt = nullptr;                       // [max_ids / kPosChunk + 1]
+  // single-pass prefixes (look-back): state words of the rank pass [max_ids / kPosChunk + 2] and of
+  // the victim pass [C / kPosChunk + 2], their ticket counters, and the count of finished
+  // resolve blocks; all zero between kernels
+  unsigned long long *lb_rank = nullptr, *lb_victim = nullptr;
+  int* lb_ticket = nullptr;                     // [0] rank pass, [1] victim pass, [2] resolve blocks done
   int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
-  int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
   // positions per virtual id [max_ids] and its copies for the lowest virtual ids [kHotRep, kHotBins]:
   // two sets, used by steps of even / odd number, so that the unique passes of a step can run
   // beside the previous step's miss assignment and grouping, which still read that step's counts
@@ -249,6 +252,8 @@ int healthy(sfc_cache* c) {
 }
 
 constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
+constexpr int kVictimGrid = 1024;  // blocks of the victim pass (each draws tiles until none are left)
+constexpr int kRebuildGrid = 512;  // blocks of the two launches that only work when the index is rebuilt
 
 // The step that lookup / segment_sum / backward_update act on: the oldest one whose rows are (or
 // are about to be) in place and that has not been updated yet.
@@ -306,8 +311,12 @@ int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common, d
   EventPair e1{}, e2{};
   int rc;
   if (timed && (rc = prof_begin(c, P_SEG_STREAM, c->st, &e1))) return rc;
-  hipLaunchKernelGGL(k_seg_stream, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
-                     x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
+  if (x->d_offsets)
+    hipLaunchKernelGGL(k_seg_stream<false>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
+                       x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
+  else
+    hipLaunchKernelGGL(k_seg_stream<true>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
+                       x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
   if (timed && (rc = prof_end(c, P_SEG_STREAM, c->st, &e1))) return rc;
   if (timed && (rc = prof_begin(c, P_SEG_FINISH, c->st, &e2))) return rc;
   hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, bp,
@@ -507,10 +516,10 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->uvid, hu))) goto bad;
     if ((rc = dalloc(c, &c->hslot, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->vid_hslot, c->max_ids))) goto bad;
-    if ((rc = dalloc(c, &c->blk_cnt, c->max_ids / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->lb_rank, c->max_ids / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->lb_victim, c->C / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->lb_ticket, 4))) goto bad;
     if ((rc = dalloc(c, &c->tile_miss, c->max_ids / kVidTile + 2))) goto bad;
-    if ((rc = dalloc(c, &c->tile_lt, c->C / kPosChunk + 2))) goto bad;
-    if ((rc = dalloc(c, &c->tile_eq, c->C / kPosChunk + 2))) goto bad;
     if ((rc = dalloc(c, &c->cnt2[0], c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->cnt2[1], c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->n_unique, 1))) goto bad;
@@ -557,6 +566,9 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->cnt_rep2[0], (int64_t)kHotRep * kHotBins, 0);
     fill<int>(s, c->cnt_rep2[1], (int64_t)kHotRep * kHotBins, 0);
     fill<int>(s, c->n_unique, 1, 0);
+    fill<unsigned long long>(s, c->lb_rank, c->max_ids / kPosChunk + 2, 0ull);
+    fill<unsigned long long>(s, c->lb_victim, c->C / kPosChunk + 2, 0ull);
+    fill<int>(s, c->lb_ticket, 4, 0);
     fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
@@ -641,14 +653,13 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
     if (nub > head)
       hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, su, d_ids, n, c->V, c->utab,
                          hu, c->hslot, c->n_invalid, head);
-    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n, c->blk_cnt);
-  }
-  hipLaunchKernelGGL(k_scan_chunks, dim3(1), dim3(1024), 0, su, c->blk_cnt, nchunk, c->n_unique);
-  if (n > 0) {
-    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n,
-                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, cnt);
+    hipLaunchKernelGGL(k_uniq_rank, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n, c->lb_rank,
+                       c->lb_ticket, d_unique_ids, c->uvid, c->vid_hslot, cnt, c->n_unique, c->d_hstat,
+                       x->t);
     hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, su,
-                       c->hslot, c->uvid, n, d_inverse, cnt, cnt_rep, x->pos_slot);
+                       c->hslot, c->uvid, n, d_inverse, cnt, cnt_rep, x->pos_slot, c->lb_rank, nchunk);
+  } else {
+    fill<int>(su, c->n_unique, 1, 0);
   }
   if (su != s) {
     HIPCHK(hipEventRecord(c->ev_inserted, su));
@@ -656,33 +667,27 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   }
   // from here on behind the whole prepare of the previous step: the step's counters start from
   // that step's, the index is rebuilt if its plan asked for it
-  hipLaunchKernelGGL(k_ctr_init, dim3(kGridCap), dim3(256), 0, s, x->ctr, prev->ctr, c->n_unique,
+  hipLaunchKernelGGL(k_ctr_init, dim3(kRebuildGrid), dim3(256), 0, s, x->ctr, prev->ctr, c->n_unique,
                      c->n_invalid, c->index, c->hi, x->t);
-  hipLaunchKernelGGL(k_index_refill, dim3(kGridCap), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
+  hipLaunchKernelGGL(k_index_refill, dim3(kRebuildGrid), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
   if (n > 0 && d_offsets)
     hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
                        d_offsets, (int)n_bags, n, c->pos2bag, x->ctr);
   const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, cnt, cnt_rep,
-                     c->tile_cnt, c->age_hist, x->ctr);
+                     c->tile_cnt, c->age_hist, x->ctr, c->tile_reuse, c->cfg.lookahead, (int)c->C,
+                     c->lb_ticket + 2);
   if (c->ins) { HIPCHK(hipEventRecord(c->ev_resolved, s)); c->resolved_once = true; }
-  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
-                     c->tile_reuse,
-                     c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
-  const int gs = grid_for(c->C, kPosChunk, kGridCap);
-  hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
-                     x->ctr);
-  hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
-                     c->tile_eq, x->victim_slot, x->victim_id, x->ctr);
+  const int gs = grid_for(c->C, kPosChunk, kVictimGrid);
+  hipLaunchKernelGGL(k_victims, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->lb_victim,
+                     c->lb_ticket + 1, x->victim_slot, x->victim_id, c->index, c->hi, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);
-  hipLaunchKernelGGL(k_victim_unmap, dim3(gv), dim3(256), 0, s, x->victim_id, c->index, c->hi,
-                     x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, cnt, cnt_rep,
                      c->cur_rep, c->tile_cnt,
                      c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,
-                     c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
+                     c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr, c->lb_victim);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cursor, c->cur_rep,
@@ -743,9 +748,11 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
                          dim3(256), 0, s, x->pos_slot, (const float4*)c->cw, (float4*)d_out,
                          (int)x->n_bags, d4, sh);
     } else {
-      hipLaunchKernelGGL(k_lookup_bags, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                         x->d_offsets, x->pos_slot, (const float4*)c->cw, (float4*)d_out, total,
-                         c->d4, x->n_ids);
+      const int G = 64 / c->d4 > 0 ? 64 / c->d4 : 1;          // bags per wavefront
+      const int64_t per_block = 4 * (int64_t)G;
+      hipLaunchKernelGGL(k_lookup_bags, dim3((unsigned)((x->n_bags + per_block - 1) / per_block)),
+                         dim3(256), 0, s, x->d_offsets, x->pos_slot, (const float4*)c->cw,
+                         (float4*)d_out, (int)x->n_bags, c->d4, G, x->n_ids);
     }
   }
   HIPCHK(hipGetLastError());

@@ -18,6 +18,12 @@ __device__ __forceinline__ void st_stream(float4* p, float4 v) {
   vf4 x; x.x = v.x; x.y = v.y; x.z = v.z; x.w = v.w;
   __builtin_nontemporal_store(x, reinterpret_cast<vf4*>(p));
 }
+// kStream: the datum is read once per step (streamed); otherwise it is read again by other lanes
+// later in the same kernel and should stay cached
+template <bool kStream>
+__device__ __forceinline__ float4 ld_row(const float4* p) { return kStream ? ld_stream(p) : *p; }
+template <bool kStream>
+__device__ __forceinline__ void st_row(float4* p, float4 v) { if (kStream) st_stream(p, v); else *p = v; }
 
 // ---------------------------------------------------------------------------------------------
 // Host link (Algorithm 1 lines 5-6).  The Host table is pinned, device-mapped memory; the kernels
@@ -171,27 +177,59 @@ __global__ __launch_bounds__(256) void k_lookup_onehot(const int* __restrict__ p
   }
 }
 
+// Multi-hot forward (sum pooling): out[b] = sum over the positions q of bag b of the cached row of
+// position q, fp32 adds in bag order.  A row is d4 lanes of 16 bytes, so a wavefront holds
+// G = 64 / d4 lane groups and each group owns one bag: its lanes read the bag's slots (one
+// broadcast load per position), keep kBagUnroll row chunks in flight per lane and fetch the
+// slots of the next kBagUnroll positions meanwhile, so that the chain offsets -> slot -> row is
+// walked once per kBagUnroll rows instead of once per row.  The four bags of a wavefront are
+// neighbours, so its stores are contiguous (G * d4 * 16 bytes) and non-temporal.
+// Bags are short (1-20 ids in the benchmark's multi-hot configuration), so the lane groups of a
+// wavefront finish at different times; the idle lanes cost nothing that matters here, the kernel
+// is bound by the row traffic (every position reads a full row; only the rows that are hot
+// enough to stay in an XCD's L2 are not fetched again).
+// Malformed offsets are reported by the prepare step; here they only must not lead outside
+// pos_slot, hence the clamp to [0, n_ids].
+#ifndef SFC_BAG_UNROLL
+#define SFC_BAG_UNROLL 8
+#endif
+constexpr int kBagUnroll = SFC_BAG_UNROLL;
+
 __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__ offsets,
                                                       const int* __restrict__ pos_slot,
                                                       const float4* __restrict__ cw,
-                                                      float4* __restrict__ out, int64_t total,
-                                                      int d4, int64_t n_ids) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int64_t b = i / d4;
-  const int c = (int)(i % d4);
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                                                      float4* __restrict__ out, int n_bags,
+                                                      int d4, int G, int64_t n_ids) {
+  const int lane = lane_id();
+  const int g = lane / d4, c = lane - g * d4;
+  const int64_t b = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * G + g;
+  if (g >= G || b >= n_bags) return;
   int64_t q = offsets[b], e = offsets[b + 1];
-  if (q < 0) q = 0;                   // malformed offsets are reported by the prepare step; here
-  if (e > n_ids) e = n_ids;           // they only must not lead outside pos_slot
-  for (; q < e; ++q) {
-    const int s = pos_slot[q];
-    if (s >= 0) {
-      const float4 v = cw[(int64_t)s * d4 + c];
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  if (q < 0) q = 0;
+  if (e > n_ids) e = n_ids;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  int sl[kBagUnroll], sn[kBagUnroll];
+#pragma unroll
+  for (int k = 0; k < kBagUnroll; ++k) sl[k] = q + k < e ? pos_slot[q + k] : -1;
+  for (; q < e; q += kBagUnroll) {
+    float4 v[kBagUnroll];
+#pragma unroll
+    for (int k = 0; k < kBagUnroll; ++k) {
+      v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (sl[k] >= 0) v[k] = cw[(int64_t)sl[k] * d4 + c];
+    }
+#pragma unroll
+    for (int k = 0; k < kBagUnroll; ++k) {
+      const int64_t qn = q + kBagUnroll + k;
+      sn[k] = qn < e ? pos_slot[qn] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < kBagUnroll; ++k) {
+      acc.x += v[k].x; acc.y += v[k].y; acc.z += v[k].z; acc.w += v[k].w;
+      sl[k] = sn[k];
     }
   }
-  st_stream(&out[i], acc);
+  st_stream(&out[b * d4 + c], acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -287,6 +325,11 @@ __device__ __forceinline__ void chain_slots(int nslots, const int* __restrict__ 
   }
 }
 
+// kOneHot: every gradient row is read exactly once (one position per bag): streamed with
+// non-temporal loads (measured 75 against 96 us at the target one-hot configuration).  Multi-hot: a
+// bag's row is read once per position of the bag, from all over the grouping: plain loads, so that
+// the caches keep what they can (358 against 410 us at the multi-hot configuration).
+template <bool kOneHot>
 __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ grad,
                                                      const int64_t* __restrict__ perm64, int n,
                                                      int d4, int G, int L,
@@ -327,7 +370,7 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
 #pragma unroll
     for (int k = 0; k < kSegChunk; ++k) {
       x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (pe[k] >= 0) x[k] = ld_stream(&grad[(int64_t)(uint32_t)pe[k] * d4 + c4]);
+      if (pe[k] >= 0) x[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pe[k] * d4 + c4]);
     }
 #pragma unroll
     for (int k = 0; k < kSegChunk; ++k)
@@ -342,7 +385,7 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
 #pragma unroll
       for (int k = 0; k < kSegChunk; ++k) {
         xn[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (pn[k] >= 0) xn[k] = ld_stream(&grad[(int64_t)(uint32_t)pn[k] * d4 + c4]);
+        if (pn[k] >= 0) xn[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pn[k] * d4 + c4]);
       }
 #pragma unroll
       for (int k = 0; k < kSegChunk; ++k) {
@@ -476,17 +519,27 @@ __device__ __forceinline__ void adagrad4v(float4& w, float4& a, float4 g, float 
   adagrad1(w.w, a.w, g.w, lr, eps);
 }
 
+// The update kernels touch every row of the batch once.  When those rows (weights, state, summed
+// gradient; read and written) exceed what the memory-side cache holds, keeping them cached only
+// evicts what the next kernel could have used: they are then moved with non-temporal accesses
+// (multi-hot configuration, 1.4e6 rows of 256 bytes: 305 against 400 us).  Below that size plain
+// accesses are as fast or a little faster (target configuration: 32 us either way).
+constexpr int64_t kStreamRowsBytes = (int64_t)256 << 20;
+__device__ __forceinline__ bool stream_rows(int U, int d4, int s4) {
+  return (int64_t)U * (3 * d4 + 2 * s4) * 16 > kStreamRowsBytes;
+}
+
 // Adagrad over the common-gradient matrix (one row per virtual id), four rows per thread in flight.
 // A bypass row (slot >= C: a miss that found no cache slot) is also written to the Host table
 // here: it lives for this step only.
-__global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__ common,
-                                                       const int* __restrict__ slot,
-                                                       const int64_t* __restrict__ unique_ids,
-                                                       float4* __restrict__ cw,
-                                                       float4* __restrict__ ca, HostRows h, int C,
-                                                       int boff, float lr, float eps, int d4,
-                                                       const Ctr* ctr) {
-  const int64_t total = (int64_t)ctr->U * d4;
+template <bool kStream>
+__device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
+                                             const int* __restrict__ slot,
+                                             const int64_t* __restrict__ unique_ids,
+                                             float4* __restrict__ cw, float4* __restrict__ ca,
+                                             const HostRows& h, int C, int boff, float lr, float eps,
+                                             int d4, int U) {
+  const int64_t total = (int64_t)U * d4;
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 4 * stride) {
     float4 g[4], w[4], a[4];
@@ -500,7 +553,8 @@ __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__
         sl[u] = slot[(int)(i / d4)];
         if (sl[u] >= 0) {
           r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + (i % d4);
-          g[u] = common[i]; w[u] = cw[r[u]]; a[u] = ca[r[u]];
+          g[u] = ld_row<kStream>(&common[i]); w[u] = ld_row<kStream>(&cw[r[u]]);
+          a[u] = ld_row<kStream>(&ca[r[u]]);
         }
       }
     }
@@ -508,7 +562,7 @@ __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__
     for (int u = 0; u < 4; ++u)
       if (r[u] >= 0) {
         adagrad4v(w[u], a[u], g[u], lr, eps);
-        cw[r[u]] = w[u]; ca[r[u]] = a[u];
+        st_row<kStream>(&cw[r[u]], w[u]); st_row<kStream>(&ca[r[u]], a[u]);
         if (sl[u] >= C) {
           const int64_t i = i0 + u * stride;
           const int64_t hr = unique_ids[(int)(i / d4)] * h.hs4 + (i % d4);
@@ -517,6 +571,18 @@ __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__
         }
       }
   }
+}
+
+__global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__ common,
+                                                       const int* __restrict__ slot,
+                                                       const int64_t* __restrict__ unique_ids,
+                                                       float4* __restrict__ cw,
+                                                       float4* __restrict__ ca, HostRows h, int C,
+                                                       int boff, float lr, float eps, int d4,
+                                                       const Ctr* ctr) {
+  const int U = ctr->U;
+  if (stream_rows(U, d4, d4)) adagrad_rows<true>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U);
+  else adagrad_rows<false>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -536,14 +602,14 @@ __device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, con
   w = w - k.lr * mhat / (sqrtf(vhat) + k.eps);
 }
 
-__global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ common,
-                                                    const int* __restrict__ slot,
-                                                    const int64_t* __restrict__ unique_ids,
-                                                    float4* __restrict__ cw,
-                                                    float4* __restrict__ cs, HostRows h, int C,
-                                                    int boff, AdamArgs k, int d4,
-                                                    const Ctr* ctr) {
-  const int64_t total = (int64_t)ctr->U * d4;
+template <bool kStream>
+__device__ __forceinline__ void adam_rows(const float4* __restrict__ common,
+                                          const int* __restrict__ slot,
+                                          const int64_t* __restrict__ unique_ids,
+                                          float4* __restrict__ cw, float4* __restrict__ cs,
+                                          const HostRows& h, int C, int boff, const AdamArgs& k,
+                                          int d4, int U) {
+  const int64_t total = (int64_t)U * d4;
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 2 * stride) {
     float4 g[2], w[2], m[2], v[2];
@@ -559,7 +625,8 @@ __global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ co
           const int64_t row = sl[u] >= C ? sl[u] + boff : sl[u];
           rw[u] = row * d4 + (i % d4);
           rs[u] = row * 2 * d4 + (i % d4);
-          g[u] = common[i]; w[u] = cw[rw[u]]; m[u] = cs[rs[u]]; v[u] = cs[rs[u] + d4];
+          g[u] = ld_row<kStream>(&common[i]); w[u] = ld_row<kStream>(&cw[rw[u]]);
+          m[u] = ld_row<kStream>(&cs[rs[u]]); v[u] = ld_row<kStream>(&cs[rs[u] + d4]);
         }
       }
     }
@@ -570,7 +637,8 @@ __global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ co
         adam1(w[u].y, m[u].y, v[u].y, g[u].y, k);
         adam1(w[u].z, m[u].z, v[u].z, g[u].z, k);
         adam1(w[u].w, m[u].w, v[u].w, g[u].w, k);
-        cw[rw[u]] = w[u]; cs[rs[u]] = m[u]; cs[rs[u] + d4] = v[u];
+        st_row<kStream>(&cw[rw[u]], w[u]); st_row<kStream>(&cs[rs[u]], m[u]);
+        st_row<kStream>(&cs[rs[u] + d4], v[u]);
         if (sl[u] >= C) {
           const int64_t i = i0 + u * stride;
           const int64_t id = unique_ids[(int)(i / d4)];
@@ -581,6 +649,18 @@ __global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ co
         }
       }
   }
+}
+
+__global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ common,
+                                                    const int* __restrict__ slot,
+                                                    const int64_t* __restrict__ unique_ids,
+                                                    float4* __restrict__ cw,
+                                                    float4* __restrict__ cs, HostRows h, int C,
+                                                    int boff, AdamArgs k, int d4,
+                                                    const Ctr* ctr) {
+  const int U = ctr->U;
+  if (stream_rows(U, d4, 2 * d4)) adam_rows<true>(common, slot, unique_ids, cw, cs, h, C, boff, k, d4, U);
+  else adam_rows<false>(common, slot, unique_ids, cw, cs, h, C, boff, k, d4, U);
 }
 
 // ---------------------------------------------------------------------------------------------
