@@ -140,11 +140,8 @@ struct sfc_cache {
   UEntry* utab = nullptr; int* uvid = nullptr;  // batch table [2*max_ids]: key + first position; vid
   int* hslot = nullptr;                         // [max_ids]
   int* vid_hslot = nullptr;                     // [max_ids]
-  // single-pass prefixes (look-back): state words of the rank pass [max_ids / kPosChunk + 2] and of
-  // the victim pass [C / kPosChunk + 2], their ticket counters, and the count of finished
-  // resolve blocks; all zero between kernels
-  unsigned long long *lb_rank = nullptr, *lb_victim = nullptr;
-  int* lb_ticket = nullptr;                     // [0] rank pass, [1] victim pass, [2] resolve blocks done
+  int* blk_cnt = nullptr;                       // [max_ids / kPosChunk + 1]
+  int *tile_lt = nullptr, *tile_eq = nullptr;   // [C / kPosChunk + 1]
   int* tile_miss = nullptr;                     // [max_ids / kVidTile + 1]
   // positions per virtual id [max_ids] and its copies for the lowest virtual ids [kHotRep, kHotBins]:
   // two sets, used by steps of even / odd number, so that the unique passes of a step can run
@@ -252,7 +249,6 @@ int healthy(sfc_cache* c) {
 }
 
 constexpr int kGridCap = 2048;   // blocks of the grid-stride kernels whose size lives on the device
-constexpr int kVictimGrid = 1024;  // blocks of the victim pass (each draws tiles until none are left)
 constexpr int kRebuildGrid = 512;  // blocks of the two launches that only work when the index is rebuilt
 
 // The step that lookup / segment_sum / backward_update act on: the oldest one whose rows are (or
@@ -516,9 +512,9 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->uvid, hu))) goto bad;
     if ((rc = dalloc(c, &c->hslot, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->vid_hslot, c->max_ids))) goto bad;
-    if ((rc = dalloc(c, &c->lb_rank, c->max_ids / kPosChunk + 2))) goto bad;
-    if ((rc = dalloc(c, &c->lb_victim, c->C / kPosChunk + 2))) goto bad;
-    if ((rc = dalloc(c, &c->lb_ticket, 4))) goto bad;
+    if ((rc = dalloc(c, &c->blk_cnt, c->max_ids / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->tile_lt, c->C / kPosChunk + 2))) goto bad;
+    if ((rc = dalloc(c, &c->tile_eq, c->C / kPosChunk + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_miss, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->cnt2[0], c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->cnt2[1], c->max_ids))) goto bad;
@@ -566,9 +562,6 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->cnt_rep2[0], (int64_t)kHotRep * kHotBins, 0);
     fill<int>(s, c->cnt_rep2[1], (int64_t)kHotRep * kHotBins, 0);
     fill<int>(s, c->n_unique, 1, 0);
-    fill<unsigned long long>(s, c->lb_rank, c->max_ids / kPosChunk + 2, 0ull);
-    fill<unsigned long long>(s, c->lb_victim, c->C / kPosChunk + 2, 0ull);
-    fill<int>(s, c->lb_ticket, 4, 0);
     fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
@@ -653,11 +646,11 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
     if (nub > head)
       hipLaunchKernelGGL(k_uniq_insert, dim3(nub - head), dim3(256), 0, su, d_ids, n, c->V, c->utab,
                          hu, c->hslot, c->n_invalid, head);
-    hipLaunchKernelGGL(k_uniq_rank, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n, c->lb_rank,
-                       c->lb_ticket, d_unique_ids, c->uvid, c->vid_hslot, cnt, c->n_unique, c->d_hstat,
-                       x->t);
+    hipLaunchKernelGGL(k_uniq_count, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n, c->blk_cnt);
+    hipLaunchKernelGGL(k_uniq_assign, dim3(nchunk), dim3(256), 0, su, c->hslot, c->utab, n,
+                       c->blk_cnt, d_unique_ids, c->uvid, c->vid_hslot, cnt, c->n_unique);
     hipLaunchKernelGGL(k_uniq_inverse, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, su,
-                       c->hslot, c->uvid, n, d_inverse, cnt, cnt_rep, x->pos_slot, c->lb_rank, nchunk);
+                       c->hslot, c->uvid, n, d_inverse, cnt, cnt_rep, x->pos_slot);
   } else {
     fill<int>(su, c->n_unique, 1, 0);
   }
@@ -676,18 +669,24 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
   hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
                      c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, cnt, cnt_rep,
-                     c->tile_cnt, c->age_hist, x->ctr, c->tile_reuse, c->cfg.lookahead, (int)c->C,
-                     c->lb_ticket + 2);
+                     c->tile_cnt, c->age_hist, x->ctr);
   if (c->ins) { HIPCHK(hipEventRecord(c->ev_resolved, s)); c->resolved_once = true; }
-  const int gs = grid_for(c->C, kPosChunk, kVictimGrid);
-  hipLaunchKernelGGL(k_victims, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->lb_victim,
-                     c->lb_ticket + 1, x->victim_slot, x->victim_id, c->index, c->hi, x->ctr);
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
+                     c->tile_reuse,
+                     c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
+  const int gs = grid_for(c->C, kPosChunk, kGridCap);
+  hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
+                     x->ctr);
+  hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
+                     c->tile_eq, x->victim_slot, x->victim_id, x->ctr);
   const int gv = grid_for(n, kVidTile, kGridCap);
+  hipLaunchKernelGGL(k_victim_unmap, dim3(gv), dim3(256), 0, s, x->victim_id, c->index, c->hi,
+                     x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, cnt, cnt_rep,
                      c->cur_rep, c->tile_cnt,
                      c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,
-                     c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr, c->lb_victim);
+                     c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cursor, c->cur_rep,

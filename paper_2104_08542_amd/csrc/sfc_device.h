@@ -122,71 +122,6 @@ __device__ __forceinline__ int block_excl_scan(int x, int& total, int* smem) {
   return res;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Single-pass prefix over tiles (decoupled look-back).  Every tile publishes a 64-bit state word:
-// bits 63-62 = 0 nothing yet, 1 the tile's own total, 2 the inclusive prefix up to and with the
-// tile; bits 61-0 = the value (callers pack what they need into it; addition must not carry into
-// the flag bits).  A tile sums the words before it, newest first, until it meets an inclusive
-// prefix.  The words are zero when a kernel starts (the kernel that follows it in the stream
-// clears them again) and tiles are taken in the order of a ticket counter, so a tile only ever
-// waits for tiles whose blocks are already running.  The wait is bounded all the same: a block
-// that gives up reports it through `gave_up` and carries on with what it has, so every
-// wavefront reaches its end whatever happens.
-// ---------------------------------------------------------------------------------------------
-constexpr unsigned long long kLbOwn = 1ull << 62, kLbIncl = 2ull << 62, kLbValue = (1ull << 62) - 1;
-constexpr int kLbSpinLimit = 1 << 22;
-
-__device__ __forceinline__ unsigned long long lb_load(const unsigned long long* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void lb_store(unsigned long long* p, unsigned long long v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Called by the first wavefront of the block that owns `tile` (all 64 lanes).  own = the tile's
-// packed total.  Publishes it, looks back, publishes the inclusive prefix and returns the
-// exclusive one.  add() combines two packed values (plain addition unless the caller saturates).
-template <typename Add>
-__device__ __forceinline__ unsigned long long lb_exclusive(unsigned long long* state, int tile,
-                                                           unsigned long long own, Add add,
-                                                           bool* gave_up) {
-  const int lane = lane_id();
-  if (tile == 0) {
-    if (lane == 0) lb_store(&state[0], kLbIncl | own);
-    return 0;
-  }
-  if (lane == 0) lb_store(&state[tile], kLbOwn | own);
-  unsigned long long excl = 0;
-  int look = tile - 1;                       // lane l reads tile look - l
-  int spins = 0;
-  for (;;) {
-    const int j = look - lane;
-    unsigned long long w = 0;
-    bool ok;
-    do {
-      w = j >= 0 ? lb_load(&state[j]) : kLbIncl;     // before the first tile: prefix 0
-      ok = (w >> 62) != 0;
-      if (!__all(ok)) __builtin_amdgcn_s_sleep(1);
-    } while (!__all(ok) && ++spins < kLbSpinLimit);
-    if (!__all(ok)) { *gave_up = true; if (!ok) w = kLbIncl; }
-    // nearest tile (lowest lane) that already holds an inclusive prefix
-    const uint64_t incl = __ballot((w >> 62) == 2);
-    const int stop = incl ? __builtin_ctzll(incl) : kWave - 1;
-    // combine the values of lanes 0..stop (add is associative and commutative, 0 its identity)
-    unsigned long long v = lane <= stop ? (w & kLbValue) : 0;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-      const unsigned long long o = __shfl_down(v, d, kWave);
-      if (lane + d < kWave) v = add(v, o);
-    }
-    excl = add(excl, __shfl(v, 0, kWave));
-    if (incl) break;
-    look -= kWave;
-  }
-  if (lane == 0) lb_store(&state[tile], kLbIncl | add(excl, own));
-  return excl;
-}
-
 __device__ __forceinline__ int block_sum(int x, int* smem) {
   const int lane = lane_id(), w = (int)(threadIdx.x >> 6), nw = (int)(blockDim.x >> 6);
   x = wave_sum(x);

@@ -201,6 +201,25 @@ __device__ __forceinline__ void index_reinsert(IdxEntry* index, uint32_t hi,
   }
 }
 
+// VSI pass 2: per chunk of positions, how many are the first appearance of their id.
+__global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslot,
+                                                     const UEntry* __restrict__ utab, int n,
+                                                     int* __restrict__ blk_cnt) {
+  __shared__ int smem[20];
+  const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
+  int c = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int p = base + j;
+    if (p < n) {
+      const unsigned hs = (unsigned)hslot[p];
+      if ((hs & kCandBit) && utab[hs & ~kCandBit].minpos == p) ++c;
+    }
+  }
+  const int tot = block_sum(c, smem);
+  if (threadIdx.x == 0) blk_cnt[blockIdx.x] = tot;
+}
+
 // Starts the step's counters, once the previous step's prepare has run to its end: they inherit the
 // cache-wide fields (watermark, oldest stamp, tombstones, rebuild flag, error) from the previous
 // step's and start their own tallies at zero.  Steps in flight on the other streams keep reading
@@ -236,30 +255,23 @@ __global__ __launch_bounds__(256) void k_index_refill(IdxEntry* index, uint32_t 
   if (ctr->rebuild) index_reinsert(index, hi, slot_id, ctr->f);
 }
 
-// VSI passes 2 and 3 in one: which positions are the first appearance of their id (the candidate
-// of its block whose position equals the key's smallest position), their rank among all such
-// positions = the virtual id, and the tables keyed by it.  One tile of kPosChunk positions per
-// block; the number of first appearances in the tiles before comes from a single-pass look-back
-// over per-tile state words (see lb_exclusive), so the positions are read once.  Tiles are taken
-// in ticket order; the block that draws the last ticket of the launch returns the counter to zero.
-// The last tile leaves the number of unique ids in *n_unique for k_ctr_init.
-__global__ __launch_bounds__(256) void k_uniq_rank(const int* __restrict__ hslot,
-                                                    const UEntry* __restrict__ utab, int n,
-                                                    unsigned long long* lb_state, int* lb_ticket,
-                                                    int64_t* __restrict__ unique_ids,
-                                                    int* __restrict__ uvid,
-                                                    int* __restrict__ vid_hslot,
-                                                    int* __restrict__ cnt, int* n_unique,
-                                                    HostStatus* hstat, int t) {
+// VSI pass 3: the first appearances get their virtual ids (rank among all first appearances) and
+// the tables keyed by them.  A chunk's first virtual id is the sum of the counts of the chunks
+// before it, which every block adds up for itself (a few loads per thread from a list that sits in
+// L2: cheaper than a scan kernel between the two passes).  The last chunk leaves the number of
+// unique ids in *n_unique for k_ctr_init.
+__global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hslot,
+                                                      const UEntry* __restrict__ utab, int n,
+                                                      const int* __restrict__ blk_cnt,
+                                                      int64_t* __restrict__ unique_ids,
+                                                      int* __restrict__ uvid,
+                                                      int* __restrict__ vid_hslot,
+                                                      int* __restrict__ cnt, int* n_unique) {
   __shared__ int smem[20];
-  __shared__ int s_tile, s_base;
-  if (threadIdx.x == 0) {
-    s_tile = atomicAdd(lb_ticket, 1);
-    if (s_tile == (int)gridDim.x - 1) atomicExch(lb_ticket, 0);
-  }
-  __syncthreads();
-  const int tile = s_tile;
-  const int base = tile * kPosChunk + (int)threadIdx.x * 8;
+  int before = 0;
+  for (int i = (int)threadIdx.x; i < (int)blockIdx.x; i += 256) before += blk_cnt[i];
+  before = block_sum(before, smem);
+  const int base = blockIdx.x * kPosChunk + (int)threadIdx.x * 8;
   int hs[8];
   unsigned flags = 0;
   int c = 0;
@@ -274,20 +286,8 @@ __global__ __launch_bounds__(256) void k_uniq_rank(const int* __restrict__ hslot
     }
   }
   int tot;
-  int vid = block_excl_scan(c, tot, smem);
-  if (threadIdx.x < kWave) {
-    bool gave_up = false;
-    const unsigned long long before =
-        lb_exclusive(lb_state, tile, (unsigned long long)tot,
-                     [](unsigned long long a, unsigned long long b) { return a + b; }, &gave_up);
-    if (threadIdx.x == 0) {
-      s_base = (int)before;
-      if (gave_up) { volatile HostStatus* h = hstat; h->err_step = t; h->err = 5; }
-      if (tile == (int)gridDim.x - 1) *n_unique = (int)before + tot;
-    }
-  }
-  __syncthreads();
-  vid += s_base;
+  int vid = block_excl_scan(c, tot, smem) + before;
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *n_unique = before + tot;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     if (flags & (1u << j)) {
@@ -318,11 +318,8 @@ constexpr int kFlushPer = 16;     // bins per thread and round when k_scatter fl
 __global__ __launch_bounds__(256) void k_uniq_inverse(const int* __restrict__ hslot,
                                                        const int* __restrict__ uvid, int n,
                                                        int* __restrict__ inverse, int* cnt,
-                                                       int* cnt_rep, int* __restrict__ rank,
-                                                       unsigned long long* lb_state, int lb_n) {
+                                                       int* cnt_rep, int* __restrict__ rank) {
   __shared__ int lh[kHotBins];
-  // the look-back words of the rank pass that has just run go back to zero for the next step
-  for (int i = blockIdx.x * 256 + (int)threadIdx.x; i < lb_n; i += gridDim.x * 256) lb_state[i] = 0;
   for (int i = threadIdx.x; i < kHotBins; i += 256) lh[i] = 0;
   __syncthreads();
   const int base = blockIdx.x * kSortChunk;
@@ -449,8 +446,6 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
 // together: the longest cluster among the tens of thousands of probes of a step sets the duration
 // of the kernel, and a dependent load per entry made that tail tens of microseconds long.
 constexpr int kProbeBatch = 8;
-constexpr int kAgeBins = 1024;      // ages of hits that k_resolve tallies in LDS
-constexpr int kResolveGrid = 256;
 
 __device__ __forceinline__ int64_t idx_key(const int4& raw) {
   return ((int64_t)(uint32_t)raw.y << 32) | (uint32_t)raw.x;
@@ -518,119 +513,6 @@ __device__ __forceinline__ bool index_insert(IdxEntry* index, uint32_t hi, int64
 }
 
 // ---------------------------------------------------------------------------------------------
-// Plan (one block, the last one of k_resolve to finish): scan the per-tile miss counts, then decide
-// the victims' stamp threshold from the recency histogram: need = M - free; T is the stamp at
-// which the running count of evictable slots (stamp < limit, oldest first) passes need; r of the
-// slots stamped T go too.
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void plan_step(int* tile_miss, int* tile_cnt, int* __restrict__ age_hist,
-                                          int* __restrict__ tile_reuse, int* hist, int t,
-                                          int lookahead, int C, uint32_t hi, Ctr* ctr, int* smem) {
-  __shared__ int s_found;
-  const int NT = (int)blockDim.x;
-  // every thread reads the counters here; thread 0 overwrites them only after the last barrier
-  const int U = ctr->U;
-  const int f = ctr->f;
-  const int oldest = ctr->oldest;
-  const int ntiles = (U + kVidTile - 1) / kVidTile;
-  // deleted index entries that the previous step's miss assignment took back into use
-  int reuse = 0;
-  const int reuse_tiles = (ctr->U_prev + kVidTile - 1) / kVidTile;
-  for (int i = (int)threadIdx.x; i < reuse_tiles; i += NT) { reuse += tile_reuse[i]; tile_reuse[i] = 0; }
-  reuse = block_sum(reuse, smem);
-  // hits by age: hist[t] gains the hits (bin 0), hist[t - a] loses its share
-  for (int a = (int)threadIdx.x; a < kAgeBins; a += NT) {
-    const int sum = age_hist[a];
-    age_hist[a] = 0;
-    if (a == 0) { hist[t] += sum; ctr->n_hit = sum; }
-    else if (sum) hist[t - a] -= sum;
-  }
-  __syncthreads();
-  int carry = 0;
-  for (int b = 0; b < ntiles; b += NT) {
-    const int i = b + (int)threadIdx.x;
-    const int x = i < ntiles ? tile_miss[i] : 0;
-    int tot;
-    const int e = block_excl_scan(x, tot, smem);
-    if (i < ntiles) tile_miss[i] = carry + e;
-    carry += tot;
-  }
-  const int M = carry;
-  carry = 0;
-  for (int b = 0; b < ntiles; b += NT) {
-    const int i = b + (int)threadIdx.x;
-    const int x = i < ntiles ? tile_cnt[i] : 0;
-    int tot;
-    const int e = block_excl_scan(x, tot, smem);
-    if (i < ntiles) tile_cnt[i] = carry + e;
-    carry += tot;
-  }
-  const int free_slots = C - f;
-  const int need = M - free_slots;
-  const int limit = t - lookahead;       // candidates have stamp < limit
-  int T = limit, r = 0, K = 0;
-  if (need > 0) {
-    // running count of candidates from the oldest stamp upwards
-    int cum = 0;           // slots with stamp in [oldest, b)
-    bool done = false;
-    for (int b = oldest; b < limit && !done; b += NT) {
-      if (threadIdx.x == 0) s_found = kIntMax;
-      __syncthreads();
-      const int s = b + (int)threadIdx.x;
-      const int x = s < limit ? hist[s] : 0;
-      int tot;
-      const int e = block_excl_scan(x, tot, smem);
-      // first stamp whose inclusive count exceeds need
-      if (s < limit && cum + e + x > need) atomicMin(&s_found, s);
-      __syncthreads();
-      if (s_found != kIntMax) {
-        T = s_found;
-        if (s == T) smem[18] = cum + e;    // candidates strictly older than T
-        __syncthreads();
-        r = need - smem[18];
-        K = need;
-        done = true;
-      } else {
-        cum += tot;
-      }
-      __syncthreads();
-    }
-    if (!done) { T = limit; r = 0; K = cum; }   // everything evictable goes, the rest bypasses
-    // the histogram after eviction: stamps below T vanish, r leave stamp T
-    for (int s = oldest + (int)threadIdx.x; s < T; s += NT) hist[s] = 0;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    if (need > 0 && r > 0) hist[T] -= r;
-    int f_new = f + (M - K);
-    if (f_new > C) f_new = C;
-    const int n_bypass = M - K - (f_new - f);
-    hist[t] += M - n_bypass;
-    ctr->M = M; ctr->K = K; ctr->n_bypass = n_bypass;
-    ctr->need = need; ctr->T = T; ctr->r = r;
-    ctr->f_old = f; ctr->f = f_new;
-    if (need > 0 && T > oldest) ctr->oldest = T;
-    ctr->tomb -= reuse;
-    // a rebuild asked for by the previous step has run ahead of this step's resolve
-    if (ctr->rebuild) { ctr->rebuild = 0; ctr->tomb = 0; }
-    // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
-    // eighth of the index would be deleted entries
-    if ((unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
-    // the step's counters are final: publish them to the Host status block (sequence word odd
-    // while they are being written)
-    volatile HostStatus* h = ctr->hstat;
-    if (h) {
-      h->seq = 2 * t - 1;
-      __threadfence_system();
-      h->U = U; h->n_hit = ctr->n_hit; h->M = M; h->K = K; h->n_bypass = n_bypass;
-      h->n_invalid = ctr->n_invalid; h->n_bad_offsets = ctr->bad_offsets;
-      __threadfence_system();
-      h->seq = 2 * t;
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Resolve: each unique id against the index.  Hits get their slot and the current stamp.  The
 // recency histogram hist[stamp] = #slots with that stamp must stay exact; stamps of hits cluster
 // on the last few steps, i.e. on a few words of hist, so each block tallies its hits by age
@@ -639,6 +521,8 @@ __device__ __forceinline__ void plan_step(int* tile_miss, int* tile_cnt, int* __
 // counts the hits.  Also returns the batch-table entries of this step to the empty state, so that
 // table never needs a per-step clear, and sums cnt per tile for the segment offsets.
 // ---------------------------------------------------------------------------------------------
+constexpr int kAgeBins = 1024;
+constexpr int kResolveGrid = 256;
 
 __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
                                                   const int* __restrict__ vid_hslot, UEntry* utab,
@@ -649,12 +533,9 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
                                                   int* __restrict__ cnt,
                                                   const int* __restrict__ cnt_rep,
                                                   int* __restrict__ tile_cnt,
-                                                  int* __restrict__ age_hist, Ctr* ctr,
-                                                  int* __restrict__ tile_reuse, int lookahead,
-                                                  int C, int* blocks_done) {
+                                                  int* __restrict__ age_hist, Ctr* ctr) {
   __shared__ int smem[20];
   __shared__ int lage[kAgeBins];
-  __shared__ int s_last;
   for (int i = threadIdx.x; i < kAgeBins; i += 256) lage[i] = 0;
   __syncthreads();
   const int U = ctr->U;
@@ -727,61 +608,163 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
   __syncthreads();
   for (int i = threadIdx.x; i < kAgeBins; i += 256)
     if (lage[i]) atomicAdd(&age_hist[i], lage[i]);
-  // The block that finishes last plans the step (below): the others' tallies are complete and,
-  // through the fences on both sides of the counter, visible to it.
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    s_last = atomicAdd(blocks_done, 1) == (int)gridDim.x - 1;
-    if (s_last) atomicExch(blocks_done, 0);
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  plan_step(tile_miss, tile_cnt, age_hist, tile_reuse, hist, t, lookahead, C, hi, ctr, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Victim selection over the occupied slots, in slot order, in one pass:
-// victim  <=>  stamp < T, or stamp == T and fewer than r earlier slots carry stamp T.
-// A victim's place in the list = (slots before it with stamp < T) + min(r, slots before it with
-// stamp == T).  One tile of kPosChunk slots per block and round; the counts of the tiles before
-// come from a single-pass look-back (see lb_exclusive): the state word packs the count of
-// stamp < T (31 bits) above the count of stamp == T saturated at r (31 bits; saturating addition
-// is still associative, and only min(r, .) of that count is ever used).  Tiles are drawn from a
-// ticket counter until it passes the last tile; the last draw of the launch returns it to zero.
-// The victims leave the index here as well, each by the thread that found it.  Deletions and
-// inserts never share a kernel (the inserts of this step come in k_assign_misses), and every write
-// to the index in a kernel that uses atomics on it is itself an atomic: see the note on the index
-// in the design document of this library (a resident id once went missing when that was not so).
+// Plan (one block): scan the per-tile miss counts, then decide the victims' stamp threshold from
+// the recency histogram: need = M - free; T is the stamp at which the running count of
+// evictable slots (stamp < limit, oldest first) passes need; r of the slots stamped T go too.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_victims(const int* __restrict__ stamp,
-                                                  const int64_t* __restrict__ slot_id,
-                                                  unsigned long long* lb_state, int* lb_ticket,
-                                                  int* __restrict__ victim_slot,
-                                                  int64_t* __restrict__ victim_id,
-                                                  IdxEntry* index, uint32_t hi, Ctr* ctr) {
+__global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
+                                               int* __restrict__ age_hist,
+                                               int* __restrict__ tile_reuse, int* hist, int t,
+                                               int lookahead, int C, uint32_t hi, Ctr* ctr) {
+  static_assert(kAgeBins == 1024, "one thread per age bin");
   __shared__ int smem[20];
-  __shared__ int s_tile;
-  __shared__ unsigned long long s_before;
+  __shared__ int s_found;
+  // every thread reads the counters here; thread 0 overwrites them only after the last barrier
+  const int U = ctr->U;
+  const int f = ctr->f;
+  const int oldest = ctr->oldest;
+  const int ntiles = (U + kVidTile - 1) / kVidTile;
+  // deleted index entries that the previous step's miss assignment took back into use
+  int reuse = 0;
+  const int reuse_tiles = (ctr->U_prev + kVidTile - 1) / kVidTile;
+  for (int i = (int)threadIdx.x; i < reuse_tiles; i += 1024) { reuse += tile_reuse[i]; tile_reuse[i] = 0; }
+  reuse = block_sum(reuse, smem);
+  // hits by age: thread a owns age a.  hist[t] gains the hits, hist[t - a] loses its share.
+  {
+    const int a = (int)threadIdx.x;
+    const int sum = age_hist[a];
+    age_hist[a] = 0;
+    if (a == 0) { hist[t] += sum; ctr->n_hit = sum; }
+    else if (sum) hist[t - a] -= sum;
+  }
+  __syncthreads();
+  int carry = 0;
+  for (int b = 0; b < ntiles; b += 1024) {
+    const int i = b + (int)threadIdx.x;
+    const int x = i < ntiles ? tile_miss[i] : 0;
+    int tot;
+    const int e = block_excl_scan(x, tot, smem);
+    if (i < ntiles) tile_miss[i] = carry + e;
+    carry += tot;
+  }
+  const int M = carry;
+  carry = 0;
+  for (int b = 0; b < ntiles; b += 1024) {
+    const int i = b + (int)threadIdx.x;
+    const int x = i < ntiles ? tile_cnt[i] : 0;
+    int tot;
+    const int e = block_excl_scan(x, tot, smem);
+    if (i < ntiles) tile_cnt[i] = carry + e;
+    carry += tot;
+  }
+  const int free_slots = C - f;
+  const int need = M - free_slots;
+  const int limit = t - lookahead;       // candidates have stamp < limit
+  int T = limit, r = 0, K = 0;
+  if (need > 0) {
+    // running count of candidates from the oldest stamp upwards
+    int cum = 0;           // slots with stamp in [oldest, b)
+    bool done = false;
+    for (int b = oldest; b < limit && !done; b += 1024) {
+      if (threadIdx.x == 0) s_found = kIntMax;
+      __syncthreads();
+      const int s = b + (int)threadIdx.x;
+      const int x = s < limit ? hist[s] : 0;
+      int tot;
+      const int e = block_excl_scan(x, tot, smem);
+      // first stamp whose inclusive count exceeds need
+      if (s < limit && cum + e + x > need) atomicMin(&s_found, s);
+      __syncthreads();
+      if (s_found != kIntMax) {
+        T = s_found;
+        if (s == T) smem[18] = cum + e;    // candidates strictly older than T
+        __syncthreads();
+        r = need - smem[18];
+        K = need;
+        done = true;
+      } else {
+        cum += tot;
+      }
+      __syncthreads();
+    }
+    if (!done) { T = limit; r = 0; K = cum; }   // everything evictable goes, the rest bypasses
+    // the histogram after eviction: stamps below T vanish, r leave stamp T
+    for (int s = oldest + (int)threadIdx.x; s < T; s += 1024) hist[s] = 0;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (need > 0 && r > 0) hist[T] -= r;
+    int f_new = f + (M - K);
+    if (f_new > C) f_new = C;
+    const int n_bypass = M - K - (f_new - f);
+    hist[t] += M - n_bypass;
+    ctr->M = M; ctr->K = K; ctr->n_bypass = n_bypass;
+    ctr->need = need; ctr->T = T; ctr->r = r;
+    ctr->f_old = f; ctr->f = f_new;
+    if (need > 0 && T > oldest) ctr->oldest = T;
+    ctr->tomb -= reuse;
+    // a rebuild asked for by the previous step has run ahead of this step's resolve
+    if (ctr->rebuild) { ctr->rebuild = 0; ctr->tomb = 0; }
+    // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
+    // eighth of the index would be deleted entries
+    if ((unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Victim selection over the occupied slots, in slot order (two passes around a scan):
+// victim  <=>  stamp < T, or stamp == T and fewer than r earlier slots carry stamp T.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_victim_count(const int* __restrict__ stamp,
+                                                       int* __restrict__ tile_lt,
+                                                       int* __restrict__ tile_eq, const Ctr* ctr) {
+  __shared__ int smem[20];
+  if (ctr->K == 0) return;
+  const int f = ctr->f_old, T = ctr->T;
+  for (int tile = blockIdx.x; tile * kPosChunk < f; tile += gridDim.x) {
+    const int base = tile * kPosChunk + (int)threadIdx.x * 8;
+    int lt = 0, eq = 0;
+    if (base + 8 <= f) {
+      const int4 a = *reinterpret_cast<const int4*>(stamp + base);
+      const int4 b = *reinterpret_cast<const int4*>(stamp + base + 4);
+      const int v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { lt += v[j] < T; eq += v[j] == T; }
+    } else {
+      for (int j = 0; j < 8; ++j) {
+        const int s = base + j;
+        if (s < f) { const int st = stamp[s]; lt += st < T; eq += st == T; }
+      }
+    }
+    // both counts in one block reduction: a tile has 2048 slots, so each fits in 16 bits
+    const int both = block_sum((lt << 16) | eq, smem);
+    if (threadIdx.x == 0) { tile_lt[tile] = both >> 16; tile_eq[tile] = both & 0xffff; }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ stamp,
+                                                       const int64_t* __restrict__ slot_id,
+                                                       const int* __restrict__ tile_lt,
+                                                       const int* __restrict__ tile_eq,
+                                                       int* __restrict__ victim_slot,
+                                                       int64_t* __restrict__ victim_id, Ctr* ctr) {
+  __shared__ int smem[20];
   if (ctr->K == 0) return;
   const int f = ctr->f_old, T = ctr->T, r = ctr->r, K = ctr->K;
-  const int ntiles = (f + kPosChunk - 1) / kPosChunk;
-  const int draws = ntiles + (int)gridDim.x;        // every block draws until it draws past the end
-  constexpr unsigned long long kEqMask = (1ull << 31) - 1;
-  auto sat_add = [r](unsigned long long a, unsigned long long b) {
-    unsigned long long eq = (a & kEqMask) + (b & kEqMask);
-    if (eq > (unsigned long long)r) eq = (unsigned long long)r;
-    return (((a >> 31) + (b >> 31)) << 31) | eq;
-  };
-  for (;;) {
-    if (threadIdx.x == 0) {
-      s_tile = atomicAdd(lb_ticket, 1);
-      if (s_tile == draws - 1) atomicExch(lb_ticket, 0);
+  // victims in the tiles before this block's current one: summed from the per-tile counts, and
+  // carried on from tile to tile (each block reads every count at most once)
+  int pre_lt = 0, pre_eq = 0, summed = 0;
+  for (int tile = blockIdx.x; tile * kPosChunk < f; tile += gridDim.x) {
+    {
+      int a = 0, b = 0;
+      for (int i = summed + (int)threadIdx.x; i < tile; i += 256) { a += tile_lt[i]; b += tile_eq[i]; }
+      pre_lt += block_sum(a, smem);
+      pre_eq += block_sum(b, smem);
+      summed = tile;
     }
-    __syncthreads();
-    const int tile = s_tile;
-    if (tile >= ntiles) break;                      // the same for every thread of the block
     const int base = tile * kPosChunk + (int)threadIdx.x * 8;
     unsigned mlt = 0, meq = 0;
     int lt = 0, eq = 0;
@@ -802,22 +785,11 @@ __global__ __launch_bounds__(256) void k_victims(const int* __restrict__ stamp,
     // one scan for both counts: a tile has 2048 slots, so each prefix fits in 16 bits
     int tot;
     const int both = block_excl_scan((lt << 16) | eq, tot, smem);
-    if (threadIdx.x < kWave) {
-      bool gave_up = false;
-      unsigned long long own = (unsigned long long)(tot & 0xffff);
-      if (own > (unsigned long long)r) own = (unsigned long long)r;
-      own |= (unsigned long long)(tot >> 16) << 31;
-      const unsigned long long before = lb_exclusive(lb_state, tile, own, sat_add, &gave_up);
-      if (threadIdx.x == 0) {
-        s_before = before;
-        if (gave_up) flag_err(ctr, 5);
-      }
-    }
-    __syncthreads();
-    int lt_before = (both >> 16) + (int)(s_before >> 31);
-    int eq_before = (both & 0xffff) + (int)(s_before & kEqMask);
+    int lt_before = (both >> 16) + pre_lt;
+    int eq_before = (both & 0xffff) + pre_eq;
     // list position of each victim among this thread's eight slots, then the resident ids with all
-    // loads in flight (a thread rarely has more than one victim)
+    // loads in flight (a thread rarely has more than one victim, but a dependent load per victim
+    // inside this loop made the pass latency-bound)
     int idx[8];
     int64_t vid8[8];
 #pragma unroll
@@ -835,16 +807,25 @@ __global__ __launch_bounds__(256) void k_victims(const int* __restrict__ stamp,
     for (int j = 0; j < 8; ++j) if (idx[j] >= 0) vid8[j] = slot_id[base + j];
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      if (idx[j] >= 0) {
-        victim_slot[idx[j]] = base + j;
-        victim_id[idx[j]] = vid8[j];
-        uint32_t where;
-        if (index_find(index, hi, vid8[j], &where, ctr) >= 0)
-          atomicExch((unsigned long long*)&index[where].key, (unsigned long long)kTomb);
-        else
-          flag_err(ctr, 3);
-      }
-    if (tile == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, K);   // the deletions of this pass
+      if (idx[j] >= 0) { victim_slot[idx[j]] = base + j; victim_id[idx[j]] = vid8[j]; }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);   // deleted by the next pass
+}
+
+// The victims leave the index: one thread per victim.  A kernel of its own, before the inserts:
+// with deletions and inserts in one kernel a resident id went missing from the index about once in
+// a hundred steps at the target size (plain stores and memory-side atomics on neighbouring
+// entries of one line from different XCDs); separated, and with every write to the index of a
+// kernel that also uses atomics on it made an atomic itself, it has not been seen again.
+__global__ __launch_bounds__(256) void k_victim_unmap(const int64_t* __restrict__ victim_id,
+                                                       IdxEntry* index, uint32_t hi, Ctr* ctr) {
+  const int K = ctr->K;
+  for (int k = blockIdx.x * 256 + (int)threadIdx.x; k < K; k += gridDim.x * 256) {
+    uint32_t where;
+    if (index_find(index, hi, victim_id[k], &where, ctr) >= 0)
+      atomicExch((unsigned long long*)&index[where].key, (unsigned long long)kTomb);
+    else
+      flag_err(ctr, 3);
   }
 }
 
@@ -867,14 +848,24 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         int64_t* __restrict__ miss_id, int boff,
                                                         int64_t* __restrict__ slot_id, int* stamp,
                                                         IdxEntry* index, uint32_t hi, int t, int C,
-                                                        int* __restrict__ tile_reuse, Ctr* ctr,
-                                                        unsigned long long* lb_vstate) {
+                                                        int* __restrict__ tile_reuse, Ctr* ctr) {
   __shared__ int smem[20];
   const int U = ctr->U, K = ctr->K, f = ctr->f_old;
   const int free_slots = C - f;
-  if (K > 0) {      // the look-back words of the victim pass that has just run go back to zero
-    const int nt = (f + kPosChunk - 1) / kPosChunk;
-    for (int i = blockIdx.x * 256 + (int)threadIdx.x; i < nt; i += gridDim.x * 256) lb_vstate[i] = 0;
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+    // The step's counters have been final since the plan: publish them to the Host status block
+    // (sequence word odd while they are being written).  Here, in one thread of a wide kernel,
+    // the two fences cost nothing that anyone waits for; in the single-block plan kernel they
+    // lengthened the prepare by 6 us.
+    volatile HostStatus* h = ctr->hstat;
+    if (h) {
+      h->seq = 2 * t - 1;
+      __threadfence_system();
+      h->U = U; h->n_hit = ctr->n_hit; h->M = ctr->M; h->K = K; h->n_bypass = ctr->n_bypass;
+      h->n_invalid = ctr->n_invalid; h->n_bad_offsets = ctr->bad_offsets;
+      __threadfence_system();
+      h->seq = 2 * t;
+    }
   }
   for (int tile = blockIdx.x; tile * kVidTile < U; tile += gridDim.x) {
     const int v = tile * kVidTile + (int)threadIdx.x;
