@@ -93,6 +93,7 @@ struct StepCtx {
   int32_t *d_inverse = nullptr, *d_slot = nullptr, *d_miss = nullptr;
   Ctr* ctr = nullptr;                 // device counters of this step
   int64_t* perm64 = nullptr;          // [max_ids] positions grouped by virtual id
+  int2* cold_pay = nullptr;           // [max_ids] per virtual id: the gradient rows of a cold group (-1 = none)
   int* pos_slot = nullptr;            // [max_ids] cache row of each position
   int* victim_slot = nullptr;         // [max_ids]
   int64_t* victim_id = nullptr;       // [max_ids]
@@ -148,8 +149,8 @@ struct sfc_cache {
   // beside the previous step's miss assignment and grouping, which still read that step's counts
   int* cnt2[2] = {nullptr, nullptr};
   int* cnt_rep2[2] = {nullptr, nullptr};
-  int* cursor = nullptr;                        // [max_ids] group cursor
-  int* cur_rep = nullptr;                       // [kHotRep, kHotBins] its copies for the lowest virtual ids
+  int64_t* grp = nullptr;                       // [max_ids] per virtual id: (positions << 32) | start of its group
+  int* cur_rep = nullptr;                       // [kHotRep, kHotBins] group cursors of the lowest virtual ids, one per copy
   int* n_unique = nullptr;                      // unique ids of the step whose unique passes ran last
   int* pos2bag = nullptr;                       // [max_ids] multi-hot: bag of each position
   int* tile_cnt = nullptr;                      // [max_ids / kVidTile + 1]
@@ -299,7 +300,7 @@ int rows_ready(sfc_cache* c, StepCtx* x) {
 // bp / bp_vid: the block-edge partial sums and their virtual ids, 2 per block of the stream; timed:
 // bracket the two kernels with profiling events (which may have to be created).
 int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common, double* bp,
-               int* bp_vid, bool timed) {
+               int* bp_vid, bool timed, bool skip_cold) {
   const int n = (int)x->n_ids;
   if (n <= 0) return SFC_OK;
   const SegGeom g = seg_geom(c->D, n);
@@ -307,12 +308,10 @@ int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common, d
   EventPair e1{}, e2{};
   int rc;
   if (timed && (rc = prof_begin(c, P_SEG_STREAM, c->st, &e1))) return rc;
-  if (x->d_offsets)
-    hipLaunchKernelGGL(k_seg_stream<false>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
-                       x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
-  else
-    hipLaunchKernelGGL(k_seg_stream<true>, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad,
-                       x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
+  auto kern = x->d_offsets ? (skip_cold ? k_seg_stream<false, true> : k_seg_stream<false, false>)
+                           : (skip_cold ? k_seg_stream<true, true> : k_seg_stream<true, false>);
+  hipLaunchKernelGGL(kern, dim3(nblk), dim3(256), 0, c->st, (const float4*)d_grad, x->perm64, n,
+                     c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
   if (timed && (rc = prof_end(c, P_SEG_STREAM, c->st, &e1))) return rc;
   if (timed && (rc = prof_begin(c, P_SEG_FINISH, c->st, &e2))) return rc;
   hipLaunchKernelGGL(k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), 0, c->st, bp,
@@ -519,7 +518,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->cnt2[0], c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->cnt2[1], c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->n_unique, 1))) goto bad;
-    if ((rc = dalloc(c, &c->cursor, c->max_ids))) goto bad;
+    if ((rc = dalloc(c, &c->grp, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->pos2bag, c->max_ids))) goto bad;
     if ((rc = dalloc(c, &c->tile_cnt, c->max_ids / kVidTile + 2))) goto bad;
     if ((rc = dalloc(c, &c->tile_reuse, c->max_ids / kVidTile + 2))) goto bad;
@@ -539,6 +538,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       StepCtx* x = &c->ctx[k];
       if ((rc = dalloc(c, &x->ctr, 1))) goto bad;
       if ((rc = dalloc(c, &x->perm64, c->max_ids))) goto bad;
+      if ((rc = dalloc(c, &x->cold_pay, c->max_ids))) goto bad;
       if ((rc = dalloc(c, &x->pos_slot, c->max_ids))) goto bad;
       if ((rc = dalloc(c, &x->victim_slot, c->max_ids))) goto bad;
       if ((rc = dalloc(c, &x->victim_id, c->max_ids))) goto bad;
@@ -684,12 +684,12 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
                      x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, cnt, cnt_rep,
                      c->cur_rep, c->tile_cnt,
-                     c->cursor, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
+                     c->grp, x->cold_pay, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,
                      c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
-                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->cursor, c->cur_rep,
+                       d_offsets ? c->pos2bag : (const int*)nullptr, n, c->grp, (int*)x->cold_pay, c->cur_rep,
                        x->perm64, d_slot, x->pos_slot, (int)c->C, x->boff, (int)n_bags);
   HIPCHK(hipGetLastError());
   if ((rc = prof_end(c, P_PREPARE, s, &ep))) return rc;
@@ -767,7 +767,7 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
   int rc;
   if ((rc = rows_ready(c, x))) return rc;
-  if ((rc = seg_launch(c, x, d_grad, d_common_grad, c->bp, c->bp_vid, true))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad, c->bp, c->bp_vid, true, false))) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -804,7 +804,7 @@ int sfc_segment_sum_static(sfc_cache* c, const float* d_grad, float* d_common_gr
   // every slot that k_seg_finish reads is written by k_seg_stream in the same call: nothing to clear
   double* bp = (double*)base;
   int* bp_vid = (int*)((unsigned char*)base + sums);
-  if ((rc = seg_launch(c, x, d_grad, d_common_grad, bp, bp_vid, false))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad, bp, bp_vid, false, false))) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -821,7 +821,7 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   hipStream_t s = c->st;
   EventPair ep{}, e1{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
-  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true, c->cfg.optimizer == SFC_OPT_ADAGRAD))) return rc;
   if (c->cfg.policy == SFC_POLICY_PREFETCH) {
     // the copies of a newer step issued so far read the Host table before this update writes it
     for (int k = 0; k < c->nctx; ++k) {
@@ -833,9 +833,11 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   if ((rc = prof_begin(c, P_ADAGRAD, s, &e1))) return rc;
   const dim3 ug(grid_for(x->n_ids * c->d4, 1024, kGridCap));
   if (c->cfg.optimizer == SFC_OPT_ADAGRAD) {
-    hipLaunchKernelGGL(k_adagrad_rows, ug, dim3(256), 0, s, (const float4*)c->gsum, x->d_slot,
+    // the stream above passed over the cold groups: this kernel sums them itself
+    auto kern = x->d_offsets ? k_adagrad_rows<false> : k_adagrad_rows<true>;
+    hipLaunchKernelGGL(kern, ug, dim3(256), 0, s, (const float4*)c->gsum, x->d_slot,
                        x->d_unique, (float4*)c->cw, (float4*)c->ca, c->host, (int)c->C, x->boff,
-                       c->cfg.lr, c->cfg.eps, c->d4, x->ctr);
+                       c->cfg.lr, c->cfg.eps, c->d4, x->ctr, x->cold_pay, (const float4*)d_grad);
   } else if (c->cfg.optimizer == SFC_OPT_ADAM) {
     // every constant derived from the decay rates is computed in double and rounded to fp32 once
     AdamArgs k;

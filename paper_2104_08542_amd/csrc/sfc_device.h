@@ -13,6 +13,23 @@ constexpr int64_t kTomb = -2;       // cache index: deleted entry (ids in the in
 constexpr int kMissMark = -2;       // d_slot value between resolve and assignment
 constexpr int kIntMax = 0x7fffffff;
 
+// Grouped positions (perm64): one 64-bit entry per position, (virtual id << 32) | gradient row,
+// groups in virtual-id order.  Virtual ids stay below 2^30, so bit 62 is free: it marks the
+// entries of a *cold* group, one of at most kColdMax positions whose virtual id lies outside the
+// range the grouping passes treat in LDS.  Nine rows in ten of a power-law batch are such rows.
+// Their gradients are summed by the optimizer kernel itself, straight from the gradient rows;
+// the segment-sum stream passes over them, and their rows of the common-gradient matrix are
+// neither written nor read.
+constexpr int kHotBins = 8192;      // lowest virtual ids: counted and grouped through LDS histograms
+constexpr int kColdMax = 2;
+constexpr int64_t kColdBit = (int64_t)1 << 62;
+__device__ __forceinline__ int entry_vid(int64_t e) { return (int)(e >> 32) & 0x3fffffff; }
+__device__ __forceinline__ bool entry_cold(int64_t e) { return (e & kColdBit) != 0; }
+// per virtual id: (positions << 32) | start of its group in perm64
+__device__ __forceinline__ bool group_cold(int v, int64_t grp) {
+  return v >= kHotBins && (int)(grp >> 32) <= kColdMax;
+}
+
 // Status block in pinned, device-mapped Host memory: kernels write it, the host reads it without
 // waiting for any stream (sfc_check, sfc_peek_stats and the first lines of every step call).
 // The published counters are guarded by a sequence word: odd while a kernel is writing them.

@@ -307,7 +307,6 @@ __global__ __launch_bounds__(256) void k_uniq_assign(const int* __restrict__ hsl
 // Virtual ids are handed out in order of first appearance, so the frequent ids of a power-law
 // batch are (nearly all) among the lowest ones: those are counted in an LDS histogram per block
 // and flushed with one coalesced atomic per bin; the rest go to HBM atomics on distinct words.
-constexpr int kHotBins = 8192;
 // Every block adds its tally of a frequent id to one counter: a thousand atomics in a row on one
 // address (about 10 ns each).  The counters of the hot bins are therefore kept in kHotRep copies,
 // block b using copy b mod kHotRep; resolve folds the copies into cnt, the miss assignment turns
@@ -382,7 +381,8 @@ __global__ __launch_bounds__(256) void k_pos2bag(const int64_t* __restrict__ off
 // lives at row C + boff + j: each step in flight has its own bypass region).
 __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse,
                                                   const int* __restrict__ pos2bag, int n,
-                                                  const int* __restrict__ cursor,
+                                                  const int64_t* __restrict__ grp,
+                                                  int* __restrict__ cold_pay,
                                                   int* cur_rep,
                                                   int64_t* __restrict__ perm64,
                                                   const int* __restrict__ slot,
@@ -392,6 +392,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   __syncthreads();
   const int base = blockIdx.x * kSortChunk;
   int vv[kSortPer], rr[kSortPer], sv[kSortPer], cb[kSortPer], pay[kSortPer];
+  unsigned coldm = 0;                       // bit j: position j of this thread belongs to a cold group
   // two levels of indirection, kSortPer loads in flight at each: position -> vid -> slot / group start
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
@@ -405,7 +406,12 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
     sv[j] = vv[j] >= 0 ? slot[vv[j]] : -1;
-    cb[j] = vv[j] >= kHotBins ? cursor[vv[j]] : 0;
+    cb[j] = 0;
+    if (vv[j] >= kHotBins) {
+      const int64_t g = grp[vv[j]];
+      cb[j] = (int)g;
+      if (group_cold(vv[j], g)) coldm |= 1u << j;
+    }
   }
   // the hot ids' ranks come from LDS; every group entry is written at the end
 #pragma unroll
@@ -414,7 +420,12 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
     if (vv[j] < 0) continue;
     rank_slot[p] = sv[j] >= C ? sv[j] + boff : sv[j];   // pos_slot: row index for the forward gather
     if (vv[j] < kHotBins) rr[j] = atomicAdd(&lh[vv[j]], 1);
-    else rr[j] += cb[j];
+    else {
+      // a cold group's gradient rows also go where the optimizer kernel finds them without
+      // walking the grouping: two words per virtual id, filled in the order of the ranks
+      if ((coldm >> j) & 1u) cold_pay[2 * vv[j] + rr[j]] = pay[j];
+      rr[j] += cb[j];
+    }
   }
   __syncthreads();
   int* mine = cur_rep + (blockIdx.x & (kHotRep - 1)) * kHotBins;
@@ -435,7 +446,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
   for (int j = 0; j < kSortPer; ++j)
     if (vv[j] >= 0) {
       const int at = vv[j] < kHotBins ? lh[vv[j]] + rr[j] : rr[j];
-      perm64[at] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j];
+      perm64[at] = ((int64_t)vv[j] << 32) | (uint32_t)pay[j] | ((coldm >> j) & 1u ? kColdBit : (int64_t)0);
     }
 }
 
@@ -839,7 +850,8 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         int* __restrict__ cnt_rep,
                                                         int* __restrict__ cur_rep,
                                                         const int* __restrict__ tile_coff,
-                                                        int* __restrict__ cursor,
+                                                        int64_t* __restrict__ grp,
+                                                        int2* __restrict__ cold_pay,
                                                         const int* __restrict__ tile_moff,
                                                         const int* __restrict__ victim_slot,
                                                         int* __restrict__ slot_out,
@@ -872,8 +884,12 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
     const bool miss = v < U && slot_out[v] == kMissMark;
     int tot;
     // start of the group of virtual id v in perm64 = exclusive scan of cnt
-    const int off = block_excl_scan(v < U ? cnt[v] : 0, tot, smem) + tile_coff[tile];
-    if (v < U) cursor[v] = off;
+    const int nv = v < U ? cnt[v] : 0;
+    const int off = block_excl_scan(nv, tot, smem) + tile_coff[tile];
+    if (v < U) {
+      grp[v] = ((int64_t)nv << 32) | (uint32_t)off;
+      cold_pay[v] = make_int2(-1, -1);          // the grouping pass fills in the cold groups' rows
+    }
     if (v < U && v < kHotBins) {                // one cursor per copy of a hot bin; copies back to zero
       int at = off;
 #pragma unroll

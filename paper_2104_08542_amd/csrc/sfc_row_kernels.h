@@ -329,7 +329,15 @@ __device__ __forceinline__ void chain_slots(int nslots, const int* __restrict__ 
 // non-temporal loads (measured 75 against 96 us at the target one-hot configuration).  Multi-hot: a
 // bag's row is read once per position of the bag, from all over the grouping: plain loads, so that
 // the caches keep what they can (358 against 410 us at the multi-hot configuration).
-template <bool kOneHot>
+// kSkipCold: entries of cold groups (see kColdBit) are passed over, their gradient rows are not
+// read: sfc_backward_update with the Adagrad kernel, which sums those groups itself.  An entry
+// that is passed over acts as a separator (key -1): it ends the run before it and begins none.
+template <bool kSkipCold>
+__device__ __forceinline__ int entry_key(int64_t e) {
+  return (kSkipCold && entry_cold(e)) ? -1 : entry_vid(e);
+}
+
+template <bool kOneHot, bool kSkipCold>
 __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ grad,
                                                      const int64_t* __restrict__ perm64, int n,
                                                      int d4, int G, int L,
@@ -360,7 +368,7 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
   int tail_v = -1; D4 tail_s; d4_zero(tail_s);     // run that continues past the span
 
   if (nonempty) {
-    const int prev_v = sb > 0 ? (int)(perm64[sb - 1] >> 32) : -1;
+    const int prev_v = sb > 0 ? entry_key<kSkipCold>(perm64[sb - 1]) : -1;
     // software pipeline: pe / x = entries and grad rows of the chunk being processed (issued one
     // iteration earlier), pn = the next chunk's entries
     int64_t pe[kSegChunk], pn[kSegChunk];
@@ -370,12 +378,13 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
 #pragma unroll
     for (int k = 0; k < kSegChunk; ++k) {
       x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (pe[k] >= 0) x[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pe[k] * d4 + c4]);
+      if (pe[k] >= 0 && entry_key<kSkipCold>(pe[k]) >= 0)
+        x[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pe[k] * d4 + c4]);
     }
 #pragma unroll
     for (int k = 0; k < kSegChunk; ++k)
       pn[k] = sb + kSegChunk + k < se ? perm64[sb + kSegChunk + k] : (int64_t)-1;
-    cur = (int)(pe[0] >> 32);
+    cur = entry_key<kSkipCold>(pe[0]);
     begun = prev_v != cur;
 
     for (int64_t e = sb; e < se; e += kSegChunk) {
@@ -385,7 +394,8 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
 #pragma unroll
       for (int k = 0; k < kSegChunk; ++k) {
         xn[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (pn[k] >= 0) xn[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pn[k] * d4 + c4]);
+        if (pn[k] >= 0 && entry_key<kSkipCold>(pn[k]) >= 0)
+          xn[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pn[k] * d4 + c4]);
       }
 #pragma unroll
       for (int k = 0; k < kSegChunk; ++k) {
@@ -395,9 +405,9 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
 #pragma unroll
       for (int k = 0; k < kSegChunk; ++k) {
         if (pe[k] >= 0) {
-          const int v = (int)(pe[k] >> 32);
+          const int v = entry_key<kSkipCold>(pe[k]);
           if (v != cur) {
-            if (begun) common[(int64_t)cur * d4 + c4] = d4_round(acc);
+            if (begun) { if (cur >= 0) common[(int64_t)cur * d4 + c4] = d4_round(acc); }
             else { head_v = cur; head_s = acc; }
             cur = v; begun = true; d4_zero(acc);
           }
@@ -408,9 +418,9 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
       for (int k = 0; k < kSegChunk; ++k) { pe[k] = pn[k]; pn[k] = pnn[k]; x[k] = xn[k]; }
     }
     // close the span: the open run either ends here or continues into the next span
-    const int next_v = se < n ? (int)(perm64[se] >> 32) : -1;
-    if (next_v != cur) {
-      if (begun) common[(int64_t)cur * d4 + c4] = d4_round(acc);
+    const int next_v = se < n ? entry_key<kSkipCold>(perm64[se]) : -1;
+    if (next_v != cur || cur < 0) {
+      if (begun) { if (cur >= 0) common[(int64_t)cur * d4 + c4] = d4_round(acc); }
       else { head_v = cur; head_s = acc; }
     } else if (begun) {
       tail_v = cur; tail_s = acc;
@@ -471,12 +481,27 @@ __global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ b
   const int j = (int)blockIdx.x;
   const int v = bp_vid[j];
   if (v < 0 || (j > 0 && bp_vid[j - 1] == v)) return;     // not the first slot of its run
+  // the run's end: "same vid" is true on the run and false after it, so the block probes 256
+  // places at once and narrows the bracket by that factor per round (two rounds for thousands of
+  // slots, where a bisection took a dozen dependent loads)
+  __shared__ int s_cnt[4];
+  const int tid = (int)threadIdx.x;
   int lo = j, hi = nslots;                                 // bp_vid[lo] == v, run ends in (lo, hi]
   while (hi - lo > 1) {
-    const int mid = lo + (hi - lo) / 2;
-    if (bp_vid[mid] == v) lo = mid; else hi = mid;
+    const int step = (hi - lo + 255) / 256;
+    const int probe = lo + (tid + 1) * step;
+    const bool same = probe < hi && bp_vid[probe] == v;
+    const uint64_t m = __ballot(same);
+    if ((tid & 63) == 0) s_cnt[tid >> 6] = __popcll(m);
+    __syncthreads();
+    const int k = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];   // probes 1..k are on the run
+    __syncthreads();
+    const int nlo = lo + k * step;
+    int nhi = lo + (k + 1) * step;
+    if (nhi > hi) nhi = hi;
+    lo = nlo; hi = nhi;
   }
-  const int end = hi, D = d4 * 4, tid = (int)threadIdx.x;
+  const int end = hi, D = d4 * 4;
   const int groups = 256 / d4, g = tid / d4, c4 = tid - g * d4;
   double s0 = 0., s1 = 0., s2 = 0., s3 = 0.;
   if (g < groups) {
@@ -532,31 +557,66 @@ __device__ __forceinline__ bool stream_rows(int U, int d4, int s4) {
 // Adagrad over the common-gradient matrix (one row per virtual id), four rows per thread in flight.
 // A bypass row (slot >= C: a miss that found no cache slot) is also written to the Host table
 // here: it lives for this step only.
-template <bool kStream>
+// kGather: the gradient of a cold row (see kColdBit) is summed here from its at most kColdMax
+// gradient rows (cold_pay[v] = their numbers, -1 = none; both -1 = not a cold row), in fp64,
+// lower gradient row first (so the sum does not depend on the order in which the grouping pass
+// happened to rank the group's positions); every other row takes its sum from the common-gradient
+// matrix.  kOneHot: a gradient row is read once per step.
+template <bool kStream, bool kGather, bool kOneHot>
 __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
                                              const int* __restrict__ slot,
                                              const int64_t* __restrict__ unique_ids,
                                              float4* __restrict__ cw, float4* __restrict__ ca,
                                              const HostRows& h, int C, int boff, float lr, float eps,
-                                             int d4, int U) {
+                                             int d4, int U, const int2* __restrict__ cold_pay,
+                                             const float4* __restrict__ grad) {
+  static_assert(kColdMax == 2, "the gather path below takes two gradient rows");
   const int64_t total = (int64_t)U * d4;
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 4 * stride) {
-    float4 g[4], w[4], a[4];
+    float4 g[4], w[4], a[4], x1[4];
     int64_t r[4];
-    int sl[4];
+    int sl[4], vrow[4], cc[4];
+    int2 cp[4];
+    // two levels of indirection, four rows in flight at each: slot and cold rows of the row, then
+    // its weights, state and gradient (one row of the common matrix, or its own one or two rows)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t i = i0 + u * stride;
-      r[u] = -1;
+      r[u] = -1; sl[u] = -1; cp[u] = make_int2(-1, -1);
       if (i < total) {
-        sl[u] = slot[(int)(i / d4)];
-        if (sl[u] >= 0) {
-          r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + (i % d4);
-          g[u] = ld_row<kStream>(&common[i]); w[u] = ld_row<kStream>(&cw[r[u]]);
-          a[u] = ld_row<kStream>(&ca[r[u]]);
-        }
+        vrow[u] = (int)(i / d4); cc[u] = (int)(i - (int64_t)vrow[u] * d4);
+        sl[u] = slot[vrow[u]];
+        if (kGather) cp[u] = cold_pay[vrow[u]];
       }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      x1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (sl[u] < 0) continue;
+      r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + cc[u];
+      w[u] = ld_row<kStream>(&cw[r[u]]);
+      a[u] = ld_row<kStream>(&ca[r[u]]);
+      if (kGather && cp[u].x >= 0) {
+        // lower gradient row first
+        const bool two = cp[u].y >= 0;
+        const int q0 = two && cp[u].y < cp[u].x ? cp[u].y : cp[u].x;
+        const int q1 = two && cp[u].y < cp[u].x ? cp[u].x : cp[u].y;
+        g[u] = ld_row<kOneHot>(&grad[(int64_t)q0 * d4 + cc[u]]);
+        if (two) x1[u] = ld_row<kOneHot>(&grad[(int64_t)q1 * d4 + cc[u]]);
+      } else {
+        g[u] = ld_row<kStream>(&common[(int64_t)vrow[u] * d4 + cc[u]]);
+      }
+    }
+    if (kGather) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (cp[u].x >= 0 && cp[u].y >= 0) {
+          g[u].x = (float)((double)g[u].x + (double)x1[u].x);
+          g[u].y = (float)((double)g[u].y + (double)x1[u].y);
+          g[u].z = (float)((double)g[u].z + (double)x1[u].z);
+          g[u].w = (float)((double)g[u].w + (double)x1[u].w);
+        }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -564,25 +624,30 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
         adagrad4v(w[u], a[u], g[u], lr, eps);
         st_row<kStream>(&cw[r[u]], w[u]); st_row<kStream>(&ca[r[u]], a[u]);
         if (sl[u] >= C) {
-          const int64_t i = i0 + u * stride;
-          const int64_t hr = unique_ids[(int)(i / d4)] * h.hs4 + (i % d4);
-          h.w[hr] = w[u];
-          h.a[unique_ids[(int)(i / d4)] * h.has4 + (i % d4)] = a[u];
+          const int64_t id = unique_ids[vrow[u]];
+          h.w[id * h.hs4 + cc[u]] = w[u];
+          h.a[id * h.has4 + cc[u]] = a[u];
         }
       }
   }
 }
 
+// cold rows are summed here (the stream that ran before passed over them)
+template <bool kOneHot>
 __global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__ common,
                                                        const int* __restrict__ slot,
                                                        const int64_t* __restrict__ unique_ids,
                                                        float4* __restrict__ cw,
                                                        float4* __restrict__ ca, HostRows h, int C,
                                                        int boff, float lr, float eps, int d4,
-                                                       const Ctr* ctr) {
+                                                       const Ctr* ctr,
+                                                       const int2* __restrict__ cold_pay,
+                                                       const float4* __restrict__ grad) {
   const int U = ctr->U;
-  if (stream_rows(U, d4, d4)) adagrad_rows<true>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U);
-  else adagrad_rows<false>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U);
+  if (stream_rows(U, d4, d4))
+    adagrad_rows<true, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad);
+  else
+    adagrad_rows<false, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad);
 }
 
 // ---------------------------------------------------------------------------------------------
