@@ -252,7 +252,24 @@ def main():
     traffic = measured_traffic(w.name, dom)
     pair_bytes = b_lookup + b_update
     pair_ms = ms["lookup"] + ms["backward_update"]
+    pair_kernel_ms = ms["lookup"] + ms["k_seg_stream"] + ms["k_seg_finish"] + ms["k_adagrad_rows"]
     link_ms = ms["fetch_misses"]
+
+    # what plain copies reach over the same link, one direction at a time (pinned buffer, 256 MiB)
+    hb = torch.empty(1 << 28, dtype=torch.uint8, pin_memory=True)
+    db = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+    copy_gbs = {}
+    for name, src, dst in (("h2d", hb, db), ("d2h", db, hb)):
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(4):
+            dst.copy_(src, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs[name] = 4 * (1 << 28) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del hb, db
 
     result = {
         "metric": "raw ids/sec through prepare+fetch_misses+lookup+backward_update",
@@ -282,9 +299,10 @@ def main():
             "bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
             "algorithmic_bytes_per_launch": kernels[dom][0], "avg_ms": kernels[dom][1],
-            "timing_source": "hipEvents on the kernel's own stream in this run, pass 2: the same "
-                             "calls on the batches that follow the timed region, issued so that "
-                             "the streams do not overlap (each kernel has the GPU to itself)",
+            "timing_source": "hipEvents that the kernel's dispatch records at its start and end, on its "
+                             "own stream, in this run, pass 2: the same calls on the batches that "
+                             "follow the timed region, issued so that the streams do not overlap "
+                             "(each kernel has the GPU to itself)",
             "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
                               "earlier run of this command, calibrated against a copy kernel); not "
                               "measured in this run",
@@ -293,14 +311,24 @@ def main():
                         "GB/s": (v[0] / (v[1] * 1e-3) / 1e9 if v[1] else None)} for k, v in kernels.items()},
         "lookup_plus_update": {"algorithmic_bytes": pair_bytes, "avg_ms": pair_ms,
                                "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
-                               "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                               "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                               "what": "the lookup kernel's duration + the backward_update call between "
+                                       "two events on its stream (three kernels and their launch gaps)",
+                               "kernel_ms_sum": pair_kernel_ms,
+                               "frac_of_hbm_peak_kernel_time": (pair_bytes / (pair_kernel_ms * 1e-3) / 1e9
+                                                                / HBM_PEAK_GBS) if pair_kernel_ms else None},
         "call_ms": {k: ms[k] for k in ("prepare", "fetch_misses", "lookup", "backward_update")},
         "kernel_ms": {"k_seg_stream": ms["k_seg_stream"], "k_seg_finish": ms["k_seg_finish"],
                       "k_%s_rows" % args.optimizer: ms["k_adagrad_rows"]},
         "call_ms_overlapped": overlapped_ms,
         "host_link": {"h2d_bytes_per_step": avg["h2d_bytes"], "d2h_bytes_per_step": avg["d2h_bytes"],
                       "GB/s": ((avg["h2d_bytes"] + avg["d2h_bytes"]) / (link_ms * 1e-3) / 1e9
-                               if link_ms else None)},
+                               if link_ms else None),
+                      "copy_GB/s": copy_gbs,
+                      # the time plain copies would need (the two directions side by side, each at
+                      # its own measured rate) over the time the copies of a step take
+                      "frac_of_measured_copy": (max(avg["h2d_bytes"] / copy_gbs["h2d"], avg["d2h_bytes"] / copy_gbs["d2h"])
+                                                / 1e9 / (link_ms * 1e-3) if link_ms else None)},
     }
 
     if not args.no_cpu_baseline:

@@ -277,13 +277,17 @@ int sfc_verify(sfc_cache* c, int64_t* h_bad /* [4] */);
 int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h_rows, float* h_acc);
 
 /*
- * Device timing.  level 1: hipEvents bracket the work of each step call on the stream it runs
- * on (with lookahead >= 1 the prepare runs on two library streams; its events sit on the one of
- * the cache manager's kernels and include its wait for the unique passes on the other).  level 2: also each of the three kernels inside sfc_backward_update (the extra events
- * lengthen the call a little, so call timings are best read at level 1).  level 0: off.
- * sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare, fetch_misses,
- * lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel, Adagrad kernel),
- * the summed milliseconds and the number of launches since the last read of that entry.
+ * Device timing.  level 1: the step calls.  sfc_prepare, sfc_fetch_misses and sfc_backward_update
+ * (several kernels each) are bracketed by hipEvents on the stream they run on, so their times
+ * include the launch latencies between the events (with lookahead >= 1 the prepare runs on two
+ * library streams; its events sit on the one of the cache manager's kernels and include its wait
+ * for the unique passes on the other).  sfc_lookup is one kernel: its start and end are recorded
+ * by the dispatch itself, i.e. the time is the kernel's own duration as a profiler's kernel trace
+ * shows it.  level 2: also, the same way, each of the three kernels inside sfc_backward_update.
+ * level 0: off.  sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare,
+ * fetch_misses, lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel,
+ * optimizer kernel), the summed milliseconds and the number of launches since the last read of
+ * that entry.
  */
 int sfc_profile_enable(sfc_cache* c, int32_t level);
 int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);

@@ -2,9 +2,13 @@
 // per-position inverse) and the MixCache manager (resolve against the index in HBM, victim
 // selection by batch-granular LRU, slot assignment, index maintenance).
 //
-// Determinism: every output is a function of the input sets and slot numbers only.  Orders are
-// produced by prefix scans over positions / virtual ids / slots, never by arrival order of
-// atomics; atomics are used only where the result is order-free (min, counters, set insert).
+// Determinism: every output of sfc_prepare (unique ids, inverse, slots, miss and victim lists,
+// cache state) is a function of the input sets and slot numbers only: their orders come from
+// prefix scans over positions / virtual ids / slots, and atomics are used only where the result
+// is order-free (min, counters, set insert).  The one thing that does follow the arrival order of
+// atomics is internal: the order of a group's entries in perm64 (k_uniq_inverse ranks the
+// positions of an id by the value its counting atomic returns).  It decides the order of an fp64
+// sum, nothing else; see the segment-sum kernels for what that means for the results.
 #pragma once
 #include "sfc_device.h"
 

@@ -246,7 +246,11 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 //     wavefront chain their partials through LDS once, at the end; runs cut by the wavefront's
 //     edge are chained once more across the block's four wavefronts; what is cut by the
 //     block's edge goes to bp[block][0 = head, 1 = tail] in HBM and k_seg_finish chains those.
-// No atomics; the summation tree depends only on perm64, n and D.
+// No atomics; the summation tree depends only on perm64, n and D.  perm64 itself lists a group's
+// positions in the order the grouping pass ranked them, which its atomics decide, so the fp64 sum
+// of a frequent id can differ in its last bits from run to run; rounded to fp32 once, the results
+// of two runs are nearly always identical and never further apart than one unit in the last place
+// of the sum (ids with at most kColdMax positions are added in a fixed order and are identical).
 // A run that covers a whole span (wavefront) stores its sum in the head slot and a zero in the
 // tail slot under the same vid, so equal vids are always adjacent in the partial lists.
 //
@@ -262,7 +266,10 @@ __global__ __launch_bounds__(256) void k_lookup_bags(const int64_t* __restrict__
 constexpr int kSegChunk = SFC_SEG_CHUNK;        // entries per group per loop iteration
 // the stream never has more wavefronts than this: 48 per compute unit measured best at the target
 // size (16: stream 82 us + finish 10; 48: 75 + 14; the finish pass grows with the number of blocks)
-constexpr int kSegTargetWaves = 256 * 48;
+#ifndef SFC_SEG_WAVES
+#define SFC_SEG_WAVES 48
+#endif
+constexpr int kSegTargetWaves = 256 * SFC_SEG_WAVES;
 
 struct SegGeom { int G, L, waves; };
 // L is chosen so that the stream has about kSegTargetWaves wavefronts, never below 32 entries.
@@ -562,6 +569,11 @@ __device__ __forceinline__ bool stream_rows(int U, int d4, int s4) {
 // lower gradient row first (so the sum does not depend on the order in which the grouping pass
 // happened to rank the group's positions); every other row takes its sum from the common-gradient
 // matrix.  kOneHot: a gradient row is read once per step.
+#ifndef SFC_UPD_ROWS
+#define SFC_UPD_ROWS 3
+#endif
+constexpr int kUpdRows = SFC_UPD_ROWS;     // rows per thread in flight in the Adagrad kernel
+
 template <bool kStream, bool kGather, bool kOneHot>
 __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
                                              const int* __restrict__ slot,
@@ -573,15 +585,15 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
   static_assert(kColdMax == 2, "the gather path below takes two gradient rows");
   const int64_t total = (int64_t)U * d4;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 4 * stride) {
-    float4 g[4], w[4], a[4], x1[4];
-    int64_t r[4];
-    int sl[4], vrow[4], cc[4];
-    int2 cp[4];
-    // two levels of indirection, four rows in flight at each: slot and cold rows of the row, then
+  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += kUpdRows * stride) {
+    float4 g[kUpdRows], w[kUpdRows], a[kUpdRows], x1[kUpdRows];
+    int64_t r[kUpdRows];
+    int sl[kUpdRows], vrow[kUpdRows], cc[kUpdRows];
+    int2 cp[kUpdRows];
+    // two levels of indirection, kUpdRows rows in flight at each: slot and cold rows of the row, then
     // its weights, state and gradient (one row of the common matrix, or its own one or two rows)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kUpdRows; ++u) {
       const int64_t i = i0 + u * stride;
       r[u] = -1; sl[u] = -1; cp[u] = make_int2(-1, -1);
       if (i < total) {
@@ -591,7 +603,7 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kUpdRows; ++u) {
       x1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (sl[u] < 0) continue;
       r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + cc[u];
@@ -610,7 +622,7 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
     }
     if (kGather) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < kUpdRows; ++u)
         if (cp[u].x >= 0 && cp[u].y >= 0) {
           g[u].x = (float)((double)g[u].x + (double)x1[u].x);
           g[u].y = (float)((double)g[u].y + (double)x1[u].y);
@@ -619,7 +631,7 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
         }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < kUpdRows; ++u)
       if (r[u] >= 0) {
         adagrad4v(w[u], a[u], g[u], lr, eps);
         st_row<kStream>(&cw[r[u]], w[u]); st_row<kStream>(&ca[r[u]], a[u]);
@@ -634,7 +646,11 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
 
 // cold rows are summed here (the stream that ran before passed over them)
 template <bool kOneHot>
-__global__ __launch_bounds__(256) void k_adagrad_rows(const float4* __restrict__ common,
+__global__ __launch_bounds__(256)
+#ifdef SFC_UPD_WAVES
+__attribute__((amdgpu_waves_per_eu(SFC_UPD_WAVES, SFC_UPD_WAVES)))
+#endif
+void k_adagrad_rows(const float4* __restrict__ common,
                                                        const int* __restrict__ slot,
                                                        const int64_t* __restrict__ unique_ids,
                                                        float4* __restrict__ cw,

@@ -18,7 +18,7 @@ def test_paper_vsi_example():
     pr = _oracle().prepare(np.array(g["batch"]))
     assert pr.unique_ids.tolist() == g["global_id"]
     assert pr.inverse.tolist() == g["virtual_id"]
-    # "able to recover the data": global_id indexed by virtual_id is the batch
+    # the batch can be recovered from the two outputs: global_id indexed by virtual_id is the batch
     assert pr.unique_ids[pr.inverse].tolist() == g["batch"]
 
 
