@@ -72,6 +72,15 @@ extern "C" {
 #define SFC_OPT_ADAM 1
 #define SFC_OPT_ROWWISE_ADAGRAD 2
 
+/* The manager's id -> slot index in HBM.  DENSE: one int per Host row (4 * host_rows bytes): no
+ * probing, no deleted entries, no rebuild.  HASHED: open addressing with 16-byte entries, four per
+ * possible resident id, rebuilt on the device when deleted entries pass an eighth of it: for id
+ * ranges whose dense map would not fit.  AUTO takes DENSE up to SFC_DENSE_INDEX_MAX_BYTES. */
+#define SFC_INDEX_AUTO 0
+#define SFC_INDEX_HASHED 1
+#define SFC_INDEX_DENSE 2
+#define SFC_DENSE_INDEX_MAX_BYTES ((int64_t)32 << 30)
+
 typedef struct sfc_cache sfc_cache; /* opaque */
 
 typedef struct {
@@ -107,7 +116,7 @@ typedef struct {
   void* stream;               /* hipStream_t for prepare / lookup / backward_update */
   void* side_stream;          /* hipStream_t for the Host<->cache copies; may equal stream */
   int32_t optimizer;          /* SFC_OPT_* */
-  int32_t reserved;           /* 0 */
+  int32_t index_kind;         /* SFC_INDEX_AUTO (0), SFC_INDEX_HASHED or SFC_INDEX_DENSE */
   int64_t host_state_stride;  /* floats between consecutive rows of h_acc; 0 = S */
   double beta1, beta2;        /* Adam's decay rates (ignored otherwise) */
 } sfc_config;

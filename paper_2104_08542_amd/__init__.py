@@ -23,6 +23,7 @@ LIB_PATH = os.path.join(_HERE, "libsfc.so")
 SFC_OK, SFC_EINVAL, SFC_ESTATE, SFC_EHIP, SFC_ENOMEM, SFC_ELIMIT, SFC_ECORRUPT = 0, -1, -2, -3, -4, -5, -6
 SFC_POLICY_LRU_BATCH = 0
 SFC_POLICY_PREFETCH = 1
+SFC_INDEX_AUTO, SFC_INDEX_HASHED, SFC_INDEX_DENSE = 0, 1, 2
 
 EXPORTS = [
     "sfc_host_alloc", "sfc_host_free", "sfc_cache_create", "sfc_cache_destroy", "sfc_prepare",
@@ -46,7 +47,7 @@ class sfc_config(ctypes.Structure):
         ("host_rows", ctypes.c_int64), ("h_weights", ctypes.c_void_p), ("h_acc", ctypes.c_void_p),
         ("host_row_stride", ctypes.c_int64), ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("lookahead", ctypes.c_int32),
         ("max_steps", ctypes.c_int32), ("stream", ctypes.c_void_p), ("side_stream", ctypes.c_void_p),
-        ("optimizer", ctypes.c_int32), ("reserved", ctypes.c_int32), ("host_state_stride", ctypes.c_int64),
+        ("optimizer", ctypes.c_int32), ("index_kind", ctypes.c_int32), ("host_state_stride", ctypes.c_int64),
         ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
     ]
 
@@ -315,7 +316,7 @@ class Cache:
 
     def __init__(self, table: HostTable, capacity_rows: int, max_ids: int, max_bags: Optional[int] = None,
                  lr=0.01, eps=1e-8, lookahead=0, max_steps=0, device="cuda:0", side_stream=True,
-                 betas=(0.9, 0.999), policy=None):
+                 betas=(0.9, 0.999), policy=None, index_kind=SFC_INDEX_AUTO):
         self.table, self.C, self.D = table, int(capacity_rows), table.dim
         self.device = torch.device(device)
         self.max_ids = int(max_ids)
@@ -327,7 +328,7 @@ class Cache:
             cfg = sfc_config(self.C, self.D, SFC_POLICY_LRU_BATCH if policy is None else policy, self.max_ids, self.max_bags,
                              table.rows, table._pw, table._pa, table.stride, lr, eps, lookahead,
                              max_steps, self.stream.cuda_stream, self.side.cuda_stream,
-                             OPTIMIZERS.index(table.optimizer), 0, table.state_stride,
+                             OPTIMIZERS.index(table.optimizer), index_kind, table.state_stride,
                              betas[0], betas[1])
             self.h = sfc_cache_create(cfg)
             self.bufs = [StepBuffers(max(self.max_ids, 1), self.device) for _ in range(self.lookahead + 1)]

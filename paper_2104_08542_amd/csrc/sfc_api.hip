@@ -137,7 +137,8 @@ struct sfc_cache {
   int S = 0, s4 = 0;                            // floats / 16-byte chunks of optimizer state per row
   int64_t* slot_id = nullptr;                   // [C]
   int* stamp = nullptr;                         // [C]
-  IdxEntry* index = nullptr; uint32_t hi = 0;   // cache index
+  IdxEntry* index = nullptr; uint32_t hi = 0;   // cache index, hashed kind
+  int* dmap = nullptr;                          // cache index, dense kind: [V] slot per id or -1 (else nullptr)
   int* hist = nullptr; int hist_len = 0;        // [max_steps + 2]
   UEntry* utab = nullptr; int* uvid = nullptr;  // batch table [2*max_ids]: key + first position; vid
   int* hslot = nullptr;                         // [max_ids]
@@ -454,6 +455,8 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   if (cfg->max_steps < 0) return fail(SFC_EINVAL, "max_steps must be >= 0");
   if (cfg->optimizer < SFC_OPT_ADAGRAD || cfg->optimizer > SFC_OPT_ROWWISE_ADAGRAD)
     return fail(SFC_EINVAL, "unknown optimizer");
+  if (cfg->index_kind < SFC_INDEX_AUTO || cfg->index_kind > SFC_INDEX_DENSE)
+    return fail(SFC_EINVAL, "unknown index_kind");
   const int S = cfg->optimizer == SFC_OPT_ADAM ? 2 * cfg->dim
               : cfg->optimizer == SFC_OPT_ROWWISE_ADAGRAD ? 4 : cfg->dim;
   if (cfg->host_state_stride && (cfg->host_state_stride < S || cfg->host_state_stride % 4))
@@ -473,7 +476,10 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
   c->side = cfg->side_stream ? (hipStream_t)cfg->side_stream : c->st;
   c->hist_len = (cfg->max_steps ? cfg->max_steps : (1 << 20)) + 2;
   (void)hipGetDevice(&c->device);
-  {
+  const bool dense = cfg->index_kind == SFC_INDEX_DENSE ||
+                     (cfg->index_kind == SFC_INDEX_AUTO &&
+                      cfg->host_rows * (int64_t)sizeof(int) <= SFC_DENSE_INDEX_MAX_BYTES);
+  if (!dense) {
     // four entries per possible resident id keep probe sequences short (HBM is plentiful); two
     // where four would not fit a 32-bit entry number
     int64_t h = 4 * (c->C + c->max_ids);
@@ -535,6 +541,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     if ((rc = dalloc(c, &c->slot_id, c->C))) goto bad;
     if ((rc = dalloc(c, &c->stamp, c->C))) goto bad;
     if ((rc = dalloc(c, &c->index, (int64_t)c->hi))) goto bad;
+    if (dense && (rc = dalloc(c, &c->dmap, c->V))) goto bad;
     if ((rc = dalloc(c, &c->hist, (int64_t)c->hist_len))) goto bad;
     if ((rc = dalloc(c, &c->utab, hu))) goto bad;
     if ((rc = dalloc(c, &c->uvid, hu))) goto bad;
@@ -585,6 +592,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->stamp, c->C, 0);
     IdxEntry empty; empty.key = kEmpty; empty.slot = -1; empty.pad = 0;
     fill<IdxEntry>(s, c->index, (int64_t)c->hi, empty);
+    if (dense) fill<int>(s, c->dmap, c->V, -1);
     fill<int>(s, c->hist, (int64_t)c->hist_len, 0);
     fill<int>(s, c->age_hist, (int64_t)kAgeBins, 0);
     fill<int>(s, c->n_invalid, 1, 0);
@@ -594,7 +602,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
     fill<int>(s, c->tile_reuse, c->max_ids / kVidTile + 2, 0);
     UEntry uempty; uempty.key = kEmpty; uempty.minpos = kIntMax; uempty.pad = 0;
     fill<UEntry>(s, c->utab, hu, uempty);
-    Ctr z; memset(&z, 0, sizeof z); z.oldest = 1; z.hstat = c->d_hstat;
+    Ctr z; memset(&z, 0, sizeof z); z.oldest = 1; z.hstat = c->d_hstat; z.dense = dense ? 1 : 0;
     for (int k = 0; k < c->nctx; ++k)
       if ((e = hipMemcpyAsync(c->ctx[k].ctr, &z, sizeof z, hipMemcpyHostToDevice, s)) != hipSuccess) {
         rc = fail(SFC_EHIP, "cache initialisation", e); goto bad;
@@ -689,17 +697,22 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   }
   // from here on behind the whole prepare of the previous step: the step's counters start from
   // that step's, the index is rebuilt if its plan asked for it
-  hipLaunchKernelGGL(k_ctr_init, dim3(kRebuildGrid), dim3(256), 0, s, x->ctr, prev->ctr, c->n_unique,
-                     c->n_invalid, c->index, c->hi, x->t);
-  hipLaunchKernelGGL(k_index_refill, dim3(kRebuildGrid), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
+  // (a dense index is never rebuilt: k_resolve starts the counters itself, neither is launched)
+  if (!c->dmap) {
+    hipLaunchKernelGGL(k_ctr_init, dim3(kRebuildGrid), dim3(256), 0, s, x->ctr, prev->ctr,
+                       c->n_unique, c->n_invalid, c->index, c->hi, x->t);
+    hipLaunchKernelGGL(k_index_refill, dim3(kRebuildGrid), dim3(256), 0, s, c->index, c->hi, c->slot_id, x->ctr);
+  }
+  const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
+  hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
+                     c->index, c->hi, c->dmap, c->stamp, c->hist, x->t, d_slot, c->tile_miss, cnt, cnt_rep,
+                     c->tile_cnt, c->age_hist, x->ctr, c->dmap ? (const Ctr*)prev->ctr : (const Ctr*)nullptr,
+                     (const int*)c->n_unique, c->n_invalid);
+  if (c->ins) { HIPCHK(hipEventRecord(c->ev_resolved, s)); c->resolved_once = true; }
+  // (after the resolve: it tallies into the step's counters, which that kernel may have started)
   if (n > 0 && d_offsets)
     hipLaunchKernelGGL(k_pos2bag, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, s,
                        d_offsets, (int)n_bags, n, c->pos2bag, x->ctr);
-  const int gr = grid_for(n, 4 * kVidTile, kResolveGrid);
-  hipLaunchKernelGGL(k_resolve, dim3(gr), dim3(256), 0, s, d_unique_ids, c->vid_hslot, c->utab,
-                     c->index, c->hi, c->stamp, c->hist, x->t, d_slot, c->tile_miss, cnt, cnt_rep,
-                     c->tile_cnt, c->age_hist, x->ctr);
-  if (c->ins) { HIPCHK(hipEventRecord(c->ev_resolved, s)); c->resolved_once = true; }
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, c->tile_miss, c->tile_cnt, c->age_hist,
                      c->tile_reuse,
                      c->hist, x->t, c->cfg.lookahead, (int)c->C, c->hi, x->ctr);
@@ -707,15 +720,16 @@ int sfc_prepare(sfc_cache* c, const int64_t* d_ids, int64_t n_ids, const int64_t
   hipLaunchKernelGGL(k_victim_count, dim3(gs), dim3(256), 0, s, c->stamp, c->tile_lt, c->tile_eq,
                      x->ctr);
   hipLaunchKernelGGL(k_victim_write, dim3(gs), dim3(256), 0, s, c->stamp, c->slot_id, c->tile_lt,
-                     c->tile_eq, x->victim_slot, x->victim_id, x->ctr);
+                     c->tile_eq, x->victim_slot, x->victim_id, x->ctr, c->dmap);
   const int gv = grid_for(n, kVidTile, kGridCap);
-  hipLaunchKernelGGL(k_victim_unmap, dim3(gv), dim3(256), 0, s, x->victim_id, c->index, c->hi,
-                     x->ctr);
+  if (!c->dmap)
+    hipLaunchKernelGGL(k_victim_unmap, dim3(gv), dim3(256), 0, s, x->victim_id, c->index, c->hi,
+                       x->ctr);
   hipLaunchKernelGGL(k_assign_misses, dim3(gv), dim3(256), 0, s, d_unique_ids, cnt, cnt_rep,
                      c->cur_rep, c->tile_cnt,
                      c->grp, x->cold_pay, c->tile_miss, x->victim_slot, d_slot, d_miss_vids, x->miss_row,
                      x->miss_id, x->boff, c->slot_id,
-                     c->stamp, c->index, c->hi, x->t, (int)c->C, c->tile_reuse, x->ctr);
+                     c->stamp, c->index, c->hi, c->dmap, x->t, (int)c->C, c->tile_reuse, x->ctr);
   if (n > 0)
     hipLaunchKernelGGL(k_scatter, dim3((n + kSortChunk - 1) / kSortChunk), dim3(256), 0, s, d_inverse,
                        d_offsets ? c->pos2bag : (const int*)nullptr, n, c->grp, (int*)x->cold_pay, c->cur_rep,
@@ -1009,9 +1023,13 @@ int sfc_verify(sfc_cache* c, int64_t* h_bad) {
   fill<unsigned long long>(s, d_bad, 4, 0ull);
   Ctr* ctr = c->ctx[c->last_prepared].ctr;
   hipLaunchKernelGGL(k_verify_slots, dim3(grid_for(c->C, 256, kGridCap)), dim3(256), 0, s,
-                     c->slot_id, c->stamp, c->index, c->hi, recount, c->hist_len, d_bad, ctr);
-  hipLaunchKernelGGL(k_verify_entries, dim3(grid_for((int64_t)c->hi, 256, kGridCap)), dim3(256), 0, s,
-                     c->index, c->hi, c->slot_id, (int)c->C, d_bad);
+                     c->slot_id, c->stamp, c->index, c->hi, c->dmap, recount, c->hist_len, d_bad, ctr);
+  if (c->dmap)
+    hipLaunchKernelGGL(k_verify_dense, dim3(grid_for(c->V, 256, kGridCap)), dim3(256), 0, s,
+                       c->dmap, c->V, c->slot_id, (int)c->C, d_bad);
+  else
+    hipLaunchKernelGGL(k_verify_entries, dim3(grid_for((int64_t)c->hi, 256, kGridCap)), dim3(256), 0, s,
+                       c->index, c->hi, c->slot_id, (int)c->C, d_bad);
   hipLaunchKernelGGL(k_verify_hist, dim3(grid_for((int64_t)c->hist_len, 256, kGridCap)), dim3(256), 0, s,
                      c->hist, recount, c->hist_len, d_bad);
   unsigned long long hb[4] = {0, 0, 0, 0};

@@ -61,6 +61,7 @@ struct Ctr {
   int err;        // nonzero: a probe loop ran off its bound
   int fetch_on_main;  // pipelined mode: this step's Host copies ran behind the older steps' updates
   int U_prev;     // unique ids of the previous step (its per-tile tallies are still to be read)
+  int dense;      // the id -> slot index is a dense map (no hashed entries, no tombstones, no rebuild)
   int t;          // number of the step these counters belong to
   int bad_offsets;    // violations found in the step's bag offsets (multi-hot input)
   HostStatus* hstat;  // device view of the cache's status block

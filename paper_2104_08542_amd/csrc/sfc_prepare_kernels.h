@@ -234,21 +234,24 @@ __global__ __launch_bounds__(256) void k_uniq_count(const int* __restrict__ hslo
 // last index update of one step and the resolve of the next.  They read the flag and the
 // watermark from the previous step's counters, which no kernel changes any more (on the very
 // first step prev == cur and both fields are zero before and after).
+__device__ __forceinline__ void ctr_start(Ctr* cur, const Ctr* prev, const int* n_unique,
+                                          int* n_invalid, int t) {
+  Ctr c = *prev;
+  c.U_prev = c.U;
+  c.U = *n_unique;
+  c.M = c.K = c.n_bypass = c.n_hit = 0;
+  c.n_invalid = *n_invalid;
+  *n_invalid = 0;
+  c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
+  c.t = t; c.bad_offsets = 0;
+  *cur = c;
+}
+
 __global__ __launch_bounds__(256) void k_ctr_init(Ctr* cur, const Ctr* prev, const int* n_unique,
                                                   int* n_invalid, IdxEntry* index, uint32_t hi,
                                                   int t) {
   const bool rebuild = prev->rebuild != 0;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    Ctr c = *prev;
-    c.U_prev = c.U;
-    c.U = *n_unique;
-    c.M = c.K = c.n_bypass = c.n_hit = 0;
-    c.n_invalid = *n_invalid;
-    *n_invalid = 0;
-    c.f_old = c.f; c.need = 0; c.T = 0; c.r = 0; c.fetch_on_main = 0;
-    c.t = t; c.bad_offsets = 0;
-    *cur = c;
-  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) ctr_start(cur, prev, n_unique, n_invalid, t);
   if (!rebuild) return;
   IdxEntry e; e.key = kEmpty; e.slot = -1; e.pad = 0;
   for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < hi; i += gridDim.x * 256) index[i] = e;
@@ -455,7 +458,14 @@ __global__ __launch_bounds__(256) void k_scatter(const int* __restrict__ inverse
 }
 
 // ---------------------------------------------------------------------------------------------
-// Cache index helpers (open addressing, linear probing, tombstones).
+// The cache index (id -> slot) comes in two kinds.
+//   dense: one int per Host row, dmap[id] = slot or -1.  With 288 GB of HBM a map of 4 bytes per
+//     Host row (1.6 % of a dim-32 table with its accumulators) is affordable for every table that
+//     fits a host, and it needs no probing, no atomics (the ids of a batch are distinct: one writer
+//     per word), no tombstones and no rebuild.  The kernels below take it as `dmap`.
+//   hashed (dmap == nullptr): open addressing, linear probing, tombstones, rebuilt on the device when
+//     deleted entries pass an eighth of the table: for id ranges too large for a dense map, or on
+//     request (sfc_config.index_kind).  The helpers that follow are its probe / insert.
 // ---------------------------------------------------------------------------------------------
 // A probe sequence is walked eight entries (128 bytes) at a time, all eight loads in flight
 // together: the longest cluster among the tens of thousands of probes of a step sets the duration
@@ -542,18 +552,27 @@ constexpr int kResolveGrid = 256;
 __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ unique_ids,
                                                   const int* __restrict__ vid_hslot, UEntry* utab,
                                                   const IdxEntry* __restrict__ index, uint32_t hi,
+                                                  const int* __restrict__ dmap,
                                                   int* stamp, int* hist, int t,
                                                   int* __restrict__ slot_out,
                                                   int* __restrict__ tile_miss,
                                                   int* __restrict__ cnt,
                                                   const int* __restrict__ cnt_rep,
                                                   int* __restrict__ tile_cnt,
-                                                  int* __restrict__ age_hist, Ctr* ctr) {
+                                                  int* __restrict__ age_hist, Ctr* ctr,
+                                                  const Ctr* prev, const int* n_unique,
+                                                  int* n_invalid) {
   __shared__ int smem[20];
   __shared__ int lage[kAgeBins];
   for (int i = threadIdx.x; i < kAgeBins; i += 256) lage[i] = 0;
+  // Dense index (prev != nullptr): nothing has to happen between the previous step's prepare and
+  // this kernel, so it starts the step's counters itself (k_ctr_init is not launched): the first
+  // thread writes them for the kernels that follow, and every block takes the number of unique ids
+  // from where the unique passes left it.  Nothing else of the counters is read in this kernel,
+  // and the dense index has no probe that could flag an error into them meanwhile.
+  const int U = prev ? *n_unique : ctr->U;
   __syncthreads();
-  const int U = ctr->U;
+  if (prev && blockIdx.x == 0 && threadIdx.x == 0) ctr_start(ctr, prev, n_unique, n_invalid, t);
   // four tiles per iteration, so that each level of the chain vid -> id -> index entry -> stamp
   // has four loads in flight per thread
   for (int tile0 = blockIdx.x * 4; tile0 * kVidTile < U; tile0 += gridDim.x * 4) {
@@ -581,17 +600,25 @@ __global__ __launch_bounds__(256) void k_resolve(const int64_t* __restrict__ uni
     for (int k = 0; k < 4; ++k) {
       if (hs[k] >= 0) { UEntry z; z.key = kEmpty; z.minpos = kIntMax; z.pad = 0; utab[hs[k]] = z; }
       if (id[k] >= 0) {
-        hb[k] = bucket_of(id[k], hi);
-        ent[k] = *reinterpret_cast<const int4*>(&index[hb[k]]);
+        if (dmap) {
+          ent[k].z = dmap[id[k]];
+        } else {
+          hb[k] = bucket_of(id[k], hi);
+          ent[k] = *reinterpret_cast<const int4*>(&index[hb[k]]);
+        }
       }
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       sl[k] = -1;
       if (id[k] >= 0) {
-        const int64_t k0 = ((int64_t)(uint32_t)ent[k].y << 32) | (uint32_t)ent[k].x;
-        if (k0 == id[k]) sl[k] = ent[k].z;
-        else if (k0 != kEmpty) sl[k] = index_find(index, hi, id[k], nullptr, ctr);   // walk on
+        if (dmap) {
+          sl[k] = ent[k].z;
+        } else {
+          const int64_t k0 = ((int64_t)(uint32_t)ent[k].y << 32) | (uint32_t)ent[k].x;
+          if (k0 == id[k]) sl[k] = ent[k].z;
+          else if (k0 != kEmpty) sl[k] = index_find(index, hi, id[k], nullptr, ctr);   // walk on
+        }
       }
     }
 #pragma unroll
@@ -725,7 +752,7 @@ __global__ __launch_bounds__(1024) void k_plan(int* tile_miss, int* tile_cnt,
     if (ctr->rebuild) { ctr->rebuild = 0; ctr->tomb = 0; }
     // K deletions are about to add tombstones; ask for a rebuild before the next resolve when a
     // eighth of the index would be deleted entries
-    if ((unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
+    if (!ctr->dense && (unsigned)(ctr->tomb + K) > hi / 8) ctr->rebuild = 1;
   }
 }
 
@@ -765,7 +792,8 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
                                                        const int* __restrict__ tile_lt,
                                                        const int* __restrict__ tile_eq,
                                                        int* __restrict__ victim_slot,
-                                                       int64_t* __restrict__ victim_id, Ctr* ctr) {
+                                                       int64_t* __restrict__ victim_id, Ctr* ctr,
+                                                       int* __restrict__ dmap) {
   __shared__ int smem[20];
   if (ctr->K == 0) return;
   const int f = ctr->f_old, T = ctr->T, r = ctr->r, K = ctr->K;
@@ -822,9 +850,13 @@ __global__ __launch_bounds__(256) void k_victim_write(const int* __restrict__ st
     for (int j = 0; j < 8; ++j) if (idx[j] >= 0) vid8[j] = slot_id[base + j];
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      if (idx[j] >= 0) { victim_slot[idx[j]] = base + j; victim_id[idx[j]] = vid8[j]; }
+      if (idx[j] >= 0) {
+        victim_slot[idx[j]] = base + j; victim_id[idx[j]] = vid8[j];
+        if (dmap) dmap[vid8[j]] = -1;          // dense index: the victim leaves it here, one store
+      }
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);   // deleted by the next pass
+  // hashed index: the victims are deleted by the next pass (k_victim_unmap)
+  if (!dmap && blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&ctr->tomb, ctr->K);
 }
 
 // The victims leave the index: one thread per victim.  A kernel of its own, before the inserts:
@@ -863,7 +895,8 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
                                                         int* __restrict__ miss_row,
                                                         int64_t* __restrict__ miss_id, int boff,
                                                         int64_t* __restrict__ slot_id, int* stamp,
-                                                        IdxEntry* index, uint32_t hi, int t, int C,
+                                                        IdxEntry* index, uint32_t hi,
+                                                        int* __restrict__ dmap, int t, int C,
                                                         int* __restrict__ tile_reuse, Ctr* ctr) {
   __shared__ int smem[20];
   const int U = ctr->U, K = ctr->K, f = ctr->f_old;
@@ -919,7 +952,8 @@ __global__ __launch_bounds__(256) void k_assign_misses(const int64_t* __restrict
       if (s < C) {
         slot_id[s] = id;
         stamp[s] = t;
-        reused = index_insert(index, hi, id, s, ctr);
+        if (dmap) dmap[id] = s;
+        else reused = index_insert(index, hi, id, s, ctr);
       }
     }
     // deleted entries taken back into use: tallied per tile for the next plan pass (thousands of
@@ -944,7 +978,8 @@ __device__ __forceinline__ void tally(unsigned long long* word, int mine) {
 __global__ __launch_bounds__(256) void k_verify_slots(const int64_t* __restrict__ slot_id,
                                                        const int* __restrict__ stamp,
                                                        const IdxEntry* __restrict__ index,
-                                                       uint32_t hi, int* recount, int hist_len,
+                                                       uint32_t hi, const int* __restrict__ dmap,
+                                                       int* recount, int hist_len,
                                                        unsigned long long* bad, Ctr* ctr) {
   const int f = ctr->f;
   const int rounds = (f + (int)gridDim.x * 256 - 1) / ((int)gridDim.x * 256);
@@ -953,7 +988,7 @@ __global__ __launch_bounds__(256) void k_verify_slots(const int64_t* __restrict_
     int lost = 0, off = 0;
     if (s < f) {
       const int64_t id = slot_id[s];
-      if (id < 0 || index_find(index, hi, id, nullptr, ctr) != s) lost = 1;
+      if (id < 0 || (dmap ? dmap[id] : index_find(index, hi, id, nullptr, ctr)) != s) lost = 1;
       const int st = stamp[s];
       if (st >= 0 && st < hist_len) atomicAdd(&recount[st], 1); else off = 1;
     }
@@ -977,6 +1012,27 @@ __global__ __launch_bounds__(256) void k_verify_entries(const IdxEntry* __restri
       if (key >= 0) {
         ++live;
         if (raw.z < 0 || raw.z >= C || slot_id[raw.z] != key) ++stray;
+      }
+    }
+  }
+  tally(&bad[3], live);
+  tally(&bad[1], stray);
+}
+
+// the same for the dense index: every entry >= 0 is live and must point at a slot holding its id
+__global__ __launch_bounds__(256) void k_verify_dense(const int* __restrict__ dmap, int64_t V,
+                                                       const int64_t* __restrict__ slot_id, int C,
+                                                       unsigned long long* bad) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const int64_t rounds = (V + stride - 1) / stride;
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int live = 0, stray = 0;
+  for (int64_t it = 0; it < rounds; ++it, i += stride) {
+    if (i < V) {
+      const int s = dmap[i];
+      if (s >= 0) {
+        ++live;
+        if (s >= C || slot_id[s] != i) ++stray;
       }
     }
   }

@@ -34,7 +34,7 @@ class Pair:
 
     def __init__(self, V, D, C, max_ids, max_bags=None, lookahead=0, seed=5, lr=0.01, eps=1e-8,
                  init_acc=0.1, max_steps=0, side_stream=True, interleaved=True, device="cuda:0",
-                 optimizer="adagrad", betas=(0.9, 0.999), strategy="cache"):
+                 optimizer="adagrad", betas=(0.9, 0.999), strategy="cache", index_kind=0):
         import paper_2104_08542_amd as sfc
         self.sfc = sfc
         self.V, self.D, self.C = V, D, C
@@ -51,7 +51,8 @@ class Pair:
         self.ow, self.oa = self.table.w.copy(), self.table.acc[:, :self.ns].copy()
         self.cache = sfc.Cache(self.table, C, max_ids, max_bags, lr=lr, eps=eps, lookahead=lookahead,
                                max_steps=max_steps, device=device, side_stream=side_stream, betas=betas,
-                               policy=sfc.SFC_POLICY_PREFETCH if strategy == "prefetch" else None)
+                               policy=sfc.SFC_POLICY_PREFETCH if strategy == "prefetch" else None,
+                               index_kind=index_kind)
         self.orc = Oracle(C, D, self.ow, self.oa, lr=lr, eps=eps, lookahead=lookahead,
                           optimizer=optimizer, betas=betas, strategy=strategy)
 

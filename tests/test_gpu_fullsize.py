@@ -110,11 +110,12 @@ def test_low_locality_configuration_shape():
     p.close()
 
 
-@pytest.mark.parametrize("lookahead", [0, 2])
-def test_long_run_keeps_every_resident_id_findable(lookahead):
-    """640 steps at the target batch size against a 2e6-row cache (about 1e5 victims per step, an
-    index rebuild every few dozen steps), no oracle beside it: the device-side consistency checks
-    must stay silent, and afterwards a batch made of resident ids must resolve to hits only."""
+@pytest.mark.parametrize("lookahead,index_kind", [(0, 1), (2, 1), (2, 2)])
+def test_long_run_keeps_every_resident_id_findable(lookahead, index_kind):
+    """640 steps at the target batch size against a 2e6-row cache (about 1e5 victims per step; with
+    the hashed index (index_kind 1) an index rebuild every few dozen steps), no oracle beside it:
+    the device-side consistency checks must stay silent, the recount of the manager state must
+    agree, and afterwards a batch made of resident ids must resolve to hits only."""
     import torch
     import paper_2104_08542_amd as sfc
     w = si.WORKLOADS["c2"]
@@ -124,7 +125,8 @@ def test_long_run_keeps_every_resident_id_findable(lookahead):
     dev = torch.device("cuda:0")
     table = sfc.HostTable(w.vocab, w.dim)
     table.acc[:] = 0.1
-    cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lookahead=lookahead, max_steps=2000)
+    cache = sfc.Cache(table, C, w.max_ids, w.n_bags, lookahead=lookahead, max_steps=2000,
+                      index_kind=index_kind)
     out = torch.empty(w.n_bags, w.dim, device=dev)
     g = w.batch_grads(0, dev)
     t0 = time.time()
@@ -143,6 +145,8 @@ def test_long_run_keeps_every_resident_id_findable(lookahead):
     for _ in range(lookahead):
         cache.lookup(out); cache.backward_update(g)
     _say("640 steps at lookahead %d in %.0fs" % (lookahead, time.time() - t0))
+    cache.check()
+    assert cache.verify() == [0, 0, 0, 0]
     sid, _ = cache.state()
     res = sid[sid >= 0]
     assert res.size == C and np.unique(res).size == C

@@ -8,6 +8,8 @@ from gpu_common import Pair
 
 pytestmark = pytest.mark.gpu
 
+HASHED, DENSE = 1, 2        # sfc_config.index_kind (0 = automatic: dense for every table of these tests)
+
 
 def _zipf_steps(p, V, n, s, seed, steps, **kw):
     for t in range(steps):
@@ -31,9 +33,10 @@ def test_paper_examples_on_gpu():
     p.finish(); p.close()
 
 
-def test_tiny_config_bypass_every_step():
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
+def test_tiny_config_bypass_every_step(index_kind):
     w = si.WORKLOADS["tiny"]                  # U ~ 10.7k > C = 10k: bypass rows on every step
-    p = Pair(w.vocab, w.dim, w.cache_rows, w.max_ids, seed=w.seed)
+    p = Pair(w.vocab, w.dim, w.cache_rows, w.max_ids, seed=w.seed, index_kind=index_kind)
     saw_bypass = saw_evict = False
     for t in range(6):
         ids, _ = w.batch_ids(t)
@@ -44,10 +47,11 @@ def test_tiny_config_bypass_every_step():
     p.finish(); p.close()
 
 
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
 @pytest.mark.parametrize("lookahead", [0, 1])
-def test_eviction_heavy_small_cache(lookahead):
+def test_eviction_heavy_small_cache(lookahead, index_kind):
     V, D, n = 5000, 8, 3000                    # several scan tiles, ragged tails (3000 % 256, % 2048)
-    p = Pair(V, D, C=1500, max_ids=4096, lookahead=lookahead)
+    p = Pair(V, D, C=1500, max_ids=4096, lookahead=lookahead, index_kind=index_kind)
     _zipf_steps(p, V, n, 1.05, 21, 10)
     p.finish(); p.close()
 
@@ -63,9 +67,10 @@ def test_ties_in_stamp_break_by_slot():
     p.finish(); p.close()
 
 
-def test_multihot_bags():
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
+def test_multihot_bags(index_kind):
     V, D, nb = 20000, 16, 1500
-    p = Pair(V, D, C=4000, max_ids=nb * 20, max_bags=nb)
+    p = Pair(V, D, C=4000, max_ids=nb * 20, max_bags=nb, index_kind=index_kind)
     for t in range(6):
         off = si.bag_offsets(nb, 1, 20, 31, t).numpy()
         ids = si.zipf_ids(int(off[-1]), 1.1, V, 31, t).numpy()
@@ -88,8 +93,9 @@ def test_capacity_zero_is_the_host_strategy():
     p.finish(); p.close()
 
 
-def test_degenerate_batches():
-    p = Pair(V=100, D=4, C=16, max_ids=512)
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
+def test_degenerate_batches(index_kind):
+    p = Pair(V=100, D=4, C=16, max_ids=512, index_kind=index_kind)
     g = lambda n, t: si.grads(n, 4, 77, t).numpy()
     p.step(np.zeros(0, np.int64), np.zeros((0, 4), np.float32))     # empty batch
     p.step(np.full(300, 42), g(300, 1))                              # one id, many times
@@ -100,11 +106,12 @@ def test_degenerate_batches():
     p.finish(); p.close()
 
 
-def test_medium_zipf_many_tiles():
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
+def test_medium_zipf_many_tiles(index_kind):
     # 16384 x 39 positions like the second configuration, vocabulary shrunk so that the oracle
     # and its table stay small; cache small enough to evict from the third step on
     V, D, n = 10 ** 6, 16, 16384 * 39
-    p = Pair(V, D, C=200_000, max_ids=n)
+    p = Pair(V, D, C=200_000, max_ids=n, index_kind=index_kind)
     for t in range(5):
         ids = si.zipf_ids(n, 1.1, V, 1001, t).numpy()
         p.step(ids, si.grads(n, D, 1001, t).numpy(), check_state=(t in (0, 4)))
@@ -183,7 +190,7 @@ def test_index_rebuild_after_many_evictions():
     # tiny cache, every step evicts almost everything: deleted index entries pile up and the
     # rebuild path runs many times; state must stay identical to the oracle throughout
     V, D = 100_000, 4
-    p = Pair(V, D, C=64, max_ids=64)
+    p = Pair(V, D, C=64, max_ids=64, index_kind=HASHED)
     for t in range(60):
         ids = si.uniform_ids(64, V, 3, t).numpy()
         p.step(ids, si.grads(64, D, 3, t).numpy(), check_common=False)
@@ -227,13 +234,14 @@ def _batches(V, D, n, s, seed, steps):
             for t in range(steps)]
 
 
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
 @pytest.mark.parametrize("lookahead", [1, 2, 3])
 @pytest.mark.parametrize("sync_every_call", [True, False])
-def test_pipelined_steps_match_sequential_oracle(sync_every_call, lookahead):
+def test_pipelined_steps_match_sequential_oracle(sync_every_call, lookahead, index_kind):
     # prepare / fetch of later steps overlap lookup / update of the current one; the cache is
     # small enough to evict on every step and large enough never to bypass
     V, D, n = 20000, 32, 6000
-    p = Pair(V, D, C=12000, max_ids=8192, lookahead=lookahead)
+    p = Pair(V, D, C=12000, max_ids=8192, lookahead=lookahead, index_kind=index_kind)
     p.run_pipelined(_batches(V, D, n, 1.05, 77, 12), sync_every_call)
     p.close()
 
@@ -294,12 +302,14 @@ def test_pipelined_multihot(lookahead):
     p.close()
 
 
+@pytest.mark.parametrize("index_kind", [HASHED, DENSE])
 @pytest.mark.parametrize("lookahead", [0, 2, 3])
-def test_many_rebuilds_with_many_victims(lookahead):
-    # a cache much smaller than the id range with thousands of victims per step: the index fills
-    # with deleted entries and is rebuilt every few steps, also while other steps are in flight
+def test_many_rebuilds_with_many_victims(lookahead, index_kind):
+    # a cache much smaller than the id range with thousands of victims per step: the hashed index
+    # fills with deleted entries and is rebuilt every few steps, also while other steps are in
+    # flight; the dense one just follows
     V, D, n, C = 400_000, 4, 30_000, 40_000
-    p = Pair(V, D, C=C, max_ids=n, lookahead=lookahead)
+    p = Pair(V, D, C=C, max_ids=n, lookahead=lookahead, index_kind=index_kind)
     bs = [(si.zipf_ids(n, 1.05, V, 77, t).numpy(), si.grads(n, D, 77, t).numpy(), None) for t in range(60)]
     if lookahead:
         expect = p.run_pipelined(bs, False)
