@@ -243,7 +243,8 @@ def main():
     RS = R + 4 * S                                                    # a row and its optimizer state
     b_update = bags * R + 4 * N + 4 * U + 2 * U * RS + extra         # sfc_backward_update as a whole
     kernels = {
-        ("k_lookup_onehot" if w.one_hot else "k_lookup_bags"): (b_lookup, ms["lookup"]),
+        # the lookup call is two kernels: the batch's rows are warmed into the memory-side cache, then gathered
+        ("k_warm_rows+k_lookup_onehot" if w.one_hot else "k_warm_rows+k_lookup_bags"): (b_lookup, ms["lookup"]),
         "k_seg_stream": (bags * R + 4 * N + U * R + extra, ms["k_seg_stream"]),   # grad + grouping in, common out
         "k_%s_rows" % args.optimizer: (4 * U + U * R + 2 * U * RS, ms["k_adagrad_rows"]),
     }
@@ -312,8 +313,8 @@ def main():
         "lookup_plus_update": {"algorithmic_bytes": pair_bytes, "avg_ms": pair_ms,
                                "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
                                "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                               "what": "the lookup kernel's duration + the backward_update call between "
-                                       "two events on its stream (three kernels and their launch gaps)",
+                               "what": "the durations of the lookup call's two kernels + the backward_update call "
+                                       "between two events on its stream (three kernels and their launch gaps)",
                                "kernel_ms_sum": pair_kernel_ms,
                                "frac_of_hbm_peak_kernel_time": (pair_bytes / (pair_kernel_ms * 1e-3) / 1e9
                                                                 / HBM_PEAK_GBS) if pair_kernel_ms else None},
@@ -331,12 +332,54 @@ def main():
                                                 / 1e9 / (link_ms * 1e-3) if link_ms else None)},
     }
 
+    if args.lookahead and args.strategy == "cache":
+        # The same pair with the calls of a step in order and nothing else in flight: a second cache
+        # with lookahead 0 on the same Host table and batch sequence, filled the same way.  In the
+        # pipelined configuration above, lookup and update of step t run two steps after its prepare
+        # and copies, when everything those wrote has left the caches; here they follow at once.
+        for _ in range(args.lookahead):       # retire the steps that are still in flight
+            cache.lookup(out)
+            cache.backward_update(grads[0])
+        cache.flush()
+        cache.close()
+        c0 = sfc.Cache(table, C, w.max_ids, w.n_bags, lr=w.lr, eps=w.eps, lookahead=0, device="cuda:0")
+        seq = [0]
+
+        def step0(k):
+            b = w.batch_ids(seq[0], dev); seq[0] += 1
+            c0.prepare(b[0], b[1]); c0.fetch_misses(); c0.lookup(out); c0.backward_update(grads[k % 4])
+
+        for k in range(fill_steps + W):
+            step0(k)
+        torch.cuda.synchronize()
+        sfc.sfc_profile_enable(c0.h, 2)
+        for k in range(K):
+            step0(k)
+        q = sfc.sfc_profile_read(c0.h)
+        sfc.sfc_profile_enable(c0.h, 0)
+        c0.check()
+        m0 = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in q.items()}
+        calls0 = m0["lookup"] + m0["backward_update"]
+        kern0 = m0["lookup"] + m0["k_seg_stream"] + m0["k_seg_finish"] + m0["k_adagrad_rows"]
+        result["lookup_plus_update_calls_in_order"] = {
+            "what": "lookahead 0: prepare, copies, lookup, update of one step in order on one cache, "
+                    "nothing overlapped; the pipelined default above measures the same kernels two steps "
+                    "after their inputs were written",
+            "algorithmic_bytes": pair_bytes, "avg_ms": calls0,
+            "frac_of_hbm_peak": pair_bytes / (calls0 * 1e-3) / 1e9 / HBM_PEAK_GBS if calls0 else None,
+            "kernel_ms_sum": kern0,
+            "frac_of_hbm_peak_kernel_time": pair_bytes / (kern0 * 1e-3) / 1e9 / HBM_PEAK_GBS if kern0 else None,
+            "call_ms": {k: m0[k] for k in ("prepare", "fetch_misses", "lookup", "backward_update")},
+            "kernel_ms": {k: m0[k] for k in ("k_seg_stream", "k_seg_finish", "k_adagrad_rows")},
+        }
+        cache = c0
+
     if not args.no_cpu_baseline:
         # The oracle as it stands, single-threaded, on the same workload: first steps of the same
         # seeded batch sequence from a cold oracle cache, on a dense copy of the host table taken
         # after the GPU run has been flushed into it (values differ from step 0, the work does not).
         from oracle import Oracle, state_floats as oracle_state_floats
-        for _ in range(args.lookahead):       # retire the steps that are still in flight
+        for _ in range(cache.lookahead):      # retire the steps that are still in flight
             cache.lookup(out)
             cache.backward_update(grads[0])
         cache.flush()

@@ -290,9 +290,10 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
  * (several kernels each) are bracketed by hipEvents on the stream they run on, so their times
  * include the launch latencies between the events (with lookahead >= 1 the prepare runs on two
  * library streams; its events sit on the one of the cache manager's kernels and include its wait
- * for the unique passes on the other).  sfc_lookup is one kernel: its start and end are recorded
- * by the dispatch itself, i.e. the time is the kernel's own duration as a profiler's kernel trace
- * shows it.  level 2: also, the same way, each of the three kernels inside sfc_backward_update.
+ * for the unique passes on the other).  sfc_lookup is two kernels (the batch's rows are read into
+ * the memory-side cache, then gathered): the start and end of each are recorded by the dispatch
+ * itself, i.e. the time is the sum of the two kernels' own durations as a profiler's kernel trace
+ * shows them.  level 2: also, the same way, each of the three kernels inside sfc_backward_update.
  * level 0: off.  sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare,
  * fetch_misses, lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel,
  * optimizer kernel), the summed milliseconds and the number of launches since the last read of

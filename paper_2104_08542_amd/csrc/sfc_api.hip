@@ -161,6 +161,7 @@ struct sfc_cache {
   int* age_hist = nullptr;                      // [kAgeBins] hits of the step by age, zero between steps
   double* bp = nullptr; int* bp_vid = nullptr;  // [2 * blocks, D] edge partial sums of k_seg_stream
   float* gsum = nullptr;                        // [max_ids, D] common gradients of the step
+  float* warm_sink = nullptr;                   // one float that k_warm_rows never writes
   HostRows host{};                              // device view of the Host table
   HostStatus* hstat = nullptr;                  // pinned status block (host view); d_hstat its device view
   HostStatus* d_hstat = nullptr;
@@ -228,11 +229,15 @@ int prof_events(sfc_cache* c, EventPair* ep) {
 // the kernel's start and end in a pair of events, so the time read back is the kernel's own
 // duration, as a profiler's kernel trace reports it, without the launch latency that a bracket
 // of hipEventRecord calls around the launch would include.
-#define LAUNCH_TIMED(c, which, timed, kernel, grid, block, s, ...)                               \
+#define LAUNCH_TIMED(c, which, timed, kernel, grid, block, s, ...) \
+  LAUNCH_TIMED_X(c, which, timed, false, kernel, grid, block, s, __VA_ARGS__)
+// extra: the kernel's time is added to the entry, but it is not a call of its own
+#define LAUNCH_TIMED_X(c, which, timed, extra_, kernel, grid, block, s, ...)                     \
   do {                                                                                           \
     if ((timed) && prof_on(c, which)) {                                                          \
       EventPair ep_{};                                                                           \
       if (int rc_ = prof_events(c, &ep_)) return rc_;                                            \
+      ep_.extra = (extra_);                                                                      \
       hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ep_.a, ep_.b, 0, __VA_ARGS__);            \
       c->pending[which].push_back(ep_);                                                          \
     } else {                                                                                     \
@@ -570,6 +575,7 @@ int sfc_cache_create(const sfc_config* cfg, sfc_cache** out) {
       if ((rc = dalloc(c, &c->bp_vid, 2 * nwmax))) goto bad;
     }
     if ((rc = dalloc(c, &c->gsum, c->max_ids * c->D))) goto bad;
+    if ((rc = dalloc(c, &c->warm_sink, 1))) goto bad;
     for (int k = 0; k < c->nctx; ++k) {
       StepCtx* x = &c->ctx[k];
       if ((rc = dalloc(c, &x->ctr, 1))) goto bad;
@@ -782,6 +788,10 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
   hipStream_t s = c->st;
   const int64_t total = x->n_bags * c->d4;
   if (total > 0) {
+    // the rows of the batch into the memory-side cache first (returns at once when they are too many)
+    LAUNCH_TIMED_X(c, P_LOOKUP, true, true, k_warm_rows, dim3(grid_for(x->n_ids * c->d4, 2048, kWarmGrid)),
+                   dim3(256), s, (const int*)x->d_slot, (const float4*)c->cw, c->d4, (int)c->C, x->boff,
+                   (const Ctr*)x->ctr, c->warm_sink, (const int4*)x->pos_slot, (int)(x->n_ids / 4));
     if (!x->d_offsets) {
       const int d4 = c->d4, sh = (d4 & (d4 - 1)) == 0 ? __builtin_ctz(d4) : -1;
       LAUNCH_TIMED(c, P_LOOKUP, true, k_lookup_onehot,
