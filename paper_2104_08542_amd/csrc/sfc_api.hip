@@ -338,17 +338,24 @@ int rows_ready(sfc_cache* c, StepCtx* x) {
 
 // common[v] = segment sum of d_grad over the step's grouping: the stream, then the block-edge partials.
 // bp / bp_vid: the block-edge partial sums and their virtual ids, 2 per block of the stream; timed:
-// bracket the two kernels with profiling events (which may have to be created).
+// bracket the kernels with profiling events (which may have to be created).
+// fused (sfc_backward_update with the Adagrad kernel): the stream passes over the cold groups and
+// marks the groups it leaves as block-edge partials, and no finish kernel runs: the optimizer
+// kernel chains the *n_slots partials itself.
 int seg_launch(sfc_cache* c, StepCtx* x, const float* d_grad, float* d_common, double* bp,
-               int* bp_vid, bool timed, bool skip_cold) {
+               int* bp_vid, bool timed, bool fused, int* n_slots) {
   const int n = (int)x->n_ids;
+  if (n_slots) *n_slots = 0;
   if (n <= 0) return SFC_OK;
   const SegGeom g = seg_geom(c->D, n);
   const int nblk = (g.waves + 3) / 4;
-  auto kern = x->d_offsets ? (skip_cold ? k_seg_stream<false, true> : k_seg_stream<false, false>)
-                           : (skip_cold ? k_seg_stream<true, true> : k_seg_stream<true, false>);
+  auto kern = x->d_offsets ? (fused ? k_seg_stream<false, true> : k_seg_stream<false, false>)
+                           : (fused ? k_seg_stream<true, true> : k_seg_stream<true, false>);
   LAUNCH_TIMED(c, P_SEG_STREAM, timed, kern, dim3(nblk), dim3(256), c->st, (const float4*)d_grad,
-               (const int64_t*)x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid);
+               (const int64_t*)x->perm64, n, c->d4, g.G, g.L, (float4*)d_common, bp, bp_vid,
+               fused ? (int*)x->cold_pay : (int*)nullptr);
+  if (n_slots) *n_slots = 2 * nblk;
+  if (fused) return SFC_OK;
   LAUNCH_TIMED(c, P_SEG_FINISH, timed, k_seg_finish, dim3((unsigned)(2 * nblk)), dim3(256), c->st,
                (const double*)bp, (const int*)bp_vid, 2 * nblk, c->d4, (float4*)d_common);
   return SFC_OK;
@@ -819,7 +826,7 @@ int sfc_segment_sum(sfc_cache* c, const float* d_grad, float* d_common_grad) {
   if (((uintptr_t)d_grad | (uintptr_t)d_common_grad) & 15) return fail(SFC_EINVAL, "buffers must be 16-byte aligned");
   int rc;
   if ((rc = rows_ready(c, x))) return rc;
-  if ((rc = seg_launch(c, x, d_grad, d_common_grad, c->bp, c->bp_vid, true, false))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad, c->bp, c->bp_vid, true, false, nullptr))) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -856,7 +863,7 @@ int sfc_segment_sum_static(sfc_cache* c, const float* d_grad, float* d_common_gr
   // every slot that k_seg_finish reads is written by k_seg_stream in the same call: nothing to clear
   double* bp = (double*)base;
   int* bp_vid = (int*)((unsigned char*)base + sums);
-  if ((rc = seg_launch(c, x, d_grad, d_common_grad, bp, bp_vid, false, false))) return rc;
+  if ((rc = seg_launch(c, x, d_grad, d_common_grad, bp, bp_vid, false, false, nullptr))) return rc;
   HIPCHK(hipGetLastError());
   return SFC_OK;
 }
@@ -873,7 +880,8 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   hipStream_t s = c->st;
   EventPair ep{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
-  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true, c->cfg.optimizer == SFC_OPT_ADAGRAD))) return rc;
+  int n_slots = 0;
+  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true, c->cfg.optimizer == SFC_OPT_ADAGRAD, &n_slots))) return rc;
   if (c->cfg.policy == SFC_POLICY_PREFETCH) {
     // the copies of a newer step issued so far read the Host table before this update writes it
     for (int k = 0; k < c->nctx; ++k) {
@@ -884,12 +892,14 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   }
   const dim3 ug(grid_for(x->n_ids * c->d4, 1024, kGridCap));
   if (c->cfg.optimizer == SFC_OPT_ADAGRAD) {
-    // the stream above passed over the cold groups: this kernel sums them itself
+    // the stream above passed over the cold groups and left the block-edge partials unchained:
+    // this kernel sums both itself (its first n_slots blocks chain the partials)
     auto kern = x->d_offsets ? k_adagrad_rows<false> : k_adagrad_rows<true>;
-    LAUNCH_TIMED(c, P_ADAGRAD, true, kern, ug, dim3(256), s, (const float4*)c->gsum,
+    LAUNCH_TIMED(c, P_ADAGRAD, true, kern, dim3(ug.x + (unsigned)n_slots), dim3(256), s, (const float4*)c->gsum,
                  (const int*)x->d_slot, (const int64_t*)x->d_unique, (float4*)c->cw, (float4*)c->ca,
                  c->host, (int)c->C, x->boff, c->cfg.lr, c->cfg.eps, c->d4, (const Ctr*)x->ctr,
-                 (const int2*)x->cold_pay, (const float4*)d_grad);
+                 (const int2*)x->cold_pay, (const float4*)d_grad, (const double*)c->bp,
+                 (const int*)c->bp_vid, n_slots);
   } else if (c->cfg.optimizer == SFC_OPT_ADAM) {
     // every constant derived from the decay rates is computed in double and rounded to fp32 once
     AdamArgs k;

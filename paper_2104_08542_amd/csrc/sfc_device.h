@@ -23,6 +23,10 @@ constexpr int kIntMax = 0x7fffffff;
 constexpr int kHotBins = 8192;      // lowest virtual ids: counted and grouped through LDS histograms
 constexpr int kColdMax = 2;
 constexpr int64_t kColdBit = (int64_t)1 << 62;
+// cold_pay[v] holds the (at most two) gradient rows of a cold group, (-1, -1) for any other group.
+// A third value of its first word marks a group that the segment-sum stream left as block-edge
+// partials: the optimizer kernel chains those itself and updates the row there.
+constexpr int kEdgeMark = -2;
 __device__ __forceinline__ int entry_vid(int64_t e) { return (int)(e >> 32) & 0x3fffffff; }
 __device__ __forceinline__ bool entry_cold(int64_t e) { return (e & kColdBit) != 0; }
 // per virtual id: (positions << 32) | start of its group in perm64

@@ -399,7 +399,8 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
                                                      int d4, int G, int L,
                                                      float4* __restrict__ common,
                                                      double* __restrict__ bp,
-                                                     int* __restrict__ bp_vid) {
+                                                     int* __restrict__ bp_vid,
+                                                     int* __restrict__ edge_mark) {
   // per wavefront: [2G slots][D] doubles (2*G*D <= 512) and the slots' vids
   __shared__ double part[4][512];
   __shared__ int pvid[4][128];
@@ -521,7 +522,15 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
     o0[0] = b0.x; o0[1] = b0.y; o0[2] = b0.z; o0[3] = b0.w;
     double* o1 = &bp[(o + 1) * D + 4 * c4];
     o1[0] = b1.x; o1[1] = b1.y; o1[2] = b1.z; o1[3] = b1.w;
-    if (c4 == 0) { bp_vid[o] = bv0; bp_vid[o + 1] = bv1; }
+    if (c4 == 0) {
+      bp_vid[o] = bv0; bp_vid[o + 1] = bv1;
+      // a group cut by a block's edge: its sum is not in `common`, and the optimizer kernel that
+      // chains the partials itself (k_adagrad_rows) must not take it from there (see kEdgeMark)
+      if (edge_mark) {
+        if (bv0 >= 0) edge_mark[2 * bv0] = kEdgeMark;
+        if (bv1 >= 0) edge_mark[2 * bv1] = kEdgeMark;
+      }
+    }
   }
 }
 
@@ -530,17 +539,19 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
 // thread block per slot; only the first slot of a run works: it finds the run's end by binary
 // search (the predicate "same vid" is true on the run and false after it), its lane groups sum
 // the run's partials in a strided, fixed order, four loads in flight, and combine through LDS.
-__global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ bp,
-                                                     const int* __restrict__ bp_vid, int nslots,
-                                                     int d4, float4* __restrict__ common) {
+// The work of one block on slot j of the block-edge partial lists: true (for the whole block) when
+// j is the first slot of its run; then v is the run's virtual id and the threads tid < d4 hold the
+// run's fp64 sum, chunk tid of the row, in s.
+__device__ __forceinline__ bool edge_run_sum(const double* __restrict__ bp,
+                                             const int* __restrict__ bp_vid, int nslots, int d4,
+                                             int j, int& v, D4& s) {
   __shared__ double red[256 * 4];
-  const int j = (int)blockIdx.x;
-  const int v = bp_vid[j];
-  if (v < 0 || (j > 0 && bp_vid[j - 1] == v)) return;     // not the first slot of its run
+  __shared__ int s_cnt[4];
+  v = bp_vid[j];
+  if (v < 0 || (j > 0 && bp_vid[j - 1] == v)) return false;     // not the first slot of its run
   // the run's end: "same vid" is true on the run and false after it, so the block probes 256
   // places at once and narrows the bracket by that factor per round (two rounds for thousands of
   // slots, where a bisection took a dozen dependent loads)
-  __shared__ int s_cnt[4];
   const int tid = (int)threadIdx.x;
   int lo = j, hi = nslots;                                 // bp_vid[lo] == v, run ends in (lo, hi]
   while (hi - lo > 1) {
@@ -581,8 +592,18 @@ __global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ b
       const double* q = &red[(o * d4 + c4) * 4];
       s0 += q[0]; s1 += q[1]; s2 += q[2]; s3 += q[3];
     }
-    common[(int64_t)v * d4 + c4] = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
   }
+  s.x = s0; s.y = s1; s.z = s2; s.w = s3;
+  return true;
+}
+
+__global__ __launch_bounds__(256) void k_seg_finish(const double* __restrict__ bp,
+                                                     const int* __restrict__ bp_vid, int nslots,
+                                                     int d4, float4* __restrict__ common) {
+  int v;
+  D4 s;
+  if (!edge_run_sum(bp, bp_vid, nslots, d4, (int)blockIdx.x, v, s)) return;
+  if ((int)threadIdx.x < d4) common[(int64_t)v * d4 + threadIdx.x] = d4_round(s);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -630,11 +651,11 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
                                              float4* __restrict__ cw, float4* __restrict__ ca,
                                              const HostRows& h, int C, int boff, float lr, float eps,
                                              int d4, int U, const int2* __restrict__ cold_pay,
-                                             const float4* __restrict__ grad) {
+                                             const float4* __restrict__ grad, int blk, int nblk) {
   static_assert(kColdMax == 2, "the gather path below takes two gradient rows");
   const int64_t total = (int64_t)U * d4;
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += kUpdRows * stride) {
+  const int64_t stride = (int64_t)nblk * 256;
+  for (int64_t i0 = (int64_t)blk * 256 + threadIdx.x; i0 < total; i0 += kUpdRows * stride) {
     float4 g[kUpdRows], w[kUpdRows], a[kUpdRows], x1[kUpdRows];
     int64_t r[kUpdRows];
     int sl[kUpdRows], vrow[kUpdRows], cc[kUpdRows];
@@ -654,6 +675,7 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
 #pragma unroll
     for (int u = 0; u < kUpdRows; ++u) {
       x1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (kGather && cp[u].x == kEdgeMark) continue;     // updated by the block that chains its partials
       if (sl[u] < 0) continue;
       r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + cc[u];
       w[u] = ld_row<kStream>(&cw[r[u]]);
@@ -693,7 +715,12 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
   }
 }
 
-// cold rows are summed here (the stream that ran before passed over them)
+// Cold rows are summed here (the stream that ran before passed over them), and so are the groups
+// that the stream left as block-edge partials: the first `nslots` blocks of the grid do what
+// k_seg_finish does, one block per slot, and the block that holds a run's sum updates that row at
+// once.  The other blocks walk the rows and pass over the marked ones (kEdgeMark).  The two parts
+// share nothing and wait for nothing: the chain of dependent loads that sums a long run (ten
+// microseconds as a kernel of its own) runs beside the row stream instead of before it.
 template <bool kOneHot>
 __global__ __launch_bounds__(256)
 #ifdef SFC_UPD_WAVES
@@ -707,12 +734,34 @@ void k_adagrad_rows(const float4* __restrict__ common,
                                                        int boff, float lr, float eps, int d4,
                                                        const Ctr* ctr,
                                                        const int2* __restrict__ cold_pay,
-                                                       const float4* __restrict__ grad) {
+                                                       const float4* __restrict__ grad,
+                                                       const double* __restrict__ bp,
+                                                       const int* __restrict__ bp_vid, int nslots) {
+  if ((int)blockIdx.x < nslots) {
+    int v;
+    D4 s;
+    if (!edge_run_sum(bp, bp_vid, nslots, d4, (int)blockIdx.x, v, s)) return;
+    const int c4 = (int)threadIdx.x;
+    if (c4 >= d4) return;
+    const int sl = slot[v];
+    if (sl < 0) return;
+    const int64_t r = (int64_t)(sl >= C ? sl + boff : sl) * d4 + c4;
+    float4 w = cw[r], a = ca[r];
+    adagrad4v(w, a, d4_round(s), lr, eps);
+    cw[r] = w; ca[r] = a;
+    if (sl >= C) {
+      const int64_t id = unique_ids[v];
+      h.w[id * h.hs4 + c4] = w;
+      h.a[id * h.has4 + c4] = a;
+    }
+    return;
+  }
   const int U = ctr->U;
+  const int blk = (int)blockIdx.x - nslots, nblk = (int)gridDim.x - nslots;
   if (stream_rows(U, d4, d4))
-    adagrad_rows<true, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad);
+    adagrad_rows<true, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad, blk, nblk);
   else
-    adagrad_rows<false, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad);
+    adagrad_rows<false, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad, blk, nblk);
 }
 
 // ---------------------------------------------------------------------------------------------
