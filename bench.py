@@ -316,7 +316,9 @@ def main():
                                "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
                                "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                "what": "the durations of the lookup call's two kernels + the backward_update call "
-                                       "between two events on its stream (three kernels and their launch gaps)",
+                                       "between two events on its stream (its kernels and their launch gaps; with Adagrad two: "
+                                       "the stream and the optimizer kernel, which also chains the stream's block-edge "
+                                       "partials, so k_seg_finish reads 0)",
                                "kernel_ms_sum": pair_kernel_ms,
                                "frac_of_hbm_peak_kernel_time": (pair_bytes / (pair_kernel_ms * 1e-3) / 1e9
                                                                 / HBM_PEAK_GBS) if pair_kernel_ms else None},

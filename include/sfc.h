@@ -293,11 +293,13 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
  * for the unique passes on the other).  sfc_lookup is two kernels (the batch's rows are read into
  * the memory-side cache, then gathered): the start and end of each are recorded by the dispatch
  * itself, i.e. the time is the sum of the two kernels' own durations as a profiler's kernel trace
- * shows them.  level 2: also, the same way, each of the three kernels inside sfc_backward_update.
+ * shows them.  level 2: also, the same way, each of the kernels inside sfc_backward_update.
  * level 0: off.  sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare,
  * fetch_misses, lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel,
  * optimizer kernel), the summed milliseconds and the number of launches since the last read of
- * that entry.
+ * that entry.  With the Adagrad optimizer sfc_backward_update launches no finish kernel (the
+ * optimizer kernel chains the stream's block-edge partials itself): entry 5 then counts the
+ * launches of sfc_segment_sum only.
  */
 int sfc_profile_enable(sfc_cache* c, int32_t level);
 int sfc_profile_read(sfc_cache* c, int32_t which, double* h_ms_sum, int64_t* h_calls);
