@@ -893,13 +893,14 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   const dim3 ug(grid_for(x->n_ids * c->d4, 1024, kGridCap));
   if (c->cfg.optimizer == SFC_OPT_ADAGRAD) {
     // the stream above passed over the cold groups and left the block-edge partials unchained:
-    // this kernel sums both itself (its first n_slots blocks chain the partials)
+    // this kernel sums both itself (its first blocks chain the partials, a lane group per slot)
     auto kern = x->d_offsets ? k_adagrad_rows<false> : k_adagrad_rows<true>;
-    LAUNCH_TIMED(c, P_ADAGRAD, true, kern, dim3(ug.x + (unsigned)n_slots), dim3(256), s, (const float4*)c->gsum,
+    const int n_edge = edge_blocks(n_slots, c->d4);
+    LAUNCH_TIMED(c, P_ADAGRAD, true, kern, dim3(ug.x + (unsigned)n_edge), dim3(256), s, (const float4*)c->gsum,
                  (const int*)x->d_slot, (const int64_t*)x->d_unique, (float4*)c->cw, (float4*)c->ca,
                  c->host, (int)c->C, x->boff, c->cfg.lr, c->cfg.eps, c->d4, (const Ctr*)x->ctr,
                  (const int2*)x->cold_pay, (const float4*)d_grad, (const double*)c->bp,
-                 (const int*)c->bp_vid, n_slots);
+                 (const int*)c->bp_vid, n_slots, n_edge);
   } else if (c->cfg.optimizer == SFC_OPT_ADAM) {
     // every constant derived from the decay rates is computed in double and rounded to fp32 once
     AdamArgs k;

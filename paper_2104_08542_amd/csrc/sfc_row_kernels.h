@@ -393,6 +393,23 @@ __device__ __forceinline__ int entry_key(int64_t e) {
   return (kSkipCold && entry_cold(e)) ? -1 : entry_vid(e);
 }
 
+// kSegChunk consecutive grouping entries from q on (q is a multiple of kSegChunk, the array is
+// 256-byte aligned), -1 for those at or beyond se: 16-byte loads of two entries where both exist.
+__device__ __forceinline__ void load_entries(const int64_t* __restrict__ perm64, int64_t q,
+                                             int64_t se, int64_t (&e)[kSegChunk]) {
+  static_assert(kSegChunk % 2 == 0, "entries are loaded in pairs");
+#pragma unroll
+  for (int k = 0; k < kSegChunk; k += 2) {
+    if (q + k + 1 < se) {
+      const longlong2 v = *reinterpret_cast<const longlong2*>(&perm64[q + k]);
+      e[k] = v.x; e[k + 1] = v.y;
+    } else {
+      e[k] = q + k < se ? perm64[q + k] : (int64_t)-1;
+      e[k + 1] = -1;
+    }
+  }
+}
+
 template <bool kOneHot, bool kSkipCold>
 __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ grad,
                                                      const int64_t* __restrict__ perm64, int n,
@@ -430,17 +447,14 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
     // iteration earlier), pn = the next chunk's entries
     int64_t pe[kSegChunk], pn[kSegChunk];
     float4 x[kSegChunk];
-#pragma unroll
-    for (int k = 0; k < kSegChunk; ++k) pe[k] = sb + k < se ? perm64[sb + k] : (int64_t)-1;
+    load_entries(perm64, sb, se, pe);
 #pragma unroll
     for (int k = 0; k < kSegChunk; ++k) {
       x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (pe[k] >= 0 && entry_key<kSkipCold>(pe[k]) >= 0)
         x[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pe[k] * d4 + c4]);
     }
-#pragma unroll
-    for (int k = 0; k < kSegChunk; ++k)
-      pn[k] = sb + kSegChunk + k < se ? perm64[sb + kSegChunk + k] : (int64_t)-1;
+    load_entries(perm64, sb + kSegChunk, se, pn);
     cur = entry_key<kSkipCold>(pe[0]);
     begun = prev_v != cur;
 
@@ -454,11 +468,7 @@ __global__ __launch_bounds__(256) void k_seg_stream(const float4* __restrict__ g
         if (pn[k] >= 0 && entry_key<kSkipCold>(pn[k]) >= 0)
           xn[k] = ld_row<kOneHot>(&grad[(int64_t)(uint32_t)pn[k] * d4 + c4]);
       }
-#pragma unroll
-      for (int k = 0; k < kSegChunk; ++k) {
-        const int64_t q = e + 2 * kSegChunk + k;
-        pnn[k] = q < se ? perm64[q] : (int64_t)-1;
-      }
+      load_entries(perm64, e + 2 * kSegChunk, se, pnn);
 #pragma unroll
       for (int k = 0; k < kSegChunk; ++k) {
         if (pe[k] >= 0) {
@@ -715,12 +725,43 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
   }
 }
 
+// One Adagrad step of row v, chunk c4 of it, with the summed gradient g (lanes c4 < d4 of a lane group).
+__device__ __forceinline__ void adagrad_one_row(int v, int c4, float4 g, const int* __restrict__ slot,
+                                                const int64_t* __restrict__ unique_ids,
+                                                float4* __restrict__ cw, float4* __restrict__ ca,
+                                                const HostRows& h, int C, int boff, float lr,
+                                                float eps, int d4) {
+  const int sl = slot[v];
+  if (sl < 0) return;
+  const int64_t r = (int64_t)(sl >= C ? sl + boff : sl) * d4 + c4;
+  float4 w = cw[r], a = ca[r];
+  adagrad4v(w, a, g, lr, eps);
+  cw[r] = w; ca[r] = a;
+  if (sl >= C) {
+    const int64_t id = unique_ids[v];
+    h.w[id * h.hs4 + c4] = w;
+    h.a[id * h.has4 + c4] = a;
+  }
+}
+
 // Cold rows are summed here (the stream that ran before passed over them), and so are the groups
-// that the stream left as block-edge partials: the first `nslots` blocks of the grid do what
-// k_seg_finish does, one block per slot, and the block that holds a run's sum updates that row at
-// once.  The other blocks walk the rows and pass over the marked ones (kEdgeMark).  The two parts
-// share nothing and wait for nothing: the chain of dependent loads that sums a long run (ten
-// microseconds as a kernel of its own) runs beside the row stream instead of before it.
+// that the stream left as block-edge partials: the first blocks of the grid do what k_seg_finish
+// does and update the rows they have summed at once; the other blocks walk the rows and pass
+// over the marked ones (kEdgeMark).  The two parts share nothing and wait for nothing: the chain of
+// dependent loads that sums a run (ten microseconds as a kernel of its own) runs beside the row
+// stream instead of before it.
+// In an edge block every lane group takes one slot of the partial lists.  Nearly all runs are two
+// slots long (the tail of one stream block and the head of the next): a group that finds the first
+// slot of a run of at most kEdgeShort slots adds them up itself, in slot order.  The few long runs
+// (an id with thousands of positions spans many stream blocks) are listed in LDS and summed by
+// the whole block, one after the other, as in k_seg_finish; their first slots lie more than
+// kEdgeShort slots apart, so a block meets only a few.
+constexpr int kEdgeShort = 8;
+inline int edge_blocks(int nslots, int d4) {
+  const int per_block = 4 * (64 / d4 > 0 ? 64 / d4 : 1);
+  return (nslots + per_block - 1) / per_block;
+}
+
 template <bool kOneHot>
 __global__ __launch_bounds__(256)
 #ifdef SFC_UPD_WAVES
@@ -736,28 +777,50 @@ void k_adagrad_rows(const float4* __restrict__ common,
                                                        const int2* __restrict__ cold_pay,
                                                        const float4* __restrict__ grad,
                                                        const double* __restrict__ bp,
-                                                       const int* __restrict__ bp_vid, int nslots) {
-  if ((int)blockIdx.x < nslots) {
-    int v;
-    D4 s;
-    if (!edge_run_sum(bp, bp_vid, nslots, d4, (int)blockIdx.x, v, s)) return;
-    const int c4 = (int)threadIdx.x;
-    if (c4 >= d4) return;
-    const int sl = slot[v];
-    if (sl < 0) return;
-    const int64_t r = (int64_t)(sl >= C ? sl + boff : sl) * d4 + c4;
-    float4 w = cw[r], a = ca[r];
-    adagrad4v(w, a, d4_round(s), lr, eps);
-    cw[r] = w; ca[r] = a;
-    if (sl >= C) {
-      const int64_t id = unique_ids[v];
-      h.w[id * h.hs4 + c4] = w;
-      h.a[id * h.has4 + c4] = a;
+                                                       const int* __restrict__ bp_vid, int nslots,
+                                                       int nedge) {
+  if ((int)blockIdx.x < nedge) {
+    __shared__ int n_long;
+    __shared__ int long_at[256];
+    if (threadIdx.x == 0) n_long = 0;
+    __syncthreads();
+    const int lane = lane_id(), G = 64 / d4 > 0 ? 64 / d4 : 1;
+    const int g = lane / d4, c4 = lane - g * d4;
+    const int j = ((int)blockIdx.x * 4 + (int)(threadIdx.x >> 6)) * G + g;
+    if (g < G && j < nslots) {
+      const int v = bp_vid[j];
+      if (v >= 0 && (j == 0 || bp_vid[j - 1] != v)) {       // first slot of its run
+        int len = 1;
+        while (len <= kEdgeShort && j + len < nslots && bp_vid[j + len] == v) ++len;
+        if (len > kEdgeShort) {
+          if (c4 == 0) long_at[atomicAdd(&n_long, 1)] = j;
+        } else {
+          const int D = d4 * 4;
+          double s0 = 0., s1 = 0., s2 = 0., s3 = 0.;
+          for (int k = 0; k < len; ++k) {
+            const double4 x = *reinterpret_cast<const double4*>(&bp[(int64_t)(j + k) * D + 4 * c4]);
+            s0 += x.x; s1 += x.y; s2 += x.z; s3 += x.w;
+          }
+          adagrad_one_row(v, c4, make_float4((float)s0, (float)s1, (float)s2, (float)s3), slot,
+                          unique_ids, cw, ca, h, C, boff, lr, eps, d4);
+        }
+      }
+    }
+    __syncthreads();
+    const int nl = n_long;
+    for (int i = 0; i < nl; ++i) {
+      int v;
+      D4 s;
+      const bool first = edge_run_sum(bp, bp_vid, nslots, d4, long_at[i], v, s);
+      if (first && (int)threadIdx.x < d4)
+        adagrad_one_row(v, (int)threadIdx.x, d4_round(s), slot, unique_ids, cw, ca, h, C, boff, lr,
+                        eps, d4);
+      __syncthreads();
     }
     return;
   }
   const int U = ctr->U;
-  const int blk = (int)blockIdx.x - nslots, nblk = (int)gridDim.x - nslots;
+  const int blk = (int)blockIdx.x - nedge, nblk = (int)gridDim.x - nedge;
   if (stream_rows(U, d4, d4))
     adagrad_rows<true, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad, blk, nblk);
   else
