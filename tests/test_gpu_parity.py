@@ -142,6 +142,24 @@ def test_long_groups_cross_many_spans():
     p.finish(); p.close()
 
 
+@pytest.mark.parametrize("D,C", [(4, 400), (16, 0), (80, 400), (256, 7)])
+def test_groups_cut_by_block_edges_are_updated_once(D, C):
+    # Adagrad path: the optimizer kernel itself adds up the partial sums of groups that the gradient
+    # stream's blocks cut (a lane group per short run, the whole block for a run of many slots) and
+    # updates those rows; here one id has a run of hundreds of slots, a dozen ids have runs of a few
+    # slots, the rest close inside a block.  Row widths of one lane and of a whole wavefront, a width
+    # that does not divide the wavefront, rows that bypass the cache (C = 0: every one; C = 7: most).
+    V, n = 400, 150_000
+    rng = np.random.default_rng(100 + D)
+    r = rng.random(n)
+    mid = 20 + (rng.integers(0, 12, n))
+    ids = np.where(r < 0.45, 3, np.where(r < 0.85, mid, rng.integers(0, V, n)))
+    p = Pair(V, D, C=C, max_ids=n)
+    p.step(ids, si.grads(n, D, 70 + D, 0).numpy())
+    p.step(ids[::-1].copy(), si.grads(n, D, 70 + D, 1).numpy())
+    p.finish(); p.close()
+
+
 def test_frequent_ids_that_first_appear_late():
     # the grouping passes treat the lowest virtual ids (the early, usually frequent ones) in LDS and
     # rank the others with atomics: here the batch opens with 9000 distinct ids, so the frequent ids
