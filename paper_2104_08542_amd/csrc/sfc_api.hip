@@ -801,9 +801,10 @@ int sfc_lookup(sfc_cache* c, float* d_out) {
                    (const Ctr*)x->ctr, c->warm_sink, (const int4*)x->pos_slot, (int)(x->n_ids / 4));
     if (!x->d_offsets) {
       const int d4 = c->d4, sh = (d4 & (d4 - 1)) == 0 ? __builtin_ctz(d4) : -1;
+      const int bpb = lookup_rows_per_block(d4);
       LAUNCH_TIMED(c, P_LOOKUP, true, k_lookup_onehot,
-                   dim3((unsigned)((x->n_bags + kLookupBags - 1) / kLookupBags)), dim3(256), s,
-                   (const int*)x->pos_slot, (const float4*)c->cw, (float4*)d_out, (int)x->n_bags, d4, sh);
+                   dim3((unsigned)((x->n_bags + bpb - 1) / bpb)), dim3(256), s,
+                   (const int*)x->pos_slot, (const float4*)c->cw, (float4*)d_out, (int)x->n_bags, d4, sh, bpb);
     } else {
       const int G = 64 / c->d4 > 0 ? 64 / c->d4 : 1;          // bags per wavefront
       const int64_t per_block = 4 * (int64_t)G;

@@ -133,7 +133,16 @@ __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_
 // 79-85 us.  Variants without LDS staging, with 2/4/16 chunks per thread or persistent blocks
 // measured within +-5 % of this one under those conditions.
 // ---------------------------------------------------------------------------------------------
-constexpr int kLookupBags = 256;
+constexpr int kLookupBags = 256;      // most rows a block of the one-hot gather takes
+// Rows per block of the one-hot gather: 512 16-byte chunks, two per thread.  With the rows
+// waiting in the memory-side cache (k_warm_rows) small blocks win: 62.6 us at the target
+// configuration against 69.7 with 256 rows (2048 chunks) per block; 32 rows: 66.4.
+inline int lookup_rows_per_block(int d4) {
+  int b = 512 / d4;
+  if (b < 16) b = 16;
+  if (b > kLookupBags) b = kLookupBags;
+  return b;
+}
 
 // Before the gather: every row the batch needs is read once, by a kernel that does nothing else.
 // The gather is sensitive to the latency of its slowest row: each wavefront holds eight rows per
@@ -190,16 +199,16 @@ __device__ __forceinline__ void split_chunk(unsigned ch, int d4, int sh, unsigne
 __global__ __launch_bounds__(256) void k_lookup_onehot(const int* __restrict__ pos_slot,
                                                         const float4* __restrict__ cw,
                                                         float4* __restrict__ out, int n_bags,
-                                                        int d4, int sh) {
+                                                        int d4, int sh, int bpb) {
   __shared__ int ls[kLookupBags];
-  const int b0 = (int)blockIdx.x * kLookupBags;
+  const int b0 = (int)blockIdx.x * bpb;          // bpb <= kLookupBags = block size
   {
     const int b = b0 + (int)threadIdx.x;
-    ls[threadIdx.x] = b < n_bags ? pos_slot[b] : -1;
+    ls[threadIdx.x] = ((int)threadIdx.x < bpb && b < n_bags) ? pos_slot[b] : -1;
   }
   __syncthreads();
   int nb = n_bags - b0;
-  if (nb > kLookupBags) nb = kLookupBags;
+  if (nb > bpb) nb = bpb;
   const unsigned chunks = (unsigned)nb * (unsigned)d4;
   float4* dst = out + (int64_t)b0 * d4;
   for (unsigned base = 0; base < chunks; base += 256 * 8) {
