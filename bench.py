@@ -244,11 +244,30 @@ def main():
     b_lookup = 4 * N + 4 * U + U * R + bags * R + extra
     RS = R + 4 * S                                                    # a row and its optimizer state
     b_update = bags * R + 4 * N + 4 * U + 2 * U * RS + extra         # sfc_backward_update as a whole
+    # With Adagrad the ids with at most two positions (outside the 8192 lowest virtual ids) are summed
+    # by the optimizer kernel from their own gradient rows: that share of the gradient bytes is the
+    # optimizer kernel's, not the stream's, and those rows make no trip through the common matrix.
+    # Counted here on one batch of the timed passes (torch, outside every timed region).
+    Pc = Uc = 0
+    if args.optimizer == "adagrad":
+        ids1 = batches2[0][0].reshape(-1)
+        uq, inv, cnt = torch.unique(ids1, return_inverse=True, return_counts=True)
+        first = torch.full((uq.numel(),), ids1.numel(), dtype=torch.int64, device=dev)
+        first.scatter_reduce_(0, inv, torch.arange(ids1.numel(), device=dev), "amin")
+        rank = torch.empty_like(first)
+        rank[first.argsort()] = torch.arange(uq.numel(), device=dev)
+        cold = (cnt <= 2) & (rank >= 8192)
+        Uc, Pc = float(cold.sum().item()), float(cnt[cold].sum().item())
+        del uq, inv, cnt, first, rank, cold
+    g_stream = bags * R * (N - Pc) / N        # one-hot: a gradient row per position; bags: in proportion
     kernels = {
         # the lookup call is two kernels: the batch's rows are warmed into the memory-side cache, then gathered
         ("k_warm_rows+k_lookup_onehot" if w.one_hot else "k_warm_rows+k_lookup_bags"): (b_lookup, ms["lookup"]),
-        "k_seg_stream": (bags * R + 4 * N + U * R + extra, ms["k_seg_stream"]),   # grad + grouping in, common out
-        "k_%s_rows" % args.optimizer: (4 * U + U * R + 2 * U * RS, ms["k_adagrad_rows"]),
+        # gradient rows of the other ids + grouping in, their common rows out
+        "k_seg_stream": (g_stream + 4 * N + (U - Uc) * R + extra, ms["k_seg_stream"]),
+        # slot per row, the cold ids' gradient rows, the other ids' common rows, row + state in and out
+        "k_%s_rows" % args.optimizer: (4 * U + (bags * R - g_stream) + (U - Uc) * R + 2 * U * RS,
+                                      ms["k_adagrad_rows"]),
     }
     dom = max(kernels, key=lambda k: kernels[k][1])
     ach = kernels[dom][0] / (kernels[dom][1] * 1e-3) / 1e9
@@ -289,6 +308,7 @@ def main():
                            "uniform" if w.zipf_s is None else "Zipf(s=%.2f)" % w.zipf_s, V, D, C,
                            {"adagrad": "Adagrad", "adam": "Adam", "rowwise_adagrad": "row-wise Adagrad"}[args.optimizer]),
             "ids_per_step": N, "unique_per_step": U,
+            "cold_ids_per_step": Uc, "cold_positions_per_step": Pc,
             "hit_rate": avg["n_hit"] / max(1.0, avg["n_hit"] + avg["n_miss"]),
             "miss_per_step": avg["n_miss"], "evict_per_step": avg["n_evict"],
             "bypass_per_step": avg["n_bypass"], "lookahead": args.lookahead,
