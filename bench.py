@@ -244,12 +244,12 @@ def main():
     b_lookup = 4 * N + 4 * U + U * R + bags * R + extra
     RS = R + 4 * S                                                    # a row and its optimizer state
     b_update = bags * R + 4 * N + 4 * U + 2 * U * RS + extra         # sfc_backward_update as a whole
-    # With Adagrad the ids with at most two positions (outside the 8192 lowest virtual ids) are summed
+    # With Adagrad and Adam the ids with at most two positions (outside the 8192 lowest virtual ids) are summed
     # by the optimizer kernel from their own gradient rows: that share of the gradient bytes is the
     # optimizer kernel's, not the stream's, and those rows make no trip through the common matrix.
     # Counted here on one batch of the timed passes (torch, outside every timed region).
     Pc = Uc = 0
-    if args.optimizer == "adagrad":
+    if args.optimizer in ("adagrad", "adam"):
         ids1 = batches2[0][0].reshape(-1)
         uq, inv, cnt = torch.unique(ids1, return_inverse=True, return_counts=True)
         first = torch.full((uq.numel(),), ids1.numel(), dtype=torch.int64, device=dev)
@@ -336,7 +336,7 @@ def main():
                                "GB/s": pair_bytes / (pair_ms * 1e-3) / 1e9,
                                "frac_of_hbm_peak": pair_bytes / (pair_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                "what": "the durations of the lookup call's two kernels + the backward_update call "
-                                       "between two events on its stream (its kernels and their launch gaps; with Adagrad two: "
+                                       "between two events on its stream (its kernels and their launch gaps; with Adagrad and Adam two: "
                                        "the stream and the optimizer kernel, which also chains the stream's block-edge "
                                        "partials, so k_seg_finish reads 0)",
                                "kernel_ms_sum": pair_kernel_ms,

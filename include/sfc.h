@@ -297,7 +297,7 @@ int sfc_cache_state(sfc_cache* c, int64_t* h_slot_id, int32_t* h_stamp, float* h
  * level 0: off.  sfc_profile_read waits for the streams and returns, for which = 0..6 (prepare,
  * fetch_misses, lookup, backward_update, segment-sum stream kernel, segment-sum finish kernel,
  * optimizer kernel), the summed milliseconds and the number of launches since the last read of
- * that entry.  With the Adagrad optimizer sfc_backward_update launches no finish kernel (the
+ * that entry.  With Adagrad or Adam sfc_backward_update launches no finish kernel (the
  * optimizer kernel chains the stream's block-edge partials itself): entry 5 then counts the
  * launches of sfc_segment_sum only.
  */

@@ -882,7 +882,9 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
   EventPair ep{};
   if ((rc = prof_begin(c, P_BACKWARD, s, &ep))) return rc;
   int n_slots = 0;
-  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true, c->cfg.optimizer == SFC_OPT_ADAGRAD, &n_slots))) return rc;
+  // Adagrad and Adam: the update kernel sums the cold groups and chains the block-edge partials itself
+  const bool fused = c->cfg.optimizer == SFC_OPT_ADAGRAD || c->cfg.optimizer == SFC_OPT_ADAM;
+  if ((rc = seg_launch(c, x, d_grad, c->gsum, c->bp, c->bp_vid, true, fused, &n_slots))) return rc;
   if (c->cfg.policy == SFC_POLICY_PREFETCH) {
     // the copies of a newer step issued so far read the Host table before this update writes it
     for (int k = 0; k < c->nctx; ++k) {
@@ -892,11 +894,11 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
     }
   }
   const dim3 ug(grid_for(x->n_ids * c->d4, 1024, kGridCap));
+  // the stream above passed over the cold groups and left the block-edge partials unchained:
+  // the fused kernels sum both themselves (their first blocks chain the partials, a lane group per slot)
+  const int n_edge = edge_blocks(n_slots, c->d4);
   if (c->cfg.optimizer == SFC_OPT_ADAGRAD) {
-    // the stream above passed over the cold groups and left the block-edge partials unchained:
-    // this kernel sums both itself (its first blocks chain the partials, a lane group per slot)
     auto kern = x->d_offsets ? k_adagrad_rows<false> : k_adagrad_rows<true>;
-    const int n_edge = edge_blocks(n_slots, c->d4);
     LAUNCH_TIMED(c, P_ADAGRAD, true, kern, dim3(ug.x + (unsigned)n_edge), dim3(256), s, (const float4*)c->gsum,
                  (const int*)x->d_slot, (const int64_t*)x->d_unique, (float4*)c->cw, (float4*)c->ca,
                  c->host, (int)c->C, x->boff, c->cfg.lr, c->cfg.eps, c->d4, (const Ctr*)x->ctr,
@@ -910,9 +912,12 @@ int sfc_backward_update(sfc_cache* c, const float* d_grad) {
     k.bc1 = (float)(1.0 - pow(c->cfg.beta1, (double)x->t));
     k.bc2 = (float)(1.0 - pow(c->cfg.beta2, (double)x->t));
     k.lr = c->cfg.lr; k.eps = c->cfg.eps;
-    LAUNCH_TIMED(c, P_ADAGRAD, true, k_adam_rows, ug, dim3(256), s, (const float4*)c->gsum,
+    auto kern = x->d_offsets ? k_adam_rows<false> : k_adam_rows<true>;
+    LAUNCH_TIMED(c, P_ADAGRAD, true, kern, dim3(ug.x + (unsigned)n_edge), dim3(256), s, (const float4*)c->gsum,
                  (const int*)x->d_slot, (const int64_t*)x->d_unique, (float4*)c->cw, (float4*)c->ca,
-                 c->host, (int)c->C, x->boff, k, c->d4, (const Ctr*)x->ctr);
+                 c->host, (int)c->C, x->boff, k, c->d4, (const Ctr*)x->ctr,
+                 (const int2*)x->cold_pay, (const float4*)d_grad, (const double*)c->bp,
+                 (const int*)c->bp_vid, n_slots, n_edge);
   } else {
     const int pow2 = (c->d4 & (c->d4 - 1)) == 0;
     LAUNCH_TIMED(c, P_ADAGRAD, true, k_rowwise_adagrad_rows, ug, dim3(256), s,

@@ -650,56 +650,96 @@ __device__ __forceinline__ bool stream_rows(int U, int d4, int s4) {
   return (int64_t)U * (3 * d4 + 2 * s4) * 16 > kStreamRowsBytes;
 }
 
-// Adagrad over the common-gradient matrix (one row per virtual id), four rows per thread in flight.
+// ---------------------------------------------------------------------------------------------
+// Adam (Experiment settings: the paper's optimizer), lazily on the rows of the batch, with the
+// batch number t in the bias corrections bc = 1 - beta^t (computed by the host in double):
+//   m = b1*m + c1*g ; v = b2*v + c2*g*g ; w -= lr * (m/bc1) / (sqrt(v/bc2) + eps)
+// The state of a row is 2*d4 chunks: first moments, then second moments.
+// ---------------------------------------------------------------------------------------------
+struct AdamArgs {
+  float b1, c1, b2, c2;   // beta1, 1-beta1, beta2, 1-beta2
+  float bc1, bc2, lr, eps;
+};
+__device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, const AdamArgs& k) {
+  m = k.b1 * m + k.c1 * g;
+  v = k.b2 * v + k.c2 * (g * g);
+  const float mhat = m / k.bc1, vhat = v / k.bc2;
+  w = w - k.lr * mhat / (sqrtf(vhat) + k.eps);
+}
+
+// The two element-wise optimizers as policies of one row kernel: kParts state chunks travel with
+// each 16-byte chunk of a row (part p of chunk c of a row lies at row * kParts * d4 + p * d4 + c),
+// kRows rows are in flight per thread.
+struct AdagradOp {
+  static constexpr int kParts = 1;
+  static constexpr int kRows = 3;      // four cost a wavefront of occupancy: 33 against 28.5 us
+  float lr, eps;
+  __device__ __forceinline__ void apply(float4& w, float4 (&st)[1], float4 g) const {
+    adagrad4v(w, st[0], g, lr, eps);
+  }
+};
+struct AdamOp {
+  static constexpr int kParts = 2;
+  static constexpr int kRows = 2;
+  AdamArgs k;
+  __device__ __forceinline__ void apply(float4& w, float4 (&st)[2], float4 g) const {
+    adam1(w.x, st[0].x, st[1].x, g.x, k);
+    adam1(w.y, st[0].y, st[1].y, g.y, k);
+    adam1(w.z, st[0].z, st[1].z, g.z, k);
+    adam1(w.w, st[0].w, st[1].w, g.w, k);
+  }
+};
+
+// The update over the rows of a batch (one row per virtual id), Op::kRows rows per thread in flight.
 // A bypass row (slot >= C: a miss that found no cache slot) is also written to the Host table
 // here: it lives for this step only.
-// kGather: the gradient of a cold row (see kColdBit) is summed here from its at most kColdMax
-// gradient rows (cold_pay[v] = their numbers, -1 = none; both -1 = not a cold row), in fp64,
-// lower gradient row first (so the sum does not depend on the order in which the grouping pass
-// happened to rank the group's positions); every other row takes its sum from the common-gradient
-// matrix.  kOneHot: a gradient row is read once per step.
-#ifndef SFC_UPD_ROWS
-#define SFC_UPD_ROWS 3
-#endif
-constexpr int kUpdRows = SFC_UPD_ROWS;     // rows per thread in flight in the Adagrad kernel
-
-template <bool kStream, bool kGather, bool kOneHot>
-__device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
-                                             const int* __restrict__ slot,
-                                             const int64_t* __restrict__ unique_ids,
-                                             float4* __restrict__ cw, float4* __restrict__ ca,
-                                             const HostRows& h, int C, int boff, float lr, float eps,
-                                             int d4, int U, const int2* __restrict__ cold_pay,
-                                             const float4* __restrict__ grad, int blk, int nblk) {
+// The gradient of a cold row (see kColdBit) is summed here from its at most kColdMax gradient rows
+// (cold_pay[v] = their numbers, -1 = none; both -1 = not a cold row), in fp64, lower gradient row
+// first (so the sum does not depend on the order in which the grouping pass happened to rank the
+// group's positions); a row marked kEdgeMark is left to the block that chains its partials; every
+// other row takes its sum from the common-gradient matrix.  kOneHot: a gradient row is read once
+// per step.
+template <class Op, bool kStream, bool kOneHot>
+__device__ __forceinline__ void update_rows(const Op& op, const float4* __restrict__ common,
+                                            const int* __restrict__ slot,
+                                            const int64_t* __restrict__ unique_ids,
+                                            float4* __restrict__ cw, float4* __restrict__ cs,
+                                            const HostRows& h, int C, int boff, int d4, int U,
+                                            const int2* __restrict__ cold_pay,
+                                            const float4* __restrict__ grad, int blk, int nblk) {
   static_assert(kColdMax == 2, "the gather path below takes two gradient rows");
+  constexpr int kR = Op::kRows, kP = Op::kParts;
   const int64_t total = (int64_t)U * d4;
   const int64_t stride = (int64_t)nblk * 256;
-  for (int64_t i0 = (int64_t)blk * 256 + threadIdx.x; i0 < total; i0 += kUpdRows * stride) {
-    float4 g[kUpdRows], w[kUpdRows], a[kUpdRows], x1[kUpdRows];
-    int64_t r[kUpdRows];
-    int sl[kUpdRows], vrow[kUpdRows], cc[kUpdRows];
-    int2 cp[kUpdRows];
-    // two levels of indirection, kUpdRows rows in flight at each: slot and cold rows of the row, then
+  for (int64_t i0 = (int64_t)blk * 256 + threadIdx.x; i0 < total; i0 += kR * stride) {
+    float4 g[kR], w[kR], st[kR][kP], x1[kR];
+    int64_t r[kR], rs[kR];
+    int sl[kR], vrow[kR], cc[kR];
+    int2 cp[kR];
+    // two levels of indirection, kR rows in flight at each: slot and cold rows of the row, then
     // its weights, state and gradient (one row of the common matrix, or its own one or two rows)
 #pragma unroll
-    for (int u = 0; u < kUpdRows; ++u) {
+    for (int u = 0; u < kR; ++u) {
       const int64_t i = i0 + u * stride;
       r[u] = -1; sl[u] = -1; cp[u] = make_int2(-1, -1);
       if (i < total) {
         vrow[u] = (int)(i / d4); cc[u] = (int)(i - (int64_t)vrow[u] * d4);
         sl[u] = slot[vrow[u]];
-        if (kGather) cp[u] = cold_pay[vrow[u]];
+        cp[u] = cold_pay[vrow[u]];
       }
     }
 #pragma unroll
-    for (int u = 0; u < kUpdRows; ++u) {
+    for (int u = 0; u < kR; ++u) {
       x1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (kGather && cp[u].x == kEdgeMark) continue;     // updated by the block that chains its partials
+      if (cp[u].x == kEdgeMark) continue;     // updated by the block that chains its partials
       if (sl[u] < 0) continue;
-      r[u] = (int64_t)(sl[u] >= C ? sl[u] + boff : sl[u]) * d4 + cc[u];
+      const int64_t row = sl[u] >= C ? sl[u] + boff : sl[u];
+      r[u] = row * d4 + cc[u];
+      rs[u] = row * (kP * d4) + cc[u];
       w[u] = ld_row<kStream>(&cw[r[u]]);
-      a[u] = ld_row<kStream>(&ca[r[u]]);
-      if (kGather && cp[u].x >= 0) {
+#pragma unroll
+      for (int p = 0; p < kP; ++p) st[u][p] = ld_row<kStream>(&cs[rs[u] + p * d4]);
+      if (cp[u].x >= 0) {
         // lower gradient row first
         const bool two = cp[u].y >= 0;
         const int q0 = two && cp[u].y < cp[u].x ? cp[u].y : cp[u].x;
@@ -710,46 +750,55 @@ __device__ __forceinline__ void adagrad_rows(const float4* __restrict__ common,
         g[u] = ld_row<kStream>(&common[(int64_t)vrow[u] * d4 + cc[u]]);
       }
     }
-    if (kGather) {
 #pragma unroll
-      for (int u = 0; u < kUpdRows; ++u)
-        if (cp[u].x >= 0 && cp[u].y >= 0) {
-          g[u].x = (float)((double)g[u].x + (double)x1[u].x);
-          g[u].y = (float)((double)g[u].y + (double)x1[u].y);
-          g[u].z = (float)((double)g[u].z + (double)x1[u].z);
-          g[u].w = (float)((double)g[u].w + (double)x1[u].w);
-        }
-    }
+    for (int u = 0; u < kR; ++u)
+      if (cp[u].x >= 0 && cp[u].y >= 0) {
+        g[u].x = (float)((double)g[u].x + (double)x1[u].x);
+        g[u].y = (float)((double)g[u].y + (double)x1[u].y);
+        g[u].z = (float)((double)g[u].z + (double)x1[u].z);
+        g[u].w = (float)((double)g[u].w + (double)x1[u].w);
+      }
 #pragma unroll
-    for (int u = 0; u < kUpdRows; ++u)
+    for (int u = 0; u < kR; ++u)
       if (r[u] >= 0) {
-        adagrad4v(w[u], a[u], g[u], lr, eps);
-        st_row<kStream>(&cw[r[u]], w[u]); st_row<kStream>(&ca[r[u]], a[u]);
+        op.apply(w[u], st[u], g[u]);
+        st_row<kStream>(&cw[r[u]], w[u]);
+#pragma unroll
+        for (int p = 0; p < kP; ++p) st_row<kStream>(&cs[rs[u] + p * d4], st[u][p]);
         if (sl[u] >= C) {
           const int64_t id = unique_ids[vrow[u]];
           h.w[id * h.hs4 + cc[u]] = w[u];
-          h.a[id * h.has4 + cc[u]] = a[u];
+#pragma unroll
+          for (int p = 0; p < kP; ++p) h.a[id * h.has4 + p * d4 + cc[u]] = st[u][p];
         }
       }
   }
 }
 
-// One Adagrad step of row v, chunk c4 of it, with the summed gradient g (lanes c4 < d4 of a lane group).
-__device__ __forceinline__ void adagrad_one_row(int v, int c4, float4 g, const int* __restrict__ slot,
-                                                const int64_t* __restrict__ unique_ids,
-                                                float4* __restrict__ cw, float4* __restrict__ ca,
-                                                const HostRows& h, int C, int boff, float lr,
-                                                float eps, int d4) {
+// One update of row v, chunk c4 of it, with the summed gradient g (lanes c4 < d4 of a lane group).
+template <class Op>
+__device__ __forceinline__ void update_one_row(const Op& op, int v, int c4, float4 g,
+                                               const int* __restrict__ slot,
+                                               const int64_t* __restrict__ unique_ids,
+                                               float4* __restrict__ cw, float4* __restrict__ cs,
+                                               const HostRows& h, int C, int boff, int d4) {
+  constexpr int kP = Op::kParts;
   const int sl = slot[v];
   if (sl < 0) return;
-  const int64_t r = (int64_t)(sl >= C ? sl + boff : sl) * d4 + c4;
-  float4 w = cw[r], a = ca[r];
-  adagrad4v(w, a, g, lr, eps);
-  cw[r] = w; ca[r] = a;
+  const int64_t row = sl >= C ? sl + boff : sl;
+  const int64_t r = row * d4 + c4, rs = row * (kP * d4) + c4;
+  float4 w = cw[r], st[kP];
+#pragma unroll
+  for (int p = 0; p < kP; ++p) st[p] = cs[rs + p * d4];
+  op.apply(w, st, g);
+  cw[r] = w;
+#pragma unroll
+  for (int p = 0; p < kP; ++p) cs[rs + p * d4] = st[p];
   if (sl >= C) {
     const int64_t id = unique_ids[v];
     h.w[id * h.hs4 + c4] = w;
-    h.a[id * h.has4 + c4] = a;
+#pragma unroll
+    for (int p = 0; p < kP; ++p) h.a[id * h.has4 + p * d4 + c4] = st[p];
   }
 }
 
@@ -771,23 +820,17 @@ inline int edge_blocks(int nslots, int d4) {
   return (nslots + per_block - 1) / per_block;
 }
 
-template <bool kOneHot>
-__global__ __launch_bounds__(256)
-#ifdef SFC_UPD_WAVES
-__attribute__((amdgpu_waves_per_eu(SFC_UPD_WAVES, SFC_UPD_WAVES)))
-#endif
-void k_adagrad_rows(const float4* __restrict__ common,
-                                                       const int* __restrict__ slot,
-                                                       const int64_t* __restrict__ unique_ids,
-                                                       float4* __restrict__ cw,
-                                                       float4* __restrict__ ca, HostRows h, int C,
-                                                       int boff, float lr, float eps, int d4,
-                                                       const Ctr* ctr,
-                                                       const int2* __restrict__ cold_pay,
-                                                       const float4* __restrict__ grad,
-                                                       const double* __restrict__ bp,
-                                                       const int* __restrict__ bp_vid, int nslots,
-                                                       int nedge) {
+template <class Op, bool kOneHot>
+__device__ __forceinline__ void update_kernel(const Op& op, const float4* __restrict__ common,
+                                              const int* __restrict__ slot,
+                                              const int64_t* __restrict__ unique_ids,
+                                              float4* __restrict__ cw, float4* __restrict__ cs,
+                                              const HostRows& h, int C, int boff, int d4,
+                                              const Ctr* ctr, const int2* __restrict__ cold_pay,
+                                              const float4* __restrict__ grad,
+                                              const double* __restrict__ bp,
+                                              const int* __restrict__ bp_vid, int nslots,
+                                              int nedge) {
   if ((int)blockIdx.x < nedge) {
     __shared__ int n_long;
     __shared__ int long_at[256];
@@ -810,8 +853,8 @@ void k_adagrad_rows(const float4* __restrict__ common,
             const double4 x = *reinterpret_cast<const double4*>(&bp[(int64_t)(j + k) * D + 4 * c4]);
             s0 += x.x; s1 += x.y; s2 += x.z; s3 += x.w;
           }
-          adagrad_one_row(v, c4, make_float4((float)s0, (float)s1, (float)s2, (float)s3), slot,
-                          unique_ids, cw, ca, h, C, boff, lr, eps, d4);
+          update_one_row(op, v, c4, make_float4((float)s0, (float)s1, (float)s2, (float)s3), slot,
+                         unique_ids, cw, cs, h, C, boff, d4);
         }
       }
     }
@@ -822,96 +865,47 @@ void k_adagrad_rows(const float4* __restrict__ common,
       D4 s;
       const bool first = edge_run_sum(bp, bp_vid, nslots, d4, long_at[i], v, s);
       if (first && (int)threadIdx.x < d4)
-        adagrad_one_row(v, (int)threadIdx.x, d4_round(s), slot, unique_ids, cw, ca, h, C, boff, lr,
-                        eps, d4);
+        update_one_row(op, v, (int)threadIdx.x, d4_round(s), slot, unique_ids, cw, cs, h, C, boff, d4);
       __syncthreads();
     }
     return;
   }
   const int U = ctr->U;
   const int blk = (int)blockIdx.x - nedge, nblk = (int)gridDim.x - nedge;
-  if (stream_rows(U, d4, d4))
-    adagrad_rows<true, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad, blk, nblk);
+  if (stream_rows(U, d4, Op::kParts * d4))
+    update_rows<Op, true, kOneHot>(op, common, slot, unique_ids, cw, cs, h, C, boff, d4, U, cold_pay, grad, blk, nblk);
   else
-    adagrad_rows<false, true, kOneHot>(common, slot, unique_ids, cw, ca, h, C, boff, lr, eps, d4, U, cold_pay, grad, blk, nblk);
+    update_rows<Op, false, kOneHot>(op, common, slot, unique_ids, cw, cs, h, C, boff, d4, U, cold_pay, grad, blk, nblk);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Adam (Experiment settings: the paper's optimizer), lazily on the rows of the batch, with the
-// batch number t in the bias corrections bc = 1 - beta^t (computed by the host in double):
-//   m = b1*m + c1*g ; v = b2*v + c2*g*g ; w -= lr * (m/bc1) / (sqrt(v/bc2) + eps)
-// The state of a row is 2*d4 chunks: first moments, then second moments.
-// ---------------------------------------------------------------------------------------------
-struct AdamArgs {
-  float b1, c1, b2, c2;   // beta1, 1-beta1, beta2, 1-beta2
-  float bc1, bc2, lr, eps;
-};
-__device__ __forceinline__ void adam1(float& w, float& m, float& v, float g, const AdamArgs& k) {
-  m = k.b1 * m + k.c1 * g;
-  v = k.b2 * v + k.c2 * (g * g);
-  const float mhat = m / k.bc1, vhat = v / k.bc2;
-  w = w - k.lr * mhat / (sqrtf(vhat) + k.eps);
+// Four wavefronts per SIMD: with the registers of five or six the kernel is slower (31.1 and 36.4 us
+// against 29.1 at the target configuration: fewer loads in flight per wavefront, and more
+// wavefronts evicting each other's lines).
+template <bool kOneHot>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_adagrad_rows(
+    const float4* __restrict__ common, const int* __restrict__ slot,
+    const int64_t* __restrict__ unique_ids, float4* __restrict__ cw, float4* __restrict__ ca,
+    HostRows h, int C, int boff, float lr, float eps, int d4, const Ctr* ctr,
+    const int2* __restrict__ cold_pay, const float4* __restrict__ grad,
+    const double* __restrict__ bp, const int* __restrict__ bp_vid, int nslots, int nedge) {
+  AdagradOp op;
+  op.lr = lr; op.eps = eps;
+  update_kernel<AdagradOp, kOneHot>(op, common, slot, unique_ids, cw, ca, h, C, boff, d4, ctr, cold_pay,
+                                    grad, bp, bp_vid, nslots, nedge);
 }
 
-template <bool kStream>
-__device__ __forceinline__ void adam_rows(const float4* __restrict__ common,
-                                          const int* __restrict__ slot,
-                                          const int64_t* __restrict__ unique_ids,
-                                          float4* __restrict__ cw, float4* __restrict__ cs,
-                                          const HostRows& h, int C, int boff, const AdamArgs& k,
-                                          int d4, int U) {
-  const int64_t total = (int64_t)U * d4;
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += 2 * stride) {
-    float4 g[2], w[2], m[2], v[2];
-    int64_t rw[2], rs[2];
-    int sl[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int64_t i = i0 + u * stride;
-      rw[u] = -1;
-      if (i < total) {
-        sl[u] = slot[(int)(i / d4)];
-        if (sl[u] >= 0) {
-          const int64_t row = sl[u] >= C ? sl[u] + boff : sl[u];
-          rw[u] = row * d4 + (i % d4);
-          rs[u] = row * 2 * d4 + (i % d4);
-          g[u] = ld_row<kStream>(&common[i]); w[u] = ld_row<kStream>(&cw[rw[u]]);
-          m[u] = ld_row<kStream>(&cs[rs[u]]); v[u] = ld_row<kStream>(&cs[rs[u] + d4]);
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-      if (rw[u] >= 0) {
-        adam1(w[u].x, m[u].x, v[u].x, g[u].x, k);
-        adam1(w[u].y, m[u].y, v[u].y, g[u].y, k);
-        adam1(w[u].z, m[u].z, v[u].z, g[u].z, k);
-        adam1(w[u].w, m[u].w, v[u].w, g[u].w, k);
-        st_row<kStream>(&cw[rw[u]], w[u]); st_row<kStream>(&cs[rs[u]], m[u]);
-        st_row<kStream>(&cs[rs[u] + d4], v[u]);
-        if (sl[u] >= C) {
-          const int64_t i = i0 + u * stride;
-          const int64_t id = unique_ids[(int)(i / d4)];
-          const int c = (int)(i % d4);
-          h.w[id * h.hs4 + c] = w[u];
-          h.a[id * h.has4 + c] = m[u];
-          h.a[id * h.has4 + d4 + c] = v[u];
-        }
-      }
-  }
-}
-
-__global__ __launch_bounds__(256) void k_adam_rows(const float4* __restrict__ common,
-                                                    const int* __restrict__ slot,
-                                                    const int64_t* __restrict__ unique_ids,
-                                                    float4* __restrict__ cw,
-                                                    float4* __restrict__ cs, HostRows h, int C,
-                                                    int boff, AdamArgs k, int d4,
-                                                    const Ctr* ctr) {
-  const int U = ctr->U;
-  if (stream_rows(U, d4, 2 * d4)) adam_rows<true>(common, slot, unique_ids, cw, cs, h, C, boff, k, d4, U);
-  else adam_rows<false>(common, slot, unique_ids, cw, cs, h, C, boff, k, d4, U);
+template <bool kOneHot>
+__global__ __launch_bounds__(256) void k_adam_rows(
+    const float4* __restrict__ common, const int* __restrict__ slot,
+    const int64_t* __restrict__ unique_ids, float4* __restrict__ cw, float4* __restrict__ cs,
+    HostRows h, int C, int boff, AdamArgs k, int d4, const Ctr* ctr,
+    const int2* __restrict__ cold_pay, const float4* __restrict__ grad,
+    const double* __restrict__ bp, const int* __restrict__ bp_vid, int nslots, int nedge) {
+  AdamOp op;
+  op.k = k;
+  update_kernel<AdamOp, kOneHot>(op, common, slot, unique_ids, cw, cs, h, C, boff, d4, ctr, cold_pay,
+                                 grad, bp, bp_vid, nslots, nedge);
 }
 
 // ---------------------------------------------------------------------------------------------
