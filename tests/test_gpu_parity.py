@@ -142,9 +142,10 @@ def test_long_groups_cross_many_spans():
     p.finish(); p.close()
 
 
-@pytest.mark.parametrize("D,C", [(4, 400), (16, 0), (80, 400), (256, 7)])
-def test_groups_cut_by_block_edges_are_updated_once(D, C):
-    # Adagrad path: the optimizer kernel itself adds up the partial sums of groups that the gradient
+@pytest.mark.parametrize("D,C,optimizer", [(4, 400, "adagrad"), (16, 0, "adagrad"), (80, 400, "adagrad"),
+                                           (256, 7, "adagrad"), (16, 400, "adam"), (32, 0, "adam")])
+def test_groups_cut_by_block_edges_are_updated_once(D, C, optimizer):
+    # Adagrad and Adam path: the optimizer kernel itself adds up the partial sums of groups that the gradient
     # stream's blocks cut (a lane group per short run, the whole block for a run of many slots) and
     # updates those rows; here one id has a run of hundreds of slots, a dozen ids have runs of a few
     # slots, the rest close inside a block.  Row widths of one lane and of a whole wavefront, a width
@@ -154,7 +155,7 @@ def test_groups_cut_by_block_edges_are_updated_once(D, C):
     r = rng.random(n)
     mid = 20 + (rng.integers(0, 12, n))
     ids = np.where(r < 0.45, 3, np.where(r < 0.85, mid, rng.integers(0, V, n)))
-    p = Pair(V, D, C=C, max_ids=n)
+    p = Pair(V, D, C=C, max_ids=n, optimizer=optimizer, init_acc=0.0 if optimizer == "adam" else 0.1)
     p.step(ids, si.grads(n, D, 70 + D, 0).numpy())
     p.step(ids[::-1].copy(), si.grads(n, D, 70 + D, 1).numpy())
     p.finish(); p.close()
