@@ -123,15 +123,15 @@ __global__ __launch_bounds__(256) void k_flush(const int64_t* __restrict__ slot_
 // ---------------------------------------------------------------------------------------------
 // Forward gather (Algorithm 1 lines 9 and 11 fused): out[b] = cache row of the slot of position b.
 // pos_slot[p] = slot[inverse[p]] is written by the prepare step, so the gather is one level of
-// indirection.  A block stages the slots of its 256 bags in LDS with one coalesced load, then
-// every thread has eight 16-byte row chunks in flight before the first store; a wavefront's
-// stores are 1 KiB contiguous and non-temporal: the output is consumed by the model, and keeping
-// it out of L2 keeps the hot rows in (plain stores measured 50 % slower).
+// indirection.  A block stages the slots of its bags in LDS with one coalesced load, then every
+// thread has its 16-byte row chunks (up to eight) in flight before the first store; a
+// wavefront's stores are 1 KiB contiguous and non-temporal: the output is consumed by the model,
+// and keeping it out of L2 keeps the hot rows in (plain stores measured 50 % slower).
 // What bounds it on MI355X: with the rows resident in the memory-side cache the kernel runs at
-// the write rate of HBM (58 us for 327 MB); in the training loop the other kernels of the step
+// the write rate of HBM (52-58 us for 327 MB); in the training loop the other kernels of the step
 // have evicted them, the ~59 MB of row reads mix into the write stream and the same kernel takes
-// 79-85 us.  Variants without LDS staging, with 2/4/16 chunks per thread or persistent blocks
-// measured within +-5 % of this one under those conditions.
+// 79-85 us, which is what k_warm_rows below is for.  Variants without LDS staging or with
+// persistent blocks measured within +-5 % of this one under those conditions.
 // ---------------------------------------------------------------------------------------------
 constexpr int kLookupBags = 256;      // most rows a block of the one-hot gather takes
 // Rows per block of the one-hot gather: 512 16-byte chunks, two per thread.  With the rows
